@@ -1,0 +1,175 @@
+"""Pins for the method-level pieces of the oracle: Lemma 3.1 (exponent add == multiply by
+2^n), Algorithm 1's chunk invariance, Eq. (4) == Eq. (2), the r_i range, the FP32 overflow
+remark, and the FLOP / byte accounting against Tables 2 and 5."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import amla_oracle as orc
+from paper_2509_25224_amd import accounting as acc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ----------------------------------------------------------------------------- Lemma 3.1
+def test_worked_example_bits():
+    (pattern, fval, e), = _rows("example_3_1.txt")
+    i = int(pattern, 2)
+    assert i == int(e) * 2 ** 23
+    assert float(orc.as_fp32(np.int32(i))) == float(fval)
+    assert int(orc.as_int32(np.float32(fval))) == i
+    # adding 1 * 2^23 doubles it
+    assert float(orc.exponent_add(np.float32(fval), 1)) == 1.0
+
+
+def test_lemma_bit_exact_against_ldexp_all_exponents():
+    rng = np.random.default_rng(1)
+    mant = np.concatenate([[0, 1, 2 ** 22, 2 ** 23 - 1], rng.integers(0, 2 ** 23, 60)]).astype(np.int64)
+    for E in range(1, 255):
+        for sign in (0, 1):
+            I = (sign << 31) | (E << 23) | mant
+            F = orc.as_fp32(np.where(I >= 2 ** 31, I - 2 ** 32, I).astype(np.int32))
+            n = np.arange(-E + 1, 255 - E, dtype=np.int64)          # -E < n < 255 - E
+            got = orc.exponent_add(F[:, None], n[None, :])
+            want = np.ldexp(F[:, None].astype(np.float64), n[None, :]).astype(np.float32)
+            assert np.array_equal(got.view(np.int32), want.view(np.int32))
+
+
+def test_lemma_random_normal_floats():
+    rng = np.random.default_rng(2)
+    I = rng.integers(-2 ** 31, 2 ** 31, 200000, dtype=np.int64).astype(np.int32)
+    E = (I.astype(np.int64) >> 23) & 0xFF
+    keep = (E > 0) & (E < 255)
+    I, E = I[keep], E[keep]
+    n = np.array([rng.integers(-e + 1, 255 - e) for e in E])
+    F = orc.as_fp32(I)
+    got = orc.exponent_add(F, n)
+    want = (F.astype(np.float64) * np.exp2(n.astype(np.float64))).astype(np.float32)
+    assert np.array_equal(got.view(np.int32), want.view(np.int32))
+
+
+def test_unguarded_add_wraps_outside_the_range():
+    """Why a guard is needed: 0.0 with n = -1 becomes a huge negative number."""
+    bad = float(orc.exponent_add(np.float32(0.0), -1))
+    assert bad < -1e30
+
+
+def test_guarded_add_range_behaviour():
+    rng = np.random.default_rng(3)
+    I = rng.integers(-2 ** 31, 2 ** 31, 100000, dtype=np.int64).astype(np.int32)
+    E = (I.astype(np.int64) >> 23) & 0xFF
+    I = I[E < 255]
+    F = orc.as_fp32(I)
+    specials = np.array([0.0, -0.0, 1e-45, -1e-45, 1.1754944e-38, -1.1754944e-38, 2.0 ** -100], np.float32)
+    F = np.concatenate([F, specials])
+    for d in (0, -1, -2, -7, -30):
+        got = orc.exponent_add_guarded(F, d)
+        exact = F.astype(np.float64) * 2.0 ** d
+        normal = np.abs(exact) >= 2.0 ** -126
+        src_normal = np.abs(F.astype(np.float64)) >= 2.0 ** -126
+        ok = normal & src_normal
+        assert np.array_equal(got[ok].astype(np.float64), exact[ok])
+        rest = ~ok
+        assert np.all(np.abs(got[rest].astype(np.float64)) <= 2.0 ** -126)
+        assert np.all(np.signbit(got) == np.signbit(F))
+
+
+def test_exp_overflows_fp32_past_88():
+    with np.errstate(over="ignore"):
+        assert np.isfinite(np.exp(np.float32(88.0)))
+        assert np.isinf(np.exp(np.float32(89.0)))
+
+
+# ------------------------------------------------------------------ Algorithm 1 / Eq. (4)
+def _problem(seed, G=6, L=333, sigma=1.0):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((G, 576)) * sigma
+    K = rng.standard_normal((L, 576))
+    return Q, K, K[:, :512], 192 ** -0.5
+
+
+def _chunks(L, size, rng=None):
+    idx = [np.arange(lo, min(L, lo + size)) for lo in range(0, L, size)]
+    if rng is not None:
+        rng.shuffle(idx)
+    return idx
+
+
+@pytest.mark.parametrize("size", [1, 7, 64, 512, 333])
+@pytest.mark.parametrize("shuffle", [False, True])
+def test_algorithm1_chunk_size_and_order_invariance(size, shuffle):
+    Q, K, V, scale = _problem(4)
+    want, want_lse = orc.attention_rows(Q, K, scale)
+    rng = np.random.default_rng(5) if shuffle else None
+    O, m, l = orc.flash_attention(Q, K, V, scale, _chunks(len(K), size, rng))
+    assert np.abs(O - want).max() < 1e-12
+    assert np.abs(m + np.log(l) - want_lse).max() < 1e-12
+
+
+@pytest.mark.parametrize("sigma", [1.0, 4.0, 10.0])
+def test_amla_recurrence_equals_flash_attention(sigma):
+    Q, K, V, scale = _problem(6, sigma=sigma)
+    want, _ = orc.attention_rows(Q, K, scale)
+    O, r = orc.amla_recurrence(Q, K, V, scale, _chunks(len(K), 64))
+    assert np.abs(O - want).max() < 1e-12
+    assert r.min() >= 2 ** -0.5 - 1e-12 and r.max() <= 2 ** 0.5 + 1e-12
+
+
+def test_r_range_over_random_maxima():
+    m = np.random.default_rng(7).uniform(-200, 200, 100000)
+    n = np.rint(-m / math.log(2))
+    r = np.exp(-n * math.log(2) - m)
+    assert r.min() >= 2 ** -0.5 * (1 - 1e-12) and r.max() <= 2 ** 0.5 * (1 + 1e-12)
+
+
+def test_fp32_emulation_with_exponent_add_tracks_definition():
+    """Algorithm 2's loop in FP32 / BF16 P / INT32 add lands at the BF16-P error level."""
+    rng = np.random.default_rng(8)
+    def bf(x):
+        return orc._round_bf16(x.astype(np.float32))
+    for sigma in (1.0, 4.0):
+        Q = bf(rng.standard_normal((16, 576)) * sigma)
+        K = bf(rng.standard_normal((1000, 576)))
+        want, want_lse = orc.attention_rows(Q.astype(np.float64), K.astype(np.float64), 192 ** -0.5)
+        out, lse = orc.amla_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5)
+        assert np.abs(out - want).max() < 1e-2
+        assert np.abs(lse - want_lse).max() < 1e-3
+        assert orc.frobenius_error(out, want) < 4e-3
+
+
+# -------------------------------------------------------------------- accounting pins
+def test_table2_arithmetic_intensity():
+    for name, qh, kvh, sq, printed, kind in _rows("table2_arithmetic_intensity.txt"):
+        qh, kvh, sq, printed = int(qh), int(kvh), int(sq), float(printed)
+        S2 = 4096
+        if kind == "mla":
+            ai = acc.decode_flops(qh, sq, S2) / acc.kv_bytes_mla(S2)
+        else:
+            ai = acc.decode_flops(qh, sq, S2, 128, 128) / acc.kv_bytes_mha_gqa(kvh, S2, 128, 128)
+        assert abs(ai - printed) <= 0.5 + 0.005 * printed, (name, ai)
+
+
+def test_table5_durations_reproduce_printed_utilisation():
+    rows = [(int(a), int(b), float(c), float(d)) for a, b, c, d in _rows("table5_ascend_rows.txt")]
+    batch, heads = 96, 128
+    best = [r for r in rows if r[0] == 2 and r[1] == 16384][0]
+    tflops_best = acc.decode_flops(heads, 2, batch * 16384) / (best[2] * 1e-6) / 1e12
+    assert abs(tflops_best - 614) < 1.0                       # the abstract's 614 TFLOPS
+    peak = tflops_best / (best[3] / 100)
+    for sq, sk, dur, fu in rows:
+        tf = acc.decode_flops(heads, sq, batch * sk) / (dur * 1e-6) / 1e12
+        assert abs(tf / peak * 100 - fu) < 0.6, (sq, sk, tf / peak * 100, fu)
+
+
+def test_frobenius_error_metric():
+    A = np.array([[3.0, 0.0], [0.0, 4.0]])
+    B = np.zeros((2, 2))
+    assert orc.frobenius_error(B, A) == pytest.approx(1.0, abs=1e-9)
+    assert orc.frobenius_error(A, A) == 0.0
