@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the absorbed-MLA decode hot path on one MI355X.
+
+A step is one pass of the whole path (paged KV gather, QK^T, online softmax, rescale, PV,
+epilogue, and the split-KV combine when the shape needs it) over one synthetic batch that
+is already resident in HBM.  The default workload is the 128-head, s_q = 2 decode batch the
+headline metric is quoted on.  One JSON line is printed:
+
+  value      whole-job TFLOP/s, FLOPs = 2 * H * s_q * sum(kv_len) * (576 + 512)  (Section 2.4)
+  roofline   the decode kernel against the bf16 dense MFMA peak (2516.6 TFLOP/s)
+  cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample
+  rescale    ADD (exponent add) and MUL (FP32 multiply) variants timed side by side
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "MLA decode TFLOPS + % of MI355X bf16 MFMA peak (H=128, s_q=2)"
+MFMA_BF16_PEAK_TFLOPS = 2516.6          # 256 CU x 4096 FLOP/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
+    ap.add_argument("--variant", choices=["add", "mul"], default="add")
+    ap.add_argument("--splits", type=int, default=0, help="split-KV factor, 0 = library default")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ab", action="store_true", help="skip the ADD-vs-MUL side-by-side timing")
+    return ap.parse_args()
+
+
+def time_steps(torch, fn, steps, warmup):
+    """Returns (total_ms over exactly `steps` calls, per-step ms list) using events on the
+    stream the kernels are launched on (torch's current stream)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    marks[0].record()
+    for i in range(steps):
+        fn()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    total = marks[0].elapsed_time(marks[steps])
+    per = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    return total, per
+
+
+def cpu_baseline(case, flops_per_seq, budget_s=12.0):
+    """The oracle as it stands, one sequence at a time, until ~budget_s of CPU work."""
+    from oracle import amla_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    done, flops = 0, 0
+    t0 = time.perf_counter()
+    for b in range(case.batch):
+        orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale, seq_ids=[b])
+        done += 1
+        flops += flops_per_seq[b]
+        if time.perf_counter() - t0 >= budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {done} of {case.batch} sequences of the same workload, fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path shards by batch "
+              "with no exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2509_25224_amd import accounting as acc, amla, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    case = wl.make_config(args.config)
+    dev = torch.device("cuda:0")
+    q = torch.from_numpy(case.q_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    kv = torch.from_numpy(case.kv_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    tab = torch.from_numpy(case.block_table).to(dev)
+    lens = torch.from_numpy(case.seqlens).to(dev)
+    out = torch.empty((case.batch, case.s_q, case.heads, 512), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((case.batch, case.s_q, case.heads), dtype=torch.float32, device=dev)
+
+    desc = amla.make_desc(case.batch, case.s_q, case.heads, case.num_blocks, case.max_blocks_per_seq,
+                          num_splits=args.splits)
+    splits = amla.amla_effective_splits(desc)
+    ws_bytes = amla.amla_workspace_bytes(desc)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def step(variant):
+        amla.amla_decode(q, kv, tab, lens, case.softmax_scale, out, lse, variant=variant,
+                         num_splits=args.splits, workspace=ws)
+
+    main_variant = amla.AMLA_RESCALE_ADD if args.variant == "add" else amla.AMLA_RESCALE_MUL
+    torch.cuda.synchronize()
+    total_ms, per = time_steps(torch, lambda: step(main_variant), args.steps, args.warmup)
+    torch.cuda.synchronize()
+
+    flops = acc.decode_flops(case.heads, case.s_q, case.total_kv)
+    abytes = acc.algorithmic_bytes(case.heads, case.s_q, case.batch, case.total_kv)
+    ms_per_step = total_ms / args.steps
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    kern_ms = sum(per) / len(per)          # one decode launch per step (+ combine when split)
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {case.name}: batch {case.batch}, s_q {case.s_q}, "
+                               f"{case.heads} heads, sum kv_len {case.total_kv}, paged bf16 latent cache "
+                               f"(block 64, permuted table), d_qk 576 / d_v 512",
+                   "variant": args.variant, "kv_splits": splits, "seed": case.seed},
+        "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "amla_decode_kernel", "kernel_ms": kern_ms,
+                     "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": abytes,
+                     "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
+    }
+
+    if not args.no_ab:
+        ab = {}
+        for name, v in (("mul", amla.AMLA_RESCALE_MUL), ("add", amla.AMLA_RESCALE_ADD)) * 2:
+            t, _ = time_steps(torch, lambda: step(v), args.steps, 2)
+            ab.setdefault(name, []).append(t / args.steps)
+        add_ms, mul_ms = min(ab["add"]), min(ab["mul"])
+        result["rescale"] = {"add_ms": add_ms, "mul_ms": mul_ms, "add_over_mul_speedup": mul_ms / add_ms,
+                             "note": "interleaved runs, best of 2 per variant, same binary"}
+
+    if not args.no_cpu_baseline:
+        per_seq = [acc.decode_flops(case.heads, case.s_q, int(L)) for L in case.seqlens]
+        result["cpu_baseline"] = cpu_baseline(case, per_seq)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

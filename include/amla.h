@@ -1,0 +1,132 @@
+/*
+ * amla.h -- C ABI of the absorbed-MLA decode attention library for MI355X (gfx950).
+ *
+ * The operation (Section 2.1 Eq. (1), Section 2.2, Section 3.1 of the AMLA paper): for every
+ * query row (b, t, h) -- sequence b, query token t of s_q, head h of num_heads --
+ *
+ *     s_j   = softmax_scale * sum_{d<576} q[b,t,h,d] * K_b[j,d]          j = 0 .. kv_len[b]-1
+ *     out   = sum_j softmax(s)_j * K_b[j, 0:512]
+ *     lse   = ln sum_j exp(s_j)
+ *
+ * where K_b[j,:] is the 576-wide latent+RoPE row of cached token j of sequence b and the
+ * value row is its first 512 columns (one shared KV head for all query heads).  All s_q query
+ * tokens of a sequence attend to the whole cached prefix; there is no mask among them.
+ *
+ * The kernels run the FlashAttention recurrence (Algorithm 1) over 64-key cache blocks with
+ * the output accumulator held in MFMA accumulator registers.  Two rescale variants exist:
+ *   AMLA_RESCALE_MUL  O <- O * 2^(m_old - m_new)            FP32 multiply (Algorithm 1, Eq. (2))
+ *   AMLA_RESCALE_ADD  O <- AS_FP32(AS_INT32(O) + (n_new - n_old) * 2^23)
+ *                     with the running reference quantised to an integer power of two
+ *                     (Eq. (4), Lemma 3.1, Algorithm 2 lines 5-6 and 11-15), the INT32 add
+ *                     guarded so that an exponent that would drop to or below zero yields
+ *                     a signed zero instead of a wrapped bit pattern.
+ *
+ * Every pointer below is a DEVICE pointer unless it says host.  The library allocates
+ * nothing, keeps no state between calls, never synchronises the device, and enqueues all
+ * work on desc->stream.  The caller owns every buffer.
+ */
+#ifndef AMLA_H_
+#define AMLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  AMLA_OK = 0,
+  AMLA_ERR_NULL_ARG = -1,     /* a required pointer is NULL */
+  AMLA_ERR_UNSUPPORTED = -2,  /* shape or option outside what the kernels support */
+  AMLA_ERR_WORKSPACE = -3,    /* split-KV needs a workspace and it is missing or too small */
+  AMLA_ERR_LAUNCH = -4        /* the HIP runtime refused a launch */
+};
+
+enum { AMLA_RESCALE_MUL = 0, AMLA_RESCALE_ADD = 1 };
+
+/* desc->flags */
+enum {
+  AMLA_FLAG_NO_SKIP = 1 /* rescale the accumulator on every block even when the factor is 1
+                           (measurement aid: exposes the raw cost of the MUL / ADD rescale) */
+};
+
+typedef struct amla_desc {
+  int32_t batch;               /* B >= 1 */
+  int32_t s_q;                 /* query tokens per sequence, >= 1 */
+  int32_t num_heads;           /* H >= 1; rows of one sequence are (t, h) flattened: t*H + h */
+  int32_t d_qk;                /* must be 576 */
+  int32_t d_v;                 /* must be 512 */
+  int32_t block_size;          /* keys per cache block, must be 64 */
+  int32_t num_blocks;          /* physical blocks in kv_cache */
+  int32_t max_blocks_per_seq;  /* row stride of block_table */
+  int32_t variant;             /* AMLA_RESCALE_MUL or AMLA_RESCALE_ADD */
+  int32_t num_splits;          /* split-KV factor: each sequence's blocks are cut into this many
+                                  contiguous ranges processed by separate workgroups and merged
+                                  by a combine kernel.  0 = library chooses from the shape. */
+  int32_t flags;               /* AMLA_FLAG_* */
+  int32_t reserved;            /* must be 0 */
+  void* workspace;             /* device scratch for split-KV partials; may be NULL when the
+                                  effective split factor is 1 */
+  size_t workspace_bytes;      /* size of workspace */
+  void* stream;                /* hipStream_t; NULL = the default stream */
+} amla_desc;
+
+/*
+ * amla_decode -- decode attention over a paged latent KV cache (operation above; the loop is
+ * Algorithm 1 / Algorithm 2 of the paper per 64-key block, Section 3).
+ *
+ *   q            bf16 [batch, s_q, num_heads, 576], contiguous, read only
+ *   kv_cache     bf16 [num_blocks, 64, 576], contiguous, read only.  Every slot of every block
+ *                a sequence references must hold a finite value, including slots past the
+ *                sequence's end inside its last block (they are masked, but a NaN there would
+ *                still poison the value product).
+ *   block_table  int32 [batch, max_blocks_per_seq]; entry j of row b is the physical block of
+ *                keys 64j .. 64j+63 of sequence b.  Entries j >= ceil(kv_len[b]/64) are never
+ *                read.  Entries that are read must lie in [0, num_blocks); this is not checked
+ *                on the device.
+ *   seqlens      int32 [batch], 0 <= kv_len[b] <= 64 * max_blocks_per_seq
+ *   softmax_scale  multiplies q.k before the softmax (the paper's 1/sqrt(D_k) generalised)
+ *   out          bf16 [batch, s_q, num_heads, 512], fully overwritten; rows of a sequence with
+ *                kv_len 0 are written as 0
+ *   lse          f32 [batch, s_q, num_heads] natural-log sum of exponentials, -inf for kv_len 0;
+ *                may be NULL when not wanted
+ *   desc         host pointer; see amla_desc
+ *
+ * Returns AMLA_OK or a negative AMLA_ERR_*; never throws, never aborts.  On error nothing
+ * has been enqueued.
+ */
+int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
+                const int32_t* seqlens, float softmax_scale, void* out, float* lse,
+                const amla_desc* desc);
+
+/*
+ * amla_workspace_bytes -- bytes of desc->workspace that amla_decode needs for this desc
+ * (0 when the effective split factor is 1).  Only shape fields, num_splits and flags are
+ * read.  Returns 0 for a NULL or unsupported desc.
+ */
+size_t amla_workspace_bytes(const amla_desc* desc);
+
+/*
+ * amla_effective_splits -- the split-KV factor amla_decode will use for this desc
+ * (desc->num_splits if > 0, else the library's choice from batch, rows and
+ * max_blocks_per_seq).  Returns 0 for a NULL or unsupported desc.
+ */
+int amla_effective_splits(const amla_desc* desc);
+
+/*
+ * amla_exponent_add -- Lemma 3.1 as the kernels apply it: for each of the n device floats
+ * x[i], writes AS_FP32(AS_INT32(x[i]) + delta * 2^23) to y[i] when the biased exponent stays
+ * positive and a zero with x[i]'s sign otherwise.  Requires -126 <= delta <= 0.  Runs the
+ * same device helper the ADD variant uses on the accumulator registers (test entry point).
+ * `stream` is a hipStream_t or NULL.  x and y may alias.
+ */
+int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* stream);
+
+/* amla_status_string -- static, NUL-terminated description of a status code (host). */
+const char* amla_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMLA_H_ */

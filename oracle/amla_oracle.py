@@ -35,8 +35,9 @@ Readings taken where the paper is silent
 * round(): round-half-even.  Any integer within 1/2 of -m/ln2 keeps r in [1/sqrt2, sqrt2].
 * first block: no rescale (n_0 = -inf, "if i > 1" in Algorithm 2).
 * empty sequence (kv_len 0): out = 0, lse = -inf.
-* exponent add outside Lemma 3.1's range (E + n <= 0, including F = +-0): the result is
-  a zero with F's sign, never the wrapped bit pattern.
+* exponent add outside Lemma 3.1's range: E + n < 0 (including F = +-0 with n < 0) gives a
+  zero with F's sign, E + n == 0 gives the mantissa bits alone (magnitude < 2^-126); never
+  the wrapped bit pattern.
 """
 from __future__ import annotations
 
@@ -181,13 +182,15 @@ def exponent_add(F, n) -> np.ndarray:
 
 def exponent_add_guarded(F, n) -> np.ndarray:
     """Exponent add for n <= 0 that never wraps: where the biased exponent E of F has
-    E + n <= 0 the result is a zero carrying F's sign."""
+    E + n < 0 the result is a zero carrying F's sign.  E + n == 0 leaves the exponent
+    field empty and the mantissa bits in place: a value of magnitude < 2^-126 (the paper
+    neglects subnormals, Section 3.2; any |result| <= 2^-126 is as good as zero here)."""
     F = np.asarray(F, dtype=np.float32)
     n = np.asarray(n, dtype=np.int64)
     assert np.all(n <= 0)
     I = as_int32(F).astype(np.int64)
     E = (I >> 23) & 0xFF
-    ok = (E + n) > 0
+    ok = (E + n) >= 0
     raw = exponent_add(F, n)
     zero = as_fp32((as_int32(F) & np.int32(-2**31)))
     return np.where(ok, raw, zero)

@@ -1,0 +1,140 @@
+"""ctypes binding of the C-ABI library (`include/amla.h`): argument marshalling only.
+
+Every step of the decode path runs in the HIP kernels inside `libamla.so`; PyTorch is used
+for device memory and the stream handle.  There is no CPU or PyTorch fallback: importing
+this module raises if the library has not been built (run `__graft_entry__.build()`).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libamla.so")
+
+AMLA_OK = 0
+AMLA_ERR_NULL_ARG = -1
+AMLA_ERR_UNSUPPORTED = -2
+AMLA_ERR_WORKSPACE = -3
+AMLA_ERR_LAUNCH = -4
+AMLA_RESCALE_MUL = 0
+AMLA_RESCALE_ADD = 1
+AMLA_FLAG_NO_SKIP = 1
+
+EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
+           "amla_status_string")
+
+
+class AmlaDesc(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("s_q", ctypes.c_int32), ("num_heads", ctypes.c_int32),
+        ("d_qk", ctypes.c_int32), ("d_v", ctypes.c_int32), ("block_size", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+        ("variant", ctypes.c_int32), ("num_splits", ctypes.c_int32), ("flags", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with __graft_entry__.build() "
+                      "(hipcc --offload-arch=gfx950); there is no fallback path")
+
+lib = ctypes.CDLL(_LIB_PATH)
+lib.amla_decode.restype = ctypes.c_int
+lib.amla_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                            ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(AmlaDesc)]
+lib.amla_workspace_bytes.restype = ctypes.c_size_t
+lib.amla_workspace_bytes.argtypes = [ctypes.POINTER(AmlaDesc)]
+lib.amla_effective_splits.restype = ctypes.c_int
+lib.amla_effective_splits.argtypes = [ctypes.POINTER(AmlaDesc)]
+lib.amla_exponent_add.restype = ctypes.c_int
+lib.amla_exponent_add.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
+                                  ctypes.c_void_p]
+lib.amla_status_string.restype = ctypes.c_char_p
+lib.amla_status_string.argtypes = [ctypes.c_int]
+
+
+class AmlaError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"amla status {status}: {amla_status_string(status)}")
+
+
+def amla_status_string(status: int) -> str:
+    return lib.amla_status_string(int(status)).decode()
+
+
+def make_desc(batch, s_q, num_heads, num_blocks, max_blocks_per_seq, variant=AMLA_RESCALE_ADD,
+              num_splits=0, flags=0, d_qk=576, d_v=512, block_size=64) -> AmlaDesc:
+    d = AmlaDesc()
+    d.batch, d.s_q, d.num_heads = int(batch), int(s_q), int(num_heads)
+    d.d_qk, d.d_v, d.block_size = int(d_qk), int(d_v), int(block_size)
+    d.num_blocks, d.max_blocks_per_seq = int(num_blocks), int(max_blocks_per_seq)
+    d.variant, d.num_splits, d.flags, d.reserved = int(variant), int(num_splits), int(flags), 0
+    d.workspace, d.workspace_bytes, d.stream = None, 0, None
+    return d
+
+
+def amla_workspace_bytes(desc: AmlaDesc) -> int:
+    return int(lib.amla_workspace_bytes(ctypes.byref(desc)))
+
+
+def amla_effective_splits(desc: AmlaDesc) -> int:
+    return int(lib.amla_effective_splits(ctypes.byref(desc)))
+
+
+def amla_decode(q, kv_cache, block_table, seqlens, softmax_scale, out=None, lse=None, *,
+                variant=AMLA_RESCALE_ADD, num_splits=0, flags=0, workspace=None, want_lse=True):
+    """Decode attention on torch CUDA tensors.
+
+    q bf16 [B, s_q, H, 576]; kv_cache bf16 [num_blocks, 64, 576]; block_table int32
+    [B, max_blocks]; seqlens int32 [B].  Returns (out bf16 [B, s_q, H, 512], lse f32 [B, s_q, H]).
+    `out`, `lse` and `workspace` (a uint8 tensor) are allocated with torch when not given.
+    The call is enqueued on torch's current stream.
+    """
+    import torch
+
+    for t, dt in ((q, torch.bfloat16), (kv_cache, torch.bfloat16), (block_table, torch.int32),
+                  (seqlens, torch.int32)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == dt):
+            raise ValueError("inputs must be contiguous CUDA tensors of the documented dtypes")
+    B, T, H, D = q.shape
+    nblk, bs, D2 = kv_cache.shape
+    if block_table.shape[0] != B or seqlens.shape[0] != B:
+        raise ValueError("block_table / seqlens batch mismatch")
+    if D2 != D:
+        raise ValueError("q and kv_cache row widths differ")
+    desc = make_desc(B, T, H, nblk, block_table.shape[1], variant, num_splits, flags, D, 512, bs)
+    if out is None:
+        out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, T, H), dtype=torch.float32, device=q.device)
+    need = amla_workspace_bytes(desc)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        desc.workspace = workspace.data_ptr()
+        desc.workspace_bytes = workspace.numel() * workspace.element_size()
+    desc.stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.amla_decode(q.data_ptr(), kv_cache.data_ptr(), block_table.data_ptr(), seqlens.data_ptr(),
+                         float(softmax_scale), out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                         ctypes.byref(desc))
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return out, lse
+
+
+def amla_exponent_add(x, delta: int, y=None):
+    """y[i] = guarded exponent add of delta (<= 0) on float32 CUDA tensor x (Lemma 3.1)."""
+    import torch
+
+    if not (x.is_cuda and x.is_contiguous() and x.dtype == torch.float32):
+        raise ValueError("x must be a contiguous float32 CUDA tensor")
+    if y is None:
+        y = torch.empty_like(x)
+    st = lib.amla_exponent_add(x.data_ptr(), y.data_ptr(), x.numel(), int(delta),
+                               torch.cuda.current_stream(x.device).cuda_stream)
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return y

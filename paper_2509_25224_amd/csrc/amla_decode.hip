@@ -1,0 +1,488 @@
+// Absorbed-MLA decode attention for gfx950 (MI355X): kernels and the C-ABI entry points.
+//
+// One workgroup (4 waves, one per SIMD, up to 512 VGPRs each) owns 128 query rows of one
+// sequence and a contiguous range of that sequence's 64-key cache blocks.  Wave w owns
+// rows 32w .. 32w+31 and keeps, for those rows, the whole Q fragment (144 VGPRs) and the
+// whole 32 x 512 FP32 output accumulator (256 registers) resident for the entire loop, so
+// the accumulator never leaves the register file (the data movement that the paper's
+// Section 3.1 identifies as the bottleneck of the [V2] stage does not exist here).
+//
+// Per block (Algorithm 1 / Algorithm 2, one iteration of the loop):
+//   [C1]  S^T = K Q^T   : v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q registers.
+//         Computing the transpose puts query row (lane % 32) in every register of a lane,
+//         so row max / row sum are in-lane reductions plus one exchange with lane ^ 32.
+//   [V1]  online softmax in base 2; P rounded to bf16 straight into the B-operand layout of
+//         the second product (no cross-lane movement).
+//   [V2]  rescale of the accumulator registers: FP32 multiply (MUL variant) or guarded INT32
+//         add on the exponent field (ADD variant, Lemma 3.1), skipped when no row of the
+//         wave changed its reference.
+//   [C2]  O^T += V^T P^T : A = V^T from the same LDS tile through the transposing LDS read
+//         (ds_read_b64_tr_b16), B = P registers.
+// The KV block is brought HBM -> LDS by direct-to-LDS loads (global_load_lds_dwordx4), double
+// buffered: block j+1 streams in while block j is consumed.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "amla.h"
+
+namespace {
+
+constexpr int kDqk = 576;
+constexpr int kDv = 512;
+constexpr int kBlock = 64;               // keys per cache block
+constexpr int kRowBytes = kDqk * 2;      // 1152 bytes of bf16 per cached row
+constexpr int kLdsRow = kRowBytes + 16;  // padded LDS row: 73 chunks of 16 B (odd -> no bank conflicts)
+constexpr int kChunksPerRow = kLdsRow / 16;           // 73
+constexpr int kTileBytes = kBlock * kLdsRow;          // 74752 = 73 * 1024
+constexpr int kTileLoads = kTileBytes / 1024;         // 73 wave-wide 1 KiB direct-to-LDS loads
+constexpr int kRowsPerWg = 128;
+constexpr int kThreads = 256;
+constexpr int kLdsBytes = 2 * kTileBytes;             // double buffer, 149504 B of the 160 KiB
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+#define GLB_PTR(T) __attribute__((address_space(1))) T*
+
+struct DecodeParams {
+  const uint16_t* q;        // [B, G, 576] bf16 bits (G = s_q * H rows per sequence)
+  const uint16_t* kv;       // [num_blocks, 64, 576]
+  const int32_t* table;     // [B, max_blocks]
+  const int32_t* seqlens;   // [B]
+  uint16_t* out;            // [B, G, 512] bf16 bits
+  float* lse;               // [B, G] or null
+  float* part_o;            // [n_splits, B, G, 512] f32 (n_splits > 1)
+  float* part_lse;          // [n_splits, B, G]
+  float scale_log2e;        // softmax_scale * log2(e)
+  int32_t batch;
+  int32_t rows;             // G
+  int32_t n_tiles;          // ceil(G / 128)
+  int32_t n_splits;
+  int32_t max_blocks;
+  int32_t n_streams;        // batch * n_splits
+  int32_t flags;
+};
+
+// Lemma 3.1 with a guard: x * 2^delta as an integer add of n23 = delta << 23 (delta <= 0) on the
+// bit pattern.  The saturating add pins a negative float whose exponent would go below zero at
+// 0x80000000 (-0.0); the max with the sign bit turns a wrapped positive float into +0.0.
+__device__ __forceinline__ float exponent_add(float x, int n23) {
+  const int i = __float_as_int(x);
+  int r = __builtin_elementwise_add_sat(i, n23);
+  r = max(r, i & (int)0x80000000);
+  return __int_as_float(r);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);   // round to nearest even
+  return __builtin_bit_cast(unsigned, b);
+}
+
+// Issue this wave's share of the direct-to-LDS loads of one 64 x 576 bf16 block.
+// LDS destination of load i is the 1 KiB range [i * 1024, (i + 1) * 1024) of the tile buffer,
+// lane l landing at + 16 l; chunk c = 64 i + l of the padded tile is row c / 73, column chunk
+// c % 73, the 73rd chunk of a row being padding (it receives 16 harmless bytes).
+__device__ __forceinline__ void issue_tile_loads(const uint8_t* block_base, LDS_PTR(uint8_t) buf,
+                                                 int wave, int lane) {
+  // keep the per-lane offsets out of loop-invariant hoisting: 19 of them per lane would
+  // cost more registers than recomputing them costs VALU slots
+  asm volatile("" : "+v"(lane));
+#pragma unroll
+  for (int k = 0; k < (kTileLoads + 3) / 4; ++k) {
+    const int i = wave + 4 * k;
+    if (i < kTileLoads) {
+      const int c = i * 64 + lane;
+      const int row = (int)(((unsigned)c * 57457u) >> 22);      // c / 73 for c < 4672
+      const int cc = c - row * kChunksPerRow;
+      const int off = (cc < kChunksPerRow - 1) ? (c - row) * 16 : 0;
+      __builtin_amdgcn_global_load_lds((const GLB_PTR(void))(block_base + off),
+                                       (LDS_PTR(void))(buf + i * 1024), 16, 0, 0);
+    }
+  }
+}
+
+template <int VARIANT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void amla_decode_kernel(const DecodeParams p) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
+  LDS_PTR(uint8_t) smem = (LDS_PTR(uint8_t))smem_raw;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31;
+  const int h = lane >> 5;
+
+  // Workgroup -> (kv stream, row tile).  Consecutive workgroup ids go round-robin over the 8
+  // XCDs; the row tiles of one (sequence, split) get ids that differ by 8 so that they land on
+  // the same XCD next to each other and share the KV blocks in that XCD's L2.
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int stream = (slot / p.n_tiles) * 8 + xcd;
+  const int tile = slot % p.n_tiles;
+  if (stream >= p.n_streams) return;
+  const int b = stream / p.n_splits;
+  const int split = stream - b * p.n_splits;
+
+  const int kv_len = p.seqlens[b];
+  const int nb = (kv_len + kBlock - 1) / kBlock;
+  const int j0 = (int)(((long long)split * nb) / p.n_splits);
+  const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
+
+  const int row = tile * kRowsPerWg + wave * 32 + l32;       // row within the sequence
+  const bool row_ok = row < p.rows;
+  const size_t grow = (size_t)b * p.rows + (row_ok ? row : 0);
+
+  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].
+  bf16x8 qf[kDqk / 16];
+  {
+    const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
+#pragma unroll
+    for (int ks = 0; ks < kDqk / 16; ++ks) {
+      // rows past the end of the sequence's row range read row 0 (valid memory); their
+      // results are never stored
+      qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
+    }
+  }
+
+  f32x16 acc[kDv / 32];
+#pragma unroll
+  for (int dt = 0; dt < kDv / 32; ++dt) acc[dt] = f32x16{0};
+
+  float m_run = -INFINITY;   // running row max of t = s * scale * log2 e
+  float ref = 0.f;           // reference subtracted in the exponent: m_run (MUL) or rint(m_run) (ADD)
+  float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse)
+  float l_b16 = 0.f;         // sum of the bf16-rounded weights (normalises the output)
+
+  const int32_t* tab = p.table + (size_t)b * p.max_blocks;
+  const uint8_t* kvb = reinterpret_cast<const uint8_t*>(p.kv);
+  const size_t blk_bytes = (size_t)kBlock * kRowBytes;
+
+  if (j0 < j1) {
+    const int phys = __builtin_amdgcn_readfirstlane(tab[j0]);
+    issue_tile_loads(kvb + (size_t)phys * blk_bytes, smem, wave, lane);
+  }
+
+  // per-lane LDS offsets of the operand reads
+  const int k_off = l32 * kLdsRow + h * 16;                       // K rows, A operand of [C1]
+  const int g16 = lane >> 4, i16 = lane & 15;
+  const int v_off = (4 * (g16 >> 1) + (i16 >> 2)) * kLdsRow + (16 * (g16 & 1) + 4 * (i16 & 3)) * 2;
+
+  for (int j = j0; j < j1; ++j) {
+    LDS_PTR(uint8_t) buf = smem + ((j - j0) & 1) * kTileBytes;
+    // Block j has landed for this wave; the barrier makes that true for all waves and also
+    // guarantees everyone is done reading the other buffer, which is refilled next.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (j + 1 < j1) {
+      const int phys = __builtin_amdgcn_readfirstlane(tab[j + 1]);
+      issue_tile_loads(kvb + (size_t)phys * blk_bytes, smem + ((j + 1 - j0) & 1) * kTileBytes, wave, lane);
+    }
+
+    // ---- [C1] S^T[64 keys x 32 rows] ----
+    f32x16 s[2];
+    s[0] = f32x16{0};
+    s[1] = f32x16{0};
+#pragma unroll
+    for (int ks = 0; ks < kDqk / 16; ++ks) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const bf16x8 a = *(LDS_PTR(bf16x8))(buf + k_off + kt * 32 * kLdsRow + ks * 32);
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kt], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- [V1] online softmax ----
+    const int rem = kv_len - j * kBlock;           // valid keys in this block (>= 1)
+    if (rem < kBlock) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = 32 * kt + 4 * h + 8 * (r >> 2) + (r & 3);
+          if (key >= rem) s[kt][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx * p.scale_log2e);
+
+    const bool first = (j == j0);
+    float ref_new;
+    float alpha = 1.f;   // MUL: factor on the old accumulator
+    int n23 = 0;         // ADD: (n_i - n_{i-1}) << 23, <= 0
+    if (VARIANT == AMLA_RESCALE_MUL) {
+      ref_new = m_new;
+      if (!first) alpha = fast_exp2(ref - ref_new);
+    } else {
+      ref_new = __builtin_rintf(m_new);
+      if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
+    }
+    m_run = m_new;
+    ref = ref_new;
+
+    float psum = 0.f;
+    unsigned pk[16];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float p0 = fast_exp2(__builtin_fmaf(s[kt][r], p.scale_log2e, -ref_new));
+        const float p1 = fast_exp2(__builtin_fmaf(s[kt][r + 1], p.scale_log2e, -ref_new));
+        psum += p0 + p1;
+        pk[kt * 8 + (r >> 1)] = pack_bf16(p0, p1);
+      }
+    float bsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      bsum += __uint_as_float(pk[i] << 16) + __uint_as_float(pk[i] & 0xffff0000u);
+    psum += __shfl_xor(psum, 32);
+    bsum += __shfl_xor(bsum, 32);
+
+    // ---- [V2] rescale the accumulator registers ----
+    const bool force = (p.flags & AMLA_FLAG_NO_SKIP) && !first;
+    if (VARIANT == AMLA_RESCALE_MUL) {
+      l_f32 = l_f32 * alpha + psum;
+      l_b16 = l_b16 * alpha + bsum;
+      if (force || __builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+        for (int dt = 0; dt < kDv / 32; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+      }
+    } else {
+      l_f32 = exponent_add(l_f32, n23) + psum;
+      l_b16 = exponent_add(l_b16, n23) + bsum;
+      if (force || __builtin_amdgcn_ballot_w64(n23 != 0) != 0) {
+#pragma unroll
+        for (int dt = 0; dt < kDv / 32; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[dt][r] = exponent_add(acc[dt][r], n23);
+      }
+    }
+
+    // ---- [C2] O^T[512 x 32 rows] += V^T P^T ----
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      const i32x4 pb = {(int)pk[4 * st], (int)pk[4 * st + 1], (int)pk[4 * st + 2], (int)pk[4 * st + 3]};
+      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
+#pragma unroll
+      for (int dt = 0; dt < kDv / 32; ++dt) {
+        LDS_PTR(uint8_t) va = buf + v_off + st * 16 * kLdsRow + dt * 64;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))va);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(va + 8 * kLdsRow));
+        const i32x2 lo2 = __builtin_bit_cast(i32x2, lo), hi2 = __builtin_bit_cast(i32x2, hi);
+        const i32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pfrag, acc[dt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
+  // ---- epilogue (Algorithm 1 line 9 / Algorithm 2 line 20) ----
+  const float inv = l_b16 > 0.f ? 1.f / l_b16 : 0.f;
+  const float lse = l_f32 > 0.f ? (ref + fast_log2(l_f32)) * 0.6931471805599453f : -INFINITY;
+  if (!row_ok) return;
+  if (p.n_splits == 1) {
+    uint16_t* orow = p.out + grow * kDv;
+#pragma unroll
+    for (int dt = 0; dt < kDv / 32; ++dt)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const unsigned w0 = pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv);
+        const unsigned w1 = pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv);
+        const i32x2 w = {(int)w0, (int)w1};
+        *reinterpret_cast<i32x2*>(orow + dt * 32 + 4 * h + 8 * rg) = w;
+      }
+    if (p.lse != nullptr && h == 0) p.lse[grow] = lse;
+  } else {
+    const size_t prow = (size_t)split * p.batch * p.rows + grow;
+    float* orow = p.part_o + prow * kDv;
+#pragma unroll
+    for (int dt = 0; dt < kDv / 32; ++dt)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const f32x4 w = {acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv, acc[dt][4 * rg + 2] * inv,
+                         acc[dt][4 * rg + 3] * inv};
+        *reinterpret_cast<f32x4*>(orow + dt * 32 + 4 * h + 8 * rg) = w;
+      }
+    if (h == 0) p.part_lse[prow] = lse;
+  }
+}
+
+// Merge the per-split partial results of one row: weights exp(lse_s - lse) (the merge rule of
+// Algorithm 1's update applied across splits).  One 128-thread workgroup per row, 4 columns
+// per thread.
+__global__ __launch_bounds__(128) void amla_combine_kernel(const float* __restrict__ part_o,
+                                                          const float* __restrict__ part_lse,
+                                                          uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                          int n_rows, int n_splits) {
+  const int row = blockIdx.x;
+  if (row >= n_rows) return;
+  float mx = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_lse[(size_t)s * n_rows + row]);
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  float tot = 0.f;
+  if (mx > -INFINITY) {
+    for (int s = 0; s < n_splits; ++s) {
+      const float ls = part_lse[(size_t)s * n_rows + row];
+      if (ls == -INFINITY) continue;
+      const float w = __expf(ls - mx);
+      tot += w;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(part_o + ((size_t)s * n_rows + row) * kDv + 4 * threadIdx.x);
+      o += v * w;
+    }
+  }
+  const float inv = tot > 0.f ? 1.f / tot : 0.f;
+  const i32x2 w = {(int)pack_bf16(o[0] * inv, o[1] * inv), (int)pack_bf16(o[2] * inv, o[3] * inv)};
+  *reinterpret_cast<i32x2*>(out + (size_t)row * kDv + 4 * threadIdx.x) = w;
+  if (lse != nullptr && threadIdx.x == 0) lse[row] = tot > 0.f ? mx + __logf(tot) : -INFINITY;
+}
+
+__global__ void amla_exponent_add_kernel(const float* x, float* y, size_t n, int n23) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) y[i] = exponent_add(x[i], n23);
+}
+
+bool desc_supported(const amla_desc* d) {
+  if (d == nullptr) return false;
+  if (d->d_qk != kDqk || d->d_v != kDv || d->block_size != kBlock) return false;
+  if (d->batch < 1 || d->s_q < 1 || d->num_heads < 1 || d->num_blocks < 1 || d->max_blocks_per_seq < 1) return false;
+  if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD) return false;
+  if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
+  if ((d->flags & ~AMLA_FLAG_NO_SKIP) != 0) return false;
+  const long long rows = (long long)d->s_q * d->num_heads;
+  if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
+  return true;
+}
+
+int choose_splits(const amla_desc* d) {
+  if (d->num_splits > 0) return d->num_splits;
+  const long long rows = (long long)d->s_q * d->num_heads;
+  const long long tiles = (rows + kRowsPerWg - 1) / kRowsPerWg;
+  const long long base = (long long)d->batch * tiles;       // workgroups without splitting
+  const long long cus = 256;
+  if (base >= cus) return 1;
+  long long ns = (cus + base - 1) / base;
+  const long long cap = d->max_blocks_per_seq / 4 > 0 ? d->max_blocks_per_seq / 4 : 1;   // >= 4 blocks per split
+  if (ns > cap) ns = cap;
+  if (ns > 64) ns = 64;
+  return (int)(ns < 1 ? 1 : ns);
+}
+
+}  // namespace
+
+extern "C" {
+
+int amla_effective_splits(const amla_desc* desc) {
+  if (!desc_supported(desc)) return 0;
+  return choose_splits(desc);
+}
+
+size_t amla_workspace_bytes(const amla_desc* desc) {
+  if (!desc_supported(desc)) return 0;
+  const int ns = choose_splits(desc);
+  if (ns <= 1) return 0;
+  const size_t rows = (size_t)desc->batch * desc->s_q * desc->num_heads;
+  return (size_t)ns * rows * (kDv + 1) * sizeof(float);
+}
+
+int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* seqlens,
+                float softmax_scale, void* out, float* lse, const amla_desc* desc) {
+  if (q == nullptr || kv_cache == nullptr || block_table == nullptr || seqlens == nullptr || out == nullptr ||
+      desc == nullptr)
+    return AMLA_ERR_NULL_ARG;
+  if (!desc_supported(desc)) return AMLA_ERR_UNSUPPORTED;
+  if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale)) return AMLA_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(kv_cache) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return AMLA_ERR_UNSUPPORTED;
+
+  const int ns = choose_splits(desc);
+  const size_t need = amla_workspace_bytes(desc);
+  if (ns > 1) {
+    if (desc->workspace == nullptr || desc->workspace_bytes < need) return AMLA_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(desc->workspace) & 15) return AMLA_ERR_WORKSPACE;
+  }
+
+  DecodeParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.kv = static_cast<const uint16_t*>(kv_cache);
+  p.table = block_table;
+  p.seqlens = seqlens;
+  p.out = static_cast<uint16_t*>(out);
+  p.lse = lse;
+  p.batch = desc->batch;
+  p.rows = desc->s_q * desc->num_heads;
+  p.n_tiles = (p.rows + kRowsPerWg - 1) / kRowsPerWg;
+  p.n_splits = ns;
+  p.max_blocks = desc->max_blocks_per_seq;
+  p.n_streams = desc->batch * ns;
+  p.flags = desc->flags;
+  p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  const size_t n_rows = (size_t)desc->batch * p.rows;
+  p.part_o = ns > 1 ? static_cast<float*>(desc->workspace) : nullptr;
+  p.part_lse = ns > 1 ? p.part_o + (size_t)ns * n_rows * kDv : nullptr;
+
+  hipStream_t stream = static_cast<hipStream_t>(desc->stream);
+  const long long streams_pad = ((long long)p.n_streams + 7) / 8 * 8;
+  const long long grid = streams_pad * p.n_tiles;
+  if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
+
+  auto kern = desc->variant == AMLA_RESCALE_ADD ? amla_decode_kernel<AMLA_RESCALE_ADD>
+                                                : amla_decode_kernel<AMLA_RESCALE_MUL>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kLdsBytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return AMLA_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, stream, p);
+  if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  if (ns > 1) {
+    hipLaunchKernelGGL(amla_combine_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
+                       p.out, p.lse, (int)n_rows, ns);
+    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  }
+  return AMLA_OK;
+}
+
+int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* stream) {
+  if (x == nullptr || y == nullptr) return AMLA_ERR_NULL_ARG;
+  if (delta > 0 || delta < -126) return AMLA_ERR_UNSUPPORTED;
+  if (n == 0) return AMLA_OK;
+  const size_t blocks = (n + 255) / 256;
+  if (blocks > 0x7fffffffull) return AMLA_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(amla_exponent_add_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), x, y, n, delta * (1 << 23));
+  return hipGetLastError() == hipSuccess ? AMLA_OK : AMLA_ERR_LAUNCH;
+}
+
+const char* amla_status_string(int status) {
+  switch (status) {
+    case AMLA_OK: return "ok";
+    case AMLA_ERR_NULL_ARG: return "a required pointer is NULL";
+    case AMLA_ERR_UNSUPPORTED: return "unsupported shape, option, scale or pointer alignment";
+    case AMLA_ERR_WORKSPACE: return "split-KV workspace missing, misaligned or too small";
+    case AMLA_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

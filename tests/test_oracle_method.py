@@ -173,3 +173,14 @@ def test_frobenius_error_metric():
     B = np.zeros((2, 2))
     assert orc.frobenius_error(B, A) == pytest.approx(1.0, abs=1e-9)
     assert orc.frobenius_error(A, A) == 0.0
+
+
+def test_guarded_add_boundary_cases():
+    # E + n < 0 -> signed zero; E + n == 0 -> mantissa bits only; E + n > 0 -> exact product
+    one_and_half_min = np.float32(1.5 * 2.0 ** -126)            # E = 1, M = 2^22
+    got = orc.exponent_add_guarded(np.array([one_and_half_min, -one_and_half_min], np.float32), -1)
+    assert got.view(np.uint32).tolist() == [0x00400000, 0x80400000]
+    got = orc.exponent_add_guarded(np.array([one_and_half_min, -one_and_half_min, 0.0, -0.0], np.float32), -2)
+    assert got.view(np.uint32).tolist() == [0x00000000, 0x80000000, 0x00000000, 0x80000000]
+    got = orc.exponent_add_guarded(np.array([3.0, -3.0], np.float32), -30)
+    assert got.tolist() == [3.0 * 2.0 ** -30, -3.0 * 2.0 ** -30]
