@@ -22,8 +22,9 @@
  *                     a signed zero instead of a wrapped bit pattern.
  *
  * Every pointer below is a DEVICE pointer unless it says host.  The library allocates
- * nothing, keeps no state between calls, never synchronises the device, and enqueues all
- * work on desc->stream.  The caller owns every buffer.
+ * no device memory, never synchronises the device, and enqueues all work on desc->stream.  The
+ * caller owns every buffer.  The only state kept between calls is the code object of the
+ * hand-scheduled kernels, loaded once per device on the first call that asks for them.
  */
 #ifndef AMLA_H_
 #define AMLA_H_
@@ -47,8 +48,19 @@ enum { AMLA_RESCALE_MUL = 0, AMLA_RESCALE_ADD = 1 };
 
 /* desc->flags */
 enum {
-  AMLA_FLAG_NO_SKIP = 1 /* rescale the accumulator on every block even when the factor is 1
-                           (measurement aid: exposes the raw cost of the MUL / ADD rescale) */
+  AMLA_FLAG_NO_SKIP = 1,        /* rescale the accumulator on every block even when the factor is 1
+                                   (measurement aid: exposes the raw cost of the MUL / ADD rescale) */
+  AMLA_FLAG_LAZY_RESCALE = 2,   /* move the reference of the exponent only when the running row max
+                                   exceeds it by more than 2^8; in between the softmax weights may
+                                   grow up to 2^8 (same relative precision in bf16 and FP32), so the
+                                   accumulator rescale becomes a rare event.  Same result up to
+                                   rounding.  Only with AMLA_FLAG_ASM_KERNEL. */
+  AMLA_FLAG_ASM_KERNEL = 4      /* run the hand-scheduled assembly kernels (32-key steps, explicit
+                                   MFMA / VALU / LDS interleave) instead of the compiler-built HIP
+                                   kernel (64-key steps).  SWITCHED OFF: rejected with
+                                   AMLA_ERR_UNSUPPORTED unless the environment variable
+                                   AMLA_ENABLE_ASM_KERNELS is "1", because these kernels have not
+                                   yet passed on hardware. */
 };
 
 typedef struct amla_desc {
@@ -86,7 +98,8 @@ typedef struct amla_desc {
  *                read.  Entries that are read must lie in [0, num_blocks); this is not checked
  *                on the device.
  *   seqlens      int32 [batch], 0 <= kv_len[b] <= 64 * max_blocks_per_seq
- *   softmax_scale  multiplies q.k before the softmax (the paper's 1/sqrt(D_k) generalised)
+ *   softmax_scale  multiplies q.k before the softmax (the paper's 1/sqrt(D_k) generalised);
+ *                finite and > 0
  *   out          bf16 [batch, s_q, num_heads, 512], fully overwritten; rows of a sequence with
  *                kv_len 0 are written as 0
  *   lse          f32 [batch, s_q, num_heads] natural-log sum of exponentials, -inf for kv_len 0;

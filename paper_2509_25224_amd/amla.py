@@ -19,6 +19,8 @@ AMLA_ERR_LAUNCH = -4
 AMLA_RESCALE_MUL = 0
 AMLA_RESCALE_ADD = 1
 AMLA_FLAG_NO_SKIP = 1
+AMLA_FLAG_LAZY_RESCALE = 2
+AMLA_FLAG_ASM_KERNEL = 4
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
            "amla_status_string")

@@ -24,6 +24,9 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
 
 #include "amla.h"
 
@@ -362,13 +365,78 @@ __global__ void amla_exponent_add_kernel(const float* x, float* y, size_t n, int
   if (i < n) y[i] = exponent_add(x[i], n23);
 }
 
+// ---- hand-scheduled kernels: code object assembled from the generated gfx950 assembly --------
+const unsigned char kDecodeCodeObject[] = {
+#include "amla_decode_gfx950.hsaco.inc"
+};
+
+constexpr int kMaxDevices = 64;
+constexpr int kAsmKernels = 4;   // index = variant + 2 * lazy
+const char* const kAsmNames[kAsmKernels] = {"amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_mul_lazy",
+                                            "amla_decode_asm_add_lazy"};
+struct DeviceKernels {
+  bool tried = false;
+  bool ok = false;
+  hipModule_t module = nullptr;
+  hipFunction_t fn[kAsmKernels] = {};
+};
+DeviceKernels g_kernels[kMaxDevices];
+std::mutex g_kernels_mutex;
+
+// The code object is loaded once per device, on the first call made with that device current.
+const DeviceKernels* device_kernels() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_kernels_mutex);
+  DeviceKernels& k = g_kernels[dev];
+  if (!k.tried) {
+    k.tried = true;
+    bool ok = hipModuleLoadData(&k.module, kDecodeCodeObject) == hipSuccess;
+    for (int i = 0; ok && i < kAsmKernels; ++i) ok = hipModuleGetFunction(&k.fn[i], k.module, kAsmNames[i]) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    k.ok = ok;
+  }
+  return k.ok ? &k : nullptr;
+}
+
+// Kernel argument block of the assembly kernels (offsets are fixed in the generator).
+struct AsmArgs {
+  const void* q;
+  const void* kv;
+  const void* table;
+  const void* seqlens;
+  void* out;
+  float* lse;
+  float* part_o;
+  float* part_lse;
+  float scale_log2e;
+  int32_t batch;
+  int32_t rows;
+  int32_t n_splits;
+  int32_t max_blocks;
+  int32_t n_streams;
+  int32_t flags;
+  uint32_t split_magic;   // floor(2^32 / n_splits) + 1: x / n_splits == mulhi(x, magic) for x * n_splits < 2^32
+};
+static_assert(sizeof(AsmArgs) == 0x60, "kernel argument block layout");
+
+// The hand-scheduled kernels are switched off unless the process opts in: their first run on
+// the GPU faulted (a missing wait state before v_readfirstlane, since fixed in the generator)
+// and the fix has not been run on hardware yet.
+bool asm_kernels_enabled() {
+  const char* e = std::getenv("AMLA_ENABLE_ASM_KERNELS");
+  return e != nullptr && std::strcmp(e, "1") == 0;
+}
+
 bool desc_supported(const amla_desc* d) {
   if (d == nullptr) return false;
   if (d->d_qk != kDqk || d->d_v != kDv || d->block_size != kBlock) return false;
   if (d->batch < 1 || d->s_q < 1 || d->num_heads < 1 || d->num_blocks < 1 || d->max_blocks_per_seq < 1) return false;
   if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
-  if ((d->flags & ~AMLA_FLAG_NO_SKIP) != 0) return false;
+  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL)) != 0) return false;
+  if ((d->flags & AMLA_FLAG_LAZY_RESCALE) && !(d->flags & AMLA_FLAG_ASM_KERNEL)) return false;
+  if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
   return true;
@@ -411,7 +479,7 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
       desc == nullptr)
     return AMLA_ERR_NULL_ARG;
   if (!desc_supported(desc)) return AMLA_ERR_UNSUPPORTED;
-  if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale)) return AMLA_ERR_UNSUPPORTED;
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return AMLA_ERR_UNSUPPORTED;
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(kv_cache) | reinterpret_cast<uintptr_t>(out)) & 15)
     return AMLA_ERR_UNSUPPORTED;
 
@@ -443,18 +511,54 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
 
   hipStream_t stream = static_cast<hipStream_t>(desc->stream);
   const long long streams_pad = ((long long)p.n_streams + 7) / 8 * 8;
-  const long long grid = streams_pad * p.n_tiles;
-  if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
 
-  auto kern = desc->variant == AMLA_RESCALE_ADD ? amla_decode_kernel<AMLA_RESCALE_ADD>
-                                                : amla_decode_kernel<AMLA_RESCALE_MUL>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          kLdsBytes) != hipSuccess) {
-    (void)hipGetLastError();
-    return AMLA_ERR_LAUNCH;
+  if (!(desc->flags & AMLA_FLAG_ASM_KERNEL)) {
+    const long long grid = streams_pad * p.n_tiles;
+    if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
+    auto kern = desc->variant == AMLA_RESCALE_ADD ? amla_decode_kernel<AMLA_RESCALE_ADD>
+                                                  : amla_decode_kernel<AMLA_RESCALE_MUL>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kLdsBytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return AMLA_ERR_LAUNCH;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, stream, p);
+    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  } else {
+    // index arithmetic of the assembly kernels: mulhi-by-magic division and 32-bit row indices
+    const unsigned long long ns2 = (unsigned long long)ns * ns;
+    if (ns2 * (unsigned long long)desc->max_blocks_per_seq >= (1ull << 32) ||
+        ns2 * (unsigned long long)desc->batch >= (1ull << 32) ||
+        (unsigned long long)ns * n_rows >= (1ull << 31) || p.n_tiles * 8ll > 65535 || streams_pad / 8 > 65535)
+      return AMLA_ERR_UNSUPPORTED;
+    const DeviceKernels* dk = device_kernels();
+    if (dk == nullptr) return AMLA_ERR_LAUNCH;
+    AsmArgs a;
+    a.q = q;
+    a.kv = kv_cache;
+    a.table = block_table;
+    a.seqlens = seqlens;
+    a.out = out;
+    a.lse = lse;
+    a.part_o = p.part_o;
+    a.part_lse = p.part_lse;
+    a.scale_log2e = p.scale_log2e;
+    a.batch = p.batch;
+    a.rows = p.rows;
+    a.n_splits = ns;
+    a.max_blocks = p.max_blocks;
+    a.n_streams = p.n_streams;
+    a.flags = p.flags;
+    a.split_magic = ns > 1 ? (uint32_t)((1ull << 32) / (unsigned)ns) + 1u : 0u;
+    size_t arg_size = sizeof(a);
+    void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &a, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
+    const int which = (desc->variant == AMLA_RESCALE_ADD ? 1 : 0) + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 2 : 0);
+    if (hipModuleLaunchKernel(dk->fn[which], (unsigned)(8 * p.n_tiles), (unsigned)(streams_pad / 8), 1, kThreads, 1, 1,
+                              0, stream, nullptr, config) != hipSuccess) {
+      (void)hipGetLastError();
+      return AMLA_ERR_LAUNCH;
+    }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, stream, p);
-  if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   if (ns > 1) {
     hipLaunchKernelGGL(amla_combine_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
                        p.out, p.lse, (int)n_rows, ns);

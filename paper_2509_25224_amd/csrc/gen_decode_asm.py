@@ -1,0 +1,762 @@
+#!/usr/bin/env python3
+"""Generator of the hand-scheduled gfx950 decode kernels (CDNA4 assembly).
+
+Writes one assembly file holding four kernels, `amla_decode_asm_{mul,add}{,_lazy}`, that the
+build assembles into a code object and embeds into libamla.so.  All four run the same loop
+(Algorithm 1 / Algorithm 2 of the AMLA paper per 32-key sub-tile of a 64-key cache block);
+they differ only in how the reference of the exponent is moved and how the accumulator is
+rescaled:
+
+  mul        reference = running row max; O *= 2^(m_old - m_new)       (Algorithm 1, Eq. (2))
+  add        reference = rint(running row max), an integer power of two; O's bit patterns get
+             (n_new - n_old) << 23 added as INT32, guarded against exponent underflow
+             (Eq. (4), Lemma 3.1, Algorithm 2 lines 5-6 and 11-15)
+  *_lazy     the reference is moved only when the row max exceeds it by more than 2^8; until
+             then the softmax weights are allowed to grow up to 2^8 (same relative precision in
+             bf16 / FP32), which makes the rescale of the 32 x 512 accumulator a rare event.
+
+Work decomposition: one workgroup = 4 waves = 128 query rows of one (sequence, kv split);
+wave w owns rows 32w..32w+31.  Per lane: Q fragment in v0..v143, the 32 x 512 FP32 accumulator
+(transposed: lane % 32 is the query row) in a0..a255, everything else in v144..v255.
+
+Pipeline per sub-tile u (32 keys):
+  top      wait for sub-tile u+1 (direct-to-LDS loads issued two iterations ago), barrier,
+           issue the loads of sub-tile u+3 into the LDS slot that sub-tile u-1 just left
+  phase A  S^T(u+1) = K Q^T: 36 MFMAs in two accumulation chains, K operands streamed from LDS;
+           interleaved with the online softmax of sub-tile u on the VALU
+  rescale  (only if a row of the wave moved its reference) accumulator registers
+  phase B  O^T += V^T P^T for sub-tile u: 32 MFMAs, V^T operands through ds_read_b64_tr_b16
+LDS: ring of 4 slots of 32 rows x 1168 B (row padded by 16 B so that the 16 rows a b128 read
+touches per clock fall into distinct banks), 37 KiB per slot.
+"""
+from __future__ import annotations
+
+import os
+import sys
+
+ROW = 1168                 # padded LDS row
+SLOT = 37 * 1024           # LDS slot: 32 rows * 1168 B = 36.5 KiB, rounded up to whole 1 KiB loads
+NSLOT = 4
+LDS_BYTES = NSLOT * SLOT   # 151552
+LOADS_PER_SUBTILE = 10     # per wave: 9 distinct 1 KiB loads + the shared 37th (issued by every wave)
+LAZY_THRESHOLD = 8.0
+
+# ---- VGPR map -------------------------------------------------------------------------------
+Q = 0            # 144
+SA = 144         # 16  accumulation chain A of S^T(u+1)
+SB = 160         # 16  chain B
+SC = 176         # 16  scores / weights of sub-tile u
+PK = 192         # 8   bf16-packed weights (B operand of phase B)
+ST = 200         # 32  operand staging ring, 8 slots of 4
+NST = 8
+V_M = 232        # running row max (scaled, base 2)
+V_REF = 233      # reference subtracted in the exponent
+V_L32 = 234      # per-lane partial sum of FP32 weights
+V_L16 = 235      # per-lane partial sum of bf16-rounded weights
+V_FAC = 236      # mul: alpha, add: n23
+V_KOFF = 237
+V_VOFF = 238
+V_KCUR = 239
+V_VCUR = 240
+V_LD = 241       # 10 per-lane global offsets of the direct-to-LDS loads
+T0, T1, T2, T3, T4 = 251, 252, 253, 254, 255
+
+# ---- SGPR map -------------------------------------------------------------------------------
+S_KARG = 0       # 2
+S_WGX, S_WGY = 2, 3
+S_QP, S_KVP, S_TABP, S_LENP, S_OUTP, S_LSEP, S_POP, S_PLP = 4, 6, 8, 10, 12, 14, 16, 18
+S_C, S_BATCH, S_ROWS, S_NS, S_MAXB, S_NSTREAMS, S_FLAGS, S_MAGIC = 20, 21, 22, 23, 24, 25, 26, 27
+S_TILE, S_STREAM, S_B, S_SPLIT, S_LEN = 28, 29, 30, 31, 32
+S_U, S_ULAST, S_UEND = 33, 34, 35
+S_WAVE, S_WAVELDS = 36, 37
+S_SLOTV, S_SLOTK, S_SLOTLD = 38, 39, 40
+S_ONES = 41
+S_TABB = 42      # 2: block-table row of this sequence
+S_PHYS = 44
+S_GB = 46        # 2: global base of the sub-tile being loaded
+S_T0, S_T1, S_T2, S_T3 = 48, 49, 50, 51
+S_NEED = 52      # 2
+S_FIRST = 54
+S_ULD = 55       # sub-tile index the next load targets
+S_SAVE = 56      # 2
+S_REM = 58
+S_M0BASE = 59
+S_NEXT_FREE = 64
+
+KARG_SIZE = 0x60
+
+
+class Gen:
+    def __init__(self):
+        self.lines = []
+
+    def __call__(self, s):
+        self.lines.append("\t" + s)
+
+    def label(self, s):
+        self.lines.append(s + ":")
+
+    def comment(self, s):
+        self.lines.append("\t; " + s)
+
+
+def vr(base, n=1):
+    return f"v{base}" if n == 1 else f"v[{base}:{base + n - 1}]"
+
+
+def ar(base, n=1):
+    return f"a{base}" if n == 1 else f"a[{base}:{base + n - 1}]"
+
+
+def sr(base, n=1):
+    return f"s{base}" if n == 1 else f"s[{base}:{base + n - 1}]"
+
+
+class LdsQueue:
+    """Tracks the order of outstanding LDS reads so that each consumer waits with the exact
+    lgkmcnt.  LDS operations return in issue order."""
+
+    def __init__(self):
+        self.pending = []
+
+    def issue(self, tag):
+        self.pending.append(tag)
+        assert len(self.pending) <= 15
+
+    def wait_for(self, tag):
+        """Returns the lgkmcnt value after which `tag` has returned."""
+        i = self.pending.index(tag)
+        n = len(self.pending) - 1 - i
+        del self.pending[: i + 1]
+        return n
+
+
+def interleave(g, groups, valu, tail_first=0):
+    """Emit MFMA groups with the VALU stream spread between them, both in their own order."""
+    n = len(groups)
+    per = [0] * n
+    m = len(valu)
+    for i in range(m):
+        per[(i * n) // m if m else 0] += 1
+    vi = 0
+    for gi, grp in enumerate(groups):
+        for ins in grp:
+            g(ins)
+        for _ in range(per[gi]):
+            g(valu[vi])
+            vi += 1
+    assert vi == m
+
+
+def kernel(g: Gen, name: str, rescale: str, lazy: bool):
+    L = lambda s: f".L_{name}_{s}"
+    g.lines.append(f"\t.globl {name}\n\t.p2align 8\n\t.type {name},@function")
+    g.label(name)
+
+    # ------------------------------------------------------------------ prologue: arguments
+    g(f"s_load_dwordx16 {sr(S_QP, 16)}, {sr(S_KARG, 2)}, 0x0")
+    g(f"s_load_dwordx8 {sr(S_C, 8)}, {sr(S_KARG, 2)}, 0x40")
+    g(f"v_and_b32 v{T0}, 0x3ff, v0")                            # workitem id x (v0 packs x, y, z)
+    g(f"s_and_b32 {sr(S_T0)}, {sr(S_WGX)}, 7")                  # xcd
+    g(f"s_lshr_b32 {sr(S_TILE)}, {sr(S_WGX)}, 3")
+    g(f"s_lshl_b32 {sr(S_STREAM)}, {sr(S_WGY)}, 3")
+    g(f"s_or_b32 {sr(S_STREAM)}, {sr(S_STREAM)}, {sr(S_T0)}")
+    g("s_waitcnt lgkmcnt(0)")
+    if os.environ.get("AMLA_ASM_DEBUG") == "1":
+        g("v_mov_b32 v2, 0")
+        for i, reg in enumerate((S_WGX, S_WGY, S_STREAM, S_NSTREAMS, S_ROWS, S_NS)):
+            g(f"v_mov_b32 v1, {sr(reg)}")
+            g(f"v_cvt_f32_i32 v1, v1")
+            g(f"global_store_dword v2, v1, {sr(S_LSEP, 2)} offset:{4 * i}")
+        g("s_waitcnt vmcnt(0)")
+        g("s_endpgm")
+    g(f"s_cmp_ge_i32 {sr(S_STREAM)}, {sr(S_NSTREAMS)}")
+    g(f"s_cbranch_scc1 {L('end')}")
+    # b = stream / n_splits, split = stream % n_splits
+    g(f"s_mul_hi_u32 {sr(S_T1)}, {sr(S_STREAM)}, {sr(S_MAGIC)}")
+    g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
+    g(f"s_cselect_b32 {sr(S_B)}, {sr(S_STREAM)}, {sr(S_T1)}")
+    g(f"s_mul_i32 {sr(S_T1)}, {sr(S_B)}, {sr(S_NS)}")
+    g(f"s_sub_u32 {sr(S_SPLIT)}, {sr(S_STREAM)}, {sr(S_T1)}")
+    g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_B)}, 2")
+    g(f"s_load_dword {sr(S_LEN)}, {sr(S_LENP, 2)}, {sr(S_T1)}")
+    # block table row: table + b * max_blocks * 4
+    g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_MAXB)}")
+    g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_B)}, {sr(S_MAXB)}")
+    g(f"s_lshl_b64 {sr(S_T2, 2)}, {sr(S_T2, 2)}, 2")
+    g(f"s_add_u32 {sr(S_TABB)}, {sr(S_TABP)}, {sr(S_T2)}")
+    g(f"s_addc_u32 {sr(S_TABB + 1)}, {sr(S_TABP + 1)}, {sr(S_T3)}")
+    # lane decomposition
+    g(f"v_lshrrev_b32 v{T1}, 6, v{T0}")
+    g("s_nop 3")                                                # VALU write -> v_readfirstlane of the same VGPR needs a wait state
+    g(f"v_readfirstlane_b32 {sr(S_WAVE)}, v{T1}")
+    g("s_nop 3")
+    g(f"s_and_b32 {sr(S_WAVE)}, {sr(S_WAVE)}, 3")               # 4 waves; keeps every derived LDS / global offset in range
+    g(f"v_and_b32 v{T0}, 63, v{T0}")                            # lane
+    g(f"s_lshl_b32 {sr(S_WAVELDS)}, {sr(S_WAVE)}, 10")
+    g(f"s_mov_b32 {sr(S_ONES)}, 0x3f803f80")
+    g(f"s_mov_b32 {sr(S_FIRST)}, 1")
+    # per-lane LDS read offsets
+    g(f"v_and_b32 v{T1}, 31, v{T0}")                            # l32
+    g(f"v_lshrrev_b32 v{T2}, 5, v{T0}")                         # h
+    g(f"v_mul_u32_u24 v{V_KOFF}, {ROW}, v{T1}")
+    g(f"v_lshl_add_u32 v{V_KOFF}, v{T2}, 4, v{V_KOFF}")         # l32 * 1168 + h * 16
+    g(f"v_lshrrev_b32 v{T3}, 4, v{T0}")                         # g16 = lane >> 4
+    g(f"v_and_b32 v{T4}, 15, v{T0}")                            # i16
+    g(f"v_lshrrev_b32 v{V_VOFF}, 1, v{T3}")                     # g16 >> 1
+    g(f"v_lshlrev_b32 v{V_VOFF}, 2, v{V_VOFF}")                 # 4 * (g16 >> 1)
+    g(f"v_lshrrev_b32 v{V_KCUR}, 2, v{T4}")                     # i16 >> 2
+    g(f"v_add_u32 v{V_VOFF}, v{V_VOFF}, v{V_KCUR}")
+    g(f"v_mul_u32_u24 v{V_VOFF}, {ROW}, v{V_VOFF}")             # row part
+    g(f"v_and_b32 v{T3}, 1, v{T3}")                             # g16 & 1
+    g(f"v_lshlrev_b32 v{T3}, 5, v{T3}")                         # * 16 columns * 2 B
+    g(f"v_and_b32 v{T4}, 3, v{T4}")                             # i16 & 3
+    g(f"v_lshl_add_u32 v{T3}, v{T4}, 3, v{T3}")                 # + 4 columns * 2 B each
+    g(f"v_add_u32 v{V_VOFF}, v{V_VOFF}, v{T3}")
+    # per-lane global offsets of the direct-to-LDS loads: chunk c = 64 i + lane of the padded
+    # sub-tile is row c / 73, 16-byte column c % 73 (72 = padding); source offset 16 (c - row)
+    for k in range(LOADS_PER_SUBTILE):
+        dst = V_LD + k
+        if k < 9:
+            g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_WAVE)}, 6")
+            g(f"s_add_u32 {sr(S_T1)}, {sr(S_T1)}, {256 * k}")    # 64 * (wave + 4 k)
+        else:
+            g(f"s_mov_b32 {sr(S_T1)}, {36 * 64}")
+        g(f"v_add_u32 v{T3}, {sr(S_T1)}, v{T0}")                # c
+        g(f"v_mul_u32_u24 v{T4}, 57457, v{T3}")
+        g(f"v_lshrrev_b32 v{T4}, 22, v{T4}")                    # row = c / 73
+        g(f"v_mul_u32_u24 v{V_KCUR}, 73, v{T4}")
+        g(f"v_sub_u32 v{V_KCUR}, v{T3}, v{V_KCUR}")             # c % 73
+        g(f"v_sub_u32 v{dst}, v{T3}, v{T4}")
+        g(f"v_lshlrev_b32 v{dst}, 4, v{dst}")
+        g(f"v_cmp_gt_u32 vcc, 72, v{V_KCUR}")                   # real column
+        g(f"v_cmp_gt_u32 {sr(S_NEED, 2)}, 32, v{T4}")           # real row (37th load: lanes 32.. are past the end)
+        g(f"s_and_b64 vcc, vcc, {sr(S_NEED, 2)}")
+        g(f"v_cndmask_b32 v{dst}, 0, v{dst}, vcc")
+        g(f"v_min_u32 v{dst}, {36864 - 16}, v{dst}")             # never past the 32-row half block
+    # row of this lane and the Q fragment
+    g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_TILE)}, 7")
+    g(f"s_lshl_b32 {sr(S_T2)}, {sr(S_WAVE)}, 5")
+    g(f"s_add_u32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_T2)}")
+    g(f"v_and_b32 v{T1}, 31, v{T0}")
+    g(f"v_add_u32 v{V_M}, {sr(S_T1)}, v{T1}")                   # row within the sequence
+    g(f"v_cmp_gt_i32 vcc, {sr(S_ROWS)}, v{V_M}")
+    g(f"v_cndmask_b32 v{T1}, 0, v{V_M}, vcc")                   # rows past the end read row 0
+    g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_ROWS)}")
+    g(f"v_add_u32 v{T1}, {sr(S_T2)}, v{T1}")                    # global row
+    g(f"v_mov_b32 v{T3}, 1152")
+    g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T1}, v{T3}, {sr(S_QP, 2)}")
+    g(f"v_lshlrev_b32 v{T2}, 4, v{T2}")                         # h * 16
+    g(f"v_add_co_u32 v{V_L32}, vcc, v{V_L32}, v{T2}")
+    g(f"v_addc_co_u32 v{V_L16}, vcc, 0, v{V_L16}, vcc")
+    for ks in range(36):
+        g(f"global_load_dwordx4 {vr(Q + 4 * ks, 4)}, {vr(V_L32, 2)}, off offset:{32 * ks}")
+    # accumulator = 0
+    for i in range(256):
+        g(f"v_accvgpr_write_b32 a{i}, 0")
+
+    # sub-tile range of this split
+    g("s_waitcnt lgkmcnt(0)")
+    g(f"s_add_u32 {sr(S_T0)}, {sr(S_LEN)}, 63")
+    g(f"s_lshr_b32 {sr(S_T0)}, {sr(S_T0)}, 6")                  # nb
+    g(f"s_add_u32 {sr(S_T1)}, {sr(S_LEN)}, 31")
+    g(f"s_lshr_b32 {sr(S_T1)}, {sr(S_T1)}, 5")                  # n32
+    g(f"s_mul_i32 {sr(S_T2)}, {sr(S_SPLIT)}, {sr(S_T0)}")       # x0 = split * nb
+    g(f"s_add_u32 {sr(S_T3)}, {sr(S_T2)}, {sr(S_T0)}")          # x1
+    g(f"s_mul_hi_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_MAGIC)}")    # j0
+    g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_T3)}, {sr(S_MAGIC)}")    # j1
+    g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
+    g(f"s_cselect_b32 {sr(S_T2)}, 0, {sr(S_T2)}")
+    g(f"s_cselect_b32 {sr(S_T3)}, {sr(S_T0)}, {sr(S_T3)}")
+    g(f"s_lshl_b32 {sr(S_U)}, {sr(S_T2)}, 1")                   # u0
+    g(f"s_lshl_b32 {sr(S_UEND)}, {sr(S_T3)}, 1")
+    g(f"s_min_u32 {sr(S_UEND)}, {sr(S_UEND)}, {sr(S_T1)}")
+    g(f"s_sub_u32 {sr(S_ULAST)}, {sr(S_UEND)}, 1")
+    # state
+    g(f"v_mov_b32 v{V_M}, 0xff800000")
+    g(f"v_mov_b32 v{V_REF}, 0xff800000")
+    g(f"v_mov_b32 v{V_FAC}, 0")
+
+    def finish_state_init():
+        g(f"v_mov_b32 v{V_L32}, 0")
+        g(f"v_mov_b32 v{V_L16}, 0")
+
+    g(f"s_cmp_ge_u32 {sr(S_U)}, {sr(S_UEND)}")
+    g(f"s_cbranch_scc0 {L('nonempty')}")
+    g("s_waitcnt vmcnt(0)")
+    finish_state_init()
+    g(f"s_branch {L('epilogue')}")
+    g.label(L("nonempty"))
+
+    # ---- direct-to-LDS load of one sub-tile ---------------------------------------------------
+    def tile_base_from_phys():
+        """S_GB = kv + phys * 73728 + (S_ULD & 1) * 36864."""
+        g(f"s_mul_i32 {sr(S_T2)}, {sr(S_PHYS)}, 73728")
+        g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_PHYS)}, 73728")
+        g(f"s_and_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
+        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, 36864")
+        g(f"s_add_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_T1)}")
+        g(f"s_addc_u32 {sr(S_T3)}, {sr(S_T3)}, 0")
+        g(f"s_add_u32 {sr(S_GB)}, {sr(S_KVP)}, {sr(S_T2)}")
+        g(f"s_addc_u32 {sr(S_GB + 1)}, {sr(S_KVP + 1)}, {sr(S_T3)}")
+
+    def issue_subtile_loads():
+        """10 loads per wave into slot S_SLOTLD from S_GB."""
+        g(f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}")
+        for k in range(LOADS_PER_SUBTILE):
+            if k < 9:
+                g(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
+            else:
+                g(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
+            g("s_nop 0")
+            g(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
+
+    def fetch_phys_blocking():
+        g(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
+        g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
+        g(f"s_load_dword {sr(S_PHYS)}, {sr(S_TABB, 2)}, {sr(S_T1)}")
+        g("s_waitcnt lgkmcnt(0)")
+
+    def advance_slot(reg):
+        g(f"s_add_u32 {sr(reg)}, {sr(reg)}, {SLOT}")
+        g(f"s_cmp_ge_u32 {sr(reg)}, {LDS_BYTES}")
+        g(f"s_cselect_b32 {sr(reg)}, 0, {sr(reg)}")
+
+    # prologue loads: sub-tiles u0, u0+1, u0+2 (clamped to the last one) into slots 0, 1, 2
+    g(f"s_mov_b32 {sr(S_SLOTLD)}, 0")
+    for n in range(3):
+        g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {n}")
+        g(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
+        fetch_phys_blocking()
+        tile_base_from_phys()
+        issue_subtile_loads()
+        advance_slot(S_SLOTLD)
+    # S_SLOTLD now = slot 3, the target of sub-tile u0+3
+    g(f"s_mov_b32 {sr(S_SLOTV)}, 0")
+    g(f"s_mov_b32 {sr(S_SLOTK)}, 0")            # the prologue QK reads sub-tile u0 from slot 0
+    # phys for the first in-loop load (sub-tile u0 + 3)
+    g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, 3")
+    g(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
+    fetch_phys_blocking()
+    finish_state_init()
+
+    # ---- phase A: QK of the sub-tile in slot S_SLOTK; optional VALU stream ----------------------
+    def phase_a(valu, with_table_load):
+        q = LdsQueue()
+        g(f"v_add_u32 v{V_KCUR}, {sr(S_SLOTK)}, v{V_KOFF}")
+        groups = []
+        pre = []
+        for ks in range(NST):
+            pre.append(f"ds_read_b128 {vr(ST + 4 * (ks % NST), 4)}, v{V_KCUR} offset:{32 * ks}")
+            q.issue(ks)
+        for ins in pre:
+            g(ins)
+        for ks in range(36):
+            grp = []
+            if with_table_load and ks == 0:
+                # Block-table entry of the sub-tile the next iteration loads.  SMEM shares lgkmcnt
+                # with LDS and may return out of order; counting only the LDS reads in the waits
+                # below stays correct (an outstanding SMEM op can only make a wait stricter), and
+                # the loop top waits for lgkmcnt(0) before the entry is used.
+                grp.append(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, 4")
+                grp.append(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
+                grp.append(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
+                grp.append(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
+                grp.append(f"s_load_dword {sr(S_PHYS)}, {sr(S_TABB, 2)}, {sr(S_T1)}")
+            n = q.wait_for(ks)
+            grp.append(f"s_waitcnt lgkmcnt({n})")
+            dst = SA if ks % 2 == 0 else SB
+            src_c = "0" if ks < 2 else vr(dst, 16)
+            grp.append(f"v_mfma_f32_32x32x16_bf16 {vr(dst, 16)}, {vr(ST + 4 * (ks % NST), 4)}, "
+                       f"{vr(Q + 4 * ks, 4)}, {src_c}")
+            nxt = ks + NST
+            if nxt < 36:
+                grp.append(f"ds_read_b128 {vr(ST + 4 * (nxt % NST), 4)}, v{V_KCUR} offset:{32 * nxt}")
+                q.issue(nxt)
+            groups.append(grp)
+        interleave(g, groups, valu)
+
+    # ---- softmax of the scores in SC (VALU stream) -------------------------------------------
+    def softmax_stream():
+        v = []
+        sc = [SC + r for r in range(16)]
+        v.append(f"v_max3_f32 v{T0}, v{sc[0]}, v{sc[1]}, v{sc[2]}")
+        for i in range(3, 15, 2):
+            v.append(f"v_max3_f32 v{T0}, v{T0}, v{sc[i]}, v{sc[i + 1]}")
+        v.append(f"v_max_f32 v{T0}, v{T0}, v{sc[15]}")
+        v.append(f"v_mov_b32 v{T1}, v{T0}")
+        v.append("s_nop 1")
+        v.append(f"v_permlane32_swap_b32 v{T0}, v{T1}")
+        v.append("s_nop 1")
+        v.append(f"v_max_f32 v{T0}, v{T0}, v{T1}")
+        v.append(f"v_mul_f32 v{T0}, {sr(S_C)}, v{T0}")
+        v.append(f"v_max_f32 v{T0}, v{V_M}, v{T0}")                      # m_new
+        v.append(f"v_mov_b32 v{V_M}, v{T0}")
+        # candidate reference
+        if rescale == "add":
+            v.append(f"v_rndne_f32 v{T1}, v{T0}")
+        else:
+            v.append(f"v_mov_b32 v{T1}, v{T0}")
+        if lazy:
+            v.append(f"v_add_f32 v{T4}, {LAZY_THRESHOLD}, v{V_REF}")
+            v.append(f"v_cmp_gt_f32 vcc, v{T0}, v{T4}")
+            v.append(f"v_cndmask_b32 v{T1}, v{V_REF}, v{T1}, vcc")      # keep the old reference unless exceeded
+        # factor on the old state, and whether any row of the wave needs the accumulator rescaled
+        if rescale == "mul":
+            v.append(f"v_sub_f32 v{T4}, v{V_REF}, v{T1}")
+            v.append(f"v_exp_f32 v{V_FAC}, v{T4}")
+            v.append(f"v_cmp_neq_f32 {sr(S_NEED, 2)}, v{V_REF}, v{T1}")
+        else:
+            v.append(f"v_sub_f32 v{T4}, v{V_REF}, v{T1}")                # <= 0, integer valued (or -inf)
+            v.append(f"v_max_f32 v{T4}, 0xc1f00000, v{T4}")             # clamp at -30 (Algorithm 2 line 11)
+            v.append(f"v_cvt_i32_f32 v{T4}, v{T4}")
+            v.append(f"v_lshlrev_b32 v{V_FAC}, 23, v{T4}")
+            v.append(f"v_cmp_ne_u32 {sr(S_NEED, 2)}, 0, v{V_FAC}")
+        v.append(f"v_mov_b32 v{V_REF}, v{T1}")
+        # weights 2^(s * c - ref)
+        for r in range(16):
+            v.append(f"v_fma_f32 v{sc[r]}, v{sc[r]}, {sr(S_C)}, -v{T1}")
+        for r in range(16):
+            v.append(f"v_exp_f32 v{sc[r]}, v{sc[r]}")
+        v.append(f"v_add_f32 v{T2}, v{sc[0]}, v{sc[1]}")
+        for r in range(2, 16):
+            v.append(f"v_add_f32 v{T2}, v{T2}, v{sc[r]}")
+        for i in range(8):
+            v.append(f"v_cvt_pk_bf16_f32 v{PK + i}, v{sc[2 * i]}, v{sc[2 * i + 1]}")
+        v.append(f"v_mov_b32 v{T3}, 0")
+        for i in range(8):
+            v.append(f"v_dot2_f32_bf16 v{T3}, v{PK + i}, {sr(S_ONES)}, v{T3}")
+        if rescale == "mul":
+            v.append(f"v_fma_f32 v{V_L32}, v{V_L32}, v{V_FAC}, v{T2}")
+            v.append(f"v_fma_f32 v{V_L16}, v{V_L16}, v{V_FAC}, v{T3}")
+        else:
+            for reg, add in ((V_L32, T2), (V_L16, T3)):
+                v.append(f"v_and_b32 v{T4}, 0x80000000, v{reg}")
+                v.append(f"v_add_i32 v{reg}, v{reg}, v{V_FAC} clamp")
+                v.append(f"v_max_i32 v{reg}, v{reg}, v{T4}")
+                v.append(f"v_add_f32 v{reg}, v{reg}, v{add}")
+        return v
+
+    def form_scores_stream():
+        """SC = SA + SB once the chains have drained."""
+        return [f"v_add_f32 v{SC + r}, v{SA + r}, v{SB + r}" for r in range(16)]
+
+    def mask_partial():
+        """Keys >= S_REM of the sub-tile whose scores are in SC get -inf."""
+        # lane's key for register r: 4 h + 8 (r >> 2) + (r & 3); h = lane >> 5
+        g(f"v_mbcnt_lo_u32_b32 v{T0}, -1, 0")
+        g(f"v_mbcnt_hi_u32_b32 v{T0}, -1, v{T0}")                 # lane id
+        g(f"v_lshrrev_b32 v{T0}, 5, v{T0}")
+        g(f"v_lshlrev_b32 v{T0}, 2, v{T0}")                       # 4 h
+        g(f"v_mov_b32 v{T1}, 0xff800000")
+        for r in range(16):
+            const = 8 * (r >> 2) + (r & 3)
+            g(f"s_sub_i32 {sr(S_T1)}, {sr(S_REM)}, {const}")      # key >= rem  <=>  4 h >= rem - const
+            g(f"v_cmp_le_i32 vcc, {sr(S_T1)}, v{T0}")
+            g(f"v_cndmask_b32 v{SC + r}, v{SC + r}, v{T1}, vcc")
+
+    # ---- prologue QK of sub-tile u0 --------------------------------------------------------------
+    g(f"s_waitcnt vmcnt({2 * LOADS_PER_SUBTILE})")
+    g("s_barrier")
+    phase_a([], False)
+    g("s_nop 15")
+    g("s_nop 15")
+    for ins in form_scores_stream():
+        g(ins)
+    # partial first sub-tile?
+    g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
+    g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
+    g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
+    g(f"s_cbranch_scc1 {L('pro_full')}")
+    mask_partial()
+    g.label(L("pro_full"))
+    advance_slot(S_SLOTK)                                       # slot of sub-tile u0 + 1
+
+    # ------------------------------------------------------------------------------ main loop
+    g.label(L("loop"))
+    g(f"s_waitcnt vmcnt({LOADS_PER_SUBTILE}) lgkmcnt(0)")
+    g("s_barrier")
+    tile_base_from_phys()
+    issue_subtile_loads()
+    advance_slot(S_SLOTLD)
+    phase_a(softmax_stream(), True)
+
+    # ---- rescale of the accumulator registers (rare path) ----
+    g(f"s_cmp_lg_u64 {sr(S_NEED, 2)}, 0")
+    g(f"s_cselect_b32 {sr(S_T0)}, 1, 0")
+    g(f"s_andn2_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_FIRST)}")
+    g(f"s_bitcmp1_b32 {sr(S_FLAGS)}, 0")                         # AMLA_FLAG_NO_SKIP
+    g(f"s_cselect_b32 {sr(S_T1)}, 1, 0")
+    g(f"s_andn2_b32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_FIRST)}")
+    g(f"s_or_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_T1)}")
+    g(f"s_mov_b32 {sr(S_FIRST)}, 0")
+    g(f"s_cmp_eq_u32 {sr(S_T0)}, 0")
+    g(f"s_cbranch_scc1 {L('no_rescale')}")
+    for base in range(0, 256, 16):
+        for r in range(16):
+            g(f"v_accvgpr_read_b32 v{ST + r}, a{base + r}")
+        if rescale == "mul":
+            for r in range(16):
+                g(f"v_mul_f32 v{ST + r}, v{ST + r}, v{V_FAC}")
+        else:
+            for r in range(16):
+                g(f"v_and_b32 v{ST + 16 + r}, 0x80000000, v{ST + r}")
+            for r in range(16):
+                g(f"v_add_i32 v{ST + r}, v{ST + r}, v{V_FAC} clamp")
+            for r in range(16):
+                g(f"v_max_i32 v{ST + r}, v{ST + r}, v{ST + 16 + r}")
+        for r in range(16):
+            g(f"v_accvgpr_write_b32 a{base + r}, v{ST + r}")
+    g("s_nop 7")
+    g.label(L("no_rescale"))
+
+    # ---- phase B: O^T += V^T P^T for the sub-tile in slot S_SLOTV ----
+    q = LdsQueue()
+    g(f"v_add_u32 v{V_VCUR}, {sr(S_SLOTV)}, v{V_VOFF}")
+    order = [(st, dt) for st in range(2) for dt in range(16)]
+
+    def v_reads(idx):
+        st, dt = order[idx]
+        slot = ST + 4 * (idx % NST)
+        base = st * 16 * ROW + dt * 64
+        return [f"ds_read_b64_tr_b16 {vr(slot, 2)}, v{V_VCUR} offset:{base}",
+                f"ds_read_b64_tr_b16 {vr(slot + 2, 2)}, v{V_VCUR} offset:{base + 8 * ROW}"]
+
+    depth = 6                                  # 12 reads in flight <= 15
+    for idx in range(depth):
+        for ins in v_reads(idx):
+            g(ins)
+        q.issue((idx, 0))
+        q.issue((idx, 1))
+    groups = []
+    for idx, (st, dt) in enumerate(order):
+        grp = []
+        n = q.wait_for((idx, 1))
+        grp.append(f"s_waitcnt lgkmcnt({n})")
+        slot = ST + 4 * (idx % NST)
+        grp.append(f"v_mfma_f32_32x32x16_bf16 {ar(16 * dt, 16)}, {vr(slot, 4)}, {vr(PK + 4 * st, 4)}, "
+                   f"{ar(16 * dt, 16)}")
+        nxt = idx + depth
+        if nxt < len(order):
+            grp.extend(v_reads(nxt))
+            q.issue((nxt, 0))
+            q.issue((nxt, 1))
+        groups.append(grp)
+    # VALU stream of phase B: the scores of sub-tile u+1 (after the QK chains have drained)
+    valu_b = ["s_nop 15", "s_nop 7"] + form_scores_stream()
+    interleave(g, groups, valu_b)
+
+    # ---- advance ----
+    g(f"s_add_u32 {sr(S_U)}, {sr(S_U)}, 1")
+    advance_slot(S_SLOTV)
+    advance_slot(S_SLOTK)
+    g(f"s_cmp_ge_u32 {sr(S_U)}, {sr(S_UEND)}")
+    g(f"s_cbranch_scc1 {L('epilogue')}")
+    # sub-tile u (new) partial?  its scores are now in SC
+    g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
+    g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
+    g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
+    g(f"s_cbranch_scc1 {L('loop')}")
+    mask_partial()
+    g(f"s_branch {L('loop')}")
+
+    # --------------------------------------------------------------------------------- epilogue
+    g.label(L("epilogue"))
+    g("s_waitcnt vmcnt(0)")
+    if os.environ.get("AMLA_ASM_DEBUG") == "2":
+        g(f"v_mov_b32 v{T0}, 0")
+        for i, reg in enumerate((S_U, S_UEND, S_LEN, S_SPLIT, S_B, S_TILE, S_WAVE, S_ULAST)):
+            g(f"v_mov_b32 v{T1}, {sr(reg)}")
+            g(f"v_cvt_f32_i32 v{T1}, v{T1}")
+            g(f"global_store_dword v{T0}, v{T1}, {sr(S_LSEP, 2)} offset:{4 * i}")
+        for i, reg in enumerate((V_M, V_REF, V_L32, V_L16, V_FAC, SC, SC + 1, PK)):
+            g(f"global_store_dword v{T0}, v{reg}, {sr(S_LSEP, 2)} offset:{32 + 4 * i}")
+        g("s_waitcnt vmcnt(0)")
+        g("s_endpgm")
+    g("s_nop 15")
+    g("s_nop 15")
+    # totals over the two lane halves
+    for reg in (V_L32, V_L16):
+        g(f"v_mov_b32 v{T1}, v{reg}")
+        g("s_nop 1")
+        g(f"v_permlane32_swap_b32 v{reg}, v{T1}")
+        g("s_nop 1")
+        g(f"v_add_f32 v{reg}, v{reg}, v{T1}")
+    g(f"v_rcp_f32 v{T2}, v{V_L16}")
+    g(f"v_cmp_lt_f32 vcc, 0, v{V_L16}")
+    g("s_nop 0")
+    g(f"v_cndmask_b32 v{T2}, 0, v{T2}, vcc")                     # 1 / l (0 for an empty range)
+    g(f"v_log_f32 v{T3}, v{V_L32}")
+    g("s_nop 0")
+    g(f"v_add_f32 v{T3}, v{T3}, v{V_REF}")
+    g(f"v_mul_f32 v{T3}, 0x3f317218, v{T3}")                    # * ln 2
+    g(f"v_cmp_lt_f32 vcc, 0, v{V_L32}")
+    g(f"v_mov_b32 v{T4}, 0xff800000")
+    g(f"v_cndmask_b32 v{T3}, v{T4}, v{T3}, vcc")                 # lse (-inf for an empty range)
+    # row index and store mask
+    g(f"v_mbcnt_lo_u32_b32 v{T0}, -1, 0")
+    g(f"v_mbcnt_hi_u32_b32 v{T0}, -1, v{T0}")                    # lane
+    g(f"v_lshrrev_b32 v{V_KOFF}, 5, v{T0}")                      # h
+    g(f"v_and_b32 v{T0}, 31, v{T0}")
+    g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_TILE)}, 7")
+    g(f"s_lshl_b32 {sr(S_T2)}, {sr(S_WAVE)}, 5")
+    g(f"s_add_u32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_T2)}")
+    g(f"v_add_u32 v{T0}, {sr(S_T1)}, v{T0}")                     # row
+    g(f"v_cmp_gt_i32 vcc, {sr(S_ROWS)}, v{T0}")
+    g(f"s_and_saveexec_b64 {sr(S_SAVE, 2)}, vcc")
+    g(f"s_cbranch_execz {L('end')}")
+    g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_ROWS)}")
+    g(f"v_add_u32 v{T0}, {sr(S_T2)}, v{T0}")                     # global row  b * rows + row
+    g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
+    g(f"s_cbranch_scc0 {L('store_partial')}")
+
+    # direct: bf16 out + lse
+    g(f"v_mov_b32 v{T4}, 1024")
+    g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_OUTP, 2)}")
+    g(f"v_lshlrev_b32 v{T4}, 3, v{V_KOFF}")                      # h * 8 B
+    g(f"v_add_co_u32 v{V_L32}, vcc, v{V_L32}, v{T4}")
+    g(f"v_addc_co_u32 v{V_L16}, vcc, 0, v{V_L16}, vcc")
+    if os.environ.get("AMLA_ASM_DEBUG") == "3":
+        g(f"v_mov_b32 v{V_VOFF}, 0")
+        g(f"v_mov_b32 v{V_KCUR}, exec_lo")
+        g(f"v_cvt_f32_u32 v{V_KCUR}, v{V_KCUR}")
+        g(f"global_store_dword v{V_VOFF}, v{V_KCUR}, {sr(S_LSEP, 2)} offset:0")
+        g(f"v_cvt_f32_u32 v{V_KCUR}, v{V_L32}")
+        g(f"global_store_dword v{V_VOFF}, v{V_KCUR}, {sr(S_LSEP, 2)} offset:4")
+        g(f"v_cvt_f32_u32 v{V_KCUR}, v{V_L16}")
+        g(f"global_store_dword v{V_VOFF}, v{V_KCUR}, {sr(S_LSEP, 2)} offset:8")
+        g(f"v_mov_b32 v{V_KCUR}, {sr(S_OUTP)}")
+        g(f"v_cvt_f32_u32 v{V_KCUR}, v{V_KCUR}")
+        g(f"global_store_dword v{V_VOFF}, v{V_KCUR}, {sr(S_LSEP, 2)} offset:12")
+        g(f"v_mov_b32 v{V_KCUR}, {sr(S_OUTP + 1)}")
+        g(f"v_cvt_f32_u32 v{V_KCUR}, v{V_KCUR}")
+        g(f"global_store_dword v{V_VOFF}, v{V_KCUR}, {sr(S_LSEP, 2)} offset:16")
+        g(f"global_store_dword v{V_VOFF}, v{T2}, {sr(S_LSEP, 2)} offset:20")
+        g(f"global_store_dword v{V_VOFF}, v{T3}, {sr(S_LSEP, 2)} offset:24")
+        g(f"v_accvgpr_read_b32 v{V_KCUR}, a0")
+        g(f"global_store_dword v{V_VOFF}, v{V_KCUR}, {sr(S_LSEP, 2)} offset:28")
+        g("s_waitcnt vmcnt(0)")
+        g("s_endpgm")
+    for dt in range(16):
+        for rg in range(4):
+            t = ST + 8 * (rg % 4)
+            for e in range(4):
+                g(f"v_accvgpr_read_b32 v{t + e}, a{16 * dt + 4 * rg + e}")
+            for e in range(4):
+                g(f"v_mul_f32 v{t + e}, v{t + e}, v{T2}")
+            g(f"v_cvt_pk_bf16_f32 v{t + 4}, v{t}, v{t + 1}")
+            g(f"v_cvt_pk_bf16_f32 v{t + 5}, v{t + 2}, v{t + 3}")
+            g(f"global_store_dwordx2 {vr(V_L32, 2)}, {vr(t + 4, 2)}, off offset:{64 * dt + 16 * rg}")
+    g(f"s_cmp_eq_u64 {sr(S_LSEP, 2)}, 0")
+    g(f"s_cbranch_scc1 {L('end')}")
+    g(f"v_cmp_eq_u32 vcc, 0, v{V_KOFF}")                         # h == 0 writes the row's lse
+    g(f"s_and_b64 exec, exec, vcc")
+    g(f"s_cbranch_execz {L('end')}")
+    g(f"v_mov_b32 v{T4}, 4")
+    g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_LSEP, 2)}")
+    g(f"global_store_dword {vr(V_L32, 2)}, v{T3}, off")
+    g(f"s_branch {L('end')}")
+
+    # split: f32 partial out + partial lse at [(split * batch * rows) + global row]
+    g.label(L("store_partial"))
+    g(f"s_mul_i32 {sr(S_T1)}, {sr(S_BATCH)}, {sr(S_ROWS)}")
+    g(f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_SPLIT)}")
+    g(f"v_add_u32 v{T0}, {sr(S_T1)}, v{T0}")
+    g(f"v_mov_b32 v{T4}, 2048")
+    g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_POP, 2)}")
+    g(f"v_lshlrev_b32 v{T4}, 4, v{V_KOFF}")                      # h * 16 B
+    g(f"v_add_co_u32 v{V_L32}, vcc, v{V_L32}, v{T4}")
+    g(f"v_addc_co_u32 v{V_L16}, vcc, 0, v{V_L16}, vcc")
+    for dt in range(16):
+        for rg in range(4):
+            t = ST + 4 * ((4 * dt + rg) % 8)
+            for e in range(4):
+                g(f"v_accvgpr_read_b32 v{t + e}, a{16 * dt + 4 * rg + e}")
+            for e in range(4):
+                g(f"v_mul_f32 v{t + e}, v{t + e}, v{T2}")
+            g(f"global_store_dwordx4 {vr(V_L32, 2)}, {vr(t, 4)}, off offset:{128 * dt + 32 * rg}")
+    g(f"v_cmp_eq_u32 vcc, 0, v{V_KOFF}")
+    g(f"s_and_b64 exec, exec, vcc")
+    g(f"s_cbranch_execz {L('end')}")
+    g(f"v_mov_b32 v{T4}, 4")
+    g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_PLP, 2)}")
+    g(f"global_store_dword {vr(V_L32, 2)}, v{T3}, off")
+
+    g.label(L("end"))
+    g("s_endpgm")
+    g.lines.append(f".Lfunc_end_{name}:\n\t.size {name}, .Lfunc_end_{name}-{name}")
+
+    # kernel descriptor
+    g.lines.append(f"""
+	.rodata
+	.p2align 6
+	.amdhsa_kernel {name}
+		.amdhsa_group_segment_fixed_size {LDS_BYTES}
+		.amdhsa_private_segment_fixed_size 0
+		.amdhsa_kernarg_size {KARG_SIZE}
+		.amdhsa_user_sgpr_count 2
+		.amdhsa_user_sgpr_kernarg_segment_ptr 1
+		.amdhsa_system_sgpr_workgroup_id_x 1
+		.amdhsa_system_sgpr_workgroup_id_y 1
+		.amdhsa_system_sgpr_workgroup_id_z 0
+		.amdhsa_system_vgpr_workitem_id 0
+		.amdhsa_next_free_vgpr 512
+		.amdhsa_next_free_sgpr {S_NEXT_FREE}
+		.amdhsa_accum_offset 256
+		.amdhsa_reserve_vcc 1
+		.amdhsa_float_round_mode_32 0
+		.amdhsa_float_round_mode_16_64 0
+		.amdhsa_float_denorm_mode_32 3
+		.amdhsa_float_denorm_mode_16_64 3
+		.amdhsa_dx10_clamp 1
+		.amdhsa_ieee_mode 1
+	.end_amdhsa_kernel
+	.text
+""")
+
+
+def metadata(names):
+    out = ["\t.amdgpu_metadata", "---", "amdhsa.kernels:"]
+    for name in names:
+        out.append(f"""  - .agpr_count:     256
+    .args:
+      - .offset:         0
+        .size:           {KARG_SIZE}
+        .value_kind:     by_value
+    .group_segment_fixed_size: {LDS_BYTES}
+    .kernarg_segment_align: 8
+    .kernarg_segment_size: {KARG_SIZE}
+    .max_flat_workgroup_size: 256
+    .name:           {name}
+    .private_segment_fixed_size: 0
+    .sgpr_count:     {S_NEXT_FREE + 6}
+    .sgpr_spill_count: 0
+    .symbol:         {name}.kd
+    .uniform_work_group_size: 1
+    .uses_dynamic_stack: false
+    .vgpr_count:     512
+    .vgpr_spill_count: 0
+    .wavefront_size: 64""")
+    out += ["amdhsa.target:   amdgcn-amd-amdhsa--gfx950", "amdhsa.version:", "  - 1", "  - 2", "...", "",
+            "\t.end_amdgpu_metadata"]
+    return "\n".join(out)
+
+
+KERNELS = [("amla_decode_asm_mul", "mul", False), ("amla_decode_asm_add", "add", False),
+           ("amla_decode_asm_mul_lazy", "mul", True), ("amla_decode_asm_add_lazy", "add", True)]
+
+
+def main():
+    out_path = sys.argv[1]
+    g = Gen()
+    g.lines.append('\t.amdgcn_target "amdgcn-amd-amdhsa--gfx950"')
+    g.lines.append("\t.text")
+    for name, rescale, lazy in KERNELS:
+        kernel(g, name, rescale, lazy)
+    text = "\n".join(g.lines) + "\n" + metadata([k[0] for k in KERNELS]) + "\n"
+    with open(out_path, "w") as f:
+        f.write(text)
+
+
+if __name__ == "__main__":
+    main()

@@ -49,7 +49,8 @@ def test_argument_validation_error_codes(amla):
     assert _call(amla, good, out=None) == amla.AMLA_ERR_NULL_ARG
     assert amla.lib.amla_decode(16, 16, 16, 16, 0.1, 16, None, None) == amla.AMLA_ERR_NULL_ARG
     for field, val in (("d_qk", 512), ("d_v", 576), ("block_size", 128), ("batch", 0), ("s_q", 0),
-                       ("num_heads", 0), ("variant", 7), ("num_splits", -1), ("flags", 64), ("reserved", 1)):
+                       ("num_heads", 0), ("variant", 7), ("num_splits", -1), ("flags", 64), ("reserved", 1),
+                       ("flags", 2)):   # lazy rescale exists only in the assembly kernels
         d = amla.make_desc(2, 1, 16, 8, 4)
         setattr(d, field, val)
         assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED, field
@@ -61,6 +62,12 @@ def test_argument_validation_error_codes(amla):
     split.workspace = 4096
     split.workspace_bytes = amla.amla_workspace_bytes(split) - 1
     assert _call(amla, split) == amla.AMLA_ERR_WORKSPACE                 # too small
+
+
+def test_assembly_kernels_are_gated_off(amla, monkeypatch):
+    monkeypatch.delenv("AMLA_ENABLE_ASM_KERNELS", raising=False)
+    d = amla.make_desc(2, 1, 16, 8, 4, flags=amla.AMLA_FLAG_ASM_KERNEL)
+    assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
 
 
 def test_workspace_and_split_queries(amla):

@@ -7,6 +7,8 @@ One exception, derived from the output format: a bf16 value in [4, 8) has a spac
 Where |exact| >= 4 (a handful of elements of the long-context configuration, whose peaked
 softmax returns single value rows) the bound is that half-ulp plus 6e-3 for the bf16
 rounding of the softmax weights; everywhere else it is the flat 1e-2."""
+import os
+
 import numpy as np
 import pytest
 
@@ -57,7 +59,25 @@ def check(out, lse, want, want_lse, what):
     return eo, el
 
 
-VARIANTS = [0, 1]
+# (rescale variant, flags).  The compiler-built HIP kernel is the path that runs by default.
+# The hand-scheduled assembly kernels are switched off in the library: their first run on the
+# GPU faulted (missing wait state before v_readfirstlane, fixed in the generator since, but the
+# fix has not been run on hardware).  Their cases stay here, skipped, until the library gate
+# (environment variable AMLA_ENABLE_ASM_KERNELS=1) is opened for the run that tests the fix.
+MUL, ADD, NO_SKIP, LAZY, ASM = 0, 1, 1, 2, 4
+ASM_ON = os.environ.get("AMLA_ENABLE_ASM_KERNELS") == "1"
+asm_off = pytest.mark.skipif(not ASM_ON, reason="assembly kernels switched off: faulted the GPU on their "
+                             "first run; fix (wait state before v_readfirstlane) not yet run on hardware")
+VARIANTS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"),
+            pytest.param((MUL, ASM), id="mul_asm", marks=asm_off),
+            pytest.param((ADD, ASM), id="add_asm", marks=asm_off),
+            pytest.param((MUL, ASM | LAZY), id="mul_asm_lazy", marks=asm_off),
+            pytest.param((ADD, ASM | LAZY), id="add_asm_lazy", marks=asm_off)]
+ALL = [(MUL, 0), (ADD, 0)] + ([(MUL, ASM), (ADD, ASM), (MUL, ASM | LAZY), (ADD, ASM | LAZY)] if ASM_ON else [])
+
+
+def kw_of(v):
+    return dict(variant=v[0], flags=v[1])
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -65,7 +85,7 @@ def test_tiny_config(env, variant):
     torch, orc, amla, wl = env
     case = wl.make_config(0)
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), **kw_of(variant))
     check(out, lse, want, want_lse, f"tiny v{variant}")
 
 
@@ -85,7 +105,7 @@ def test_small_cases(env, name, kw, splits, variant):
     torch, orc, amla, wl = env
     case = wl.make_case(name, 21, spare_frac=0.25, **kw)
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant, num_splits=splits)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), num_splits=splits, **kw_of(variant))
     check(out, lse, want, want_lse, f"{name} splits={splits} v{variant}")
     empty = np.asarray(kw["seqlens"]) == 0
     assert np.all(out[empty] == 0)
@@ -99,7 +119,7 @@ def test_wide_logits_many_max_updates(env, variant, sigma):
     torch, orc, amla, wl = env
     case = wl.make_case("wide", 22, batch=2, s_q=2, heads=64, seqlens=[3000, 4500], q_sigma=sigma)
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), **kw_of(variant))
     # A peaked softmax returns single value rows, |out| up to ~4.5 here, where rounding the
     # output to bf16 alone costs up to 2^-9 * 2^ceil(log2 |out|) = 1.6e-2: allow that
     # half-ulp on top of 6e-3 for the arithmetic instead of the flat 1e-2.
@@ -116,10 +136,10 @@ def test_no_skip_flag_keeps_parity(env, variant):
     case = wl.make_case("noskip", 23, batch=2, s_q=1, heads=128, seqlens=[1500, 640], q_sigma=2.0)
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
     dev = to_dev(torch, case)
-    o1, l1 = run_gpu(torch, amla, case, dev, variant=variant)
-    o2, l2 = run_gpu(torch, amla, case, dev, variant=variant, flags=amla.AMLA_FLAG_NO_SKIP)
+    o1, l1 = run_gpu(torch, amla, case, dev, **kw_of(variant))
+    o2, l2 = run_gpu(torch, amla, case, dev, variant=variant[0], flags=variant[1] | amla.AMLA_FLAG_NO_SKIP)
     check(o2, l2, want, want_lse, f"noskip v{variant}")
-    if variant == 1:
+    if variant[0] == ADD:
         # the exponent add by 0 is the identity, so forcing it changes nothing at all
         assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
@@ -131,17 +151,18 @@ def test_zero_values_survive_the_exponent_add(env):
     case = wl.make_case("zeros", 24, batch=1, s_q=1, heads=128, seqlens=[4096], q_sigma=6.0)
     case.kv_bits[:, :, 100:200] = 0
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=1)
-    check(out, lse, want, want_lse, "zero columns ADD")
-    assert np.all(out[..., 100:200] == 0)
+    for v in [a for a in ALL if a[0] == ADD]:
+        out, lse = run_gpu(torch, amla, case, to_dev(torch, case), **kw_of(v))
+        check(out, lse, want, want_lse, f"zero columns {v}")
+        assert np.all(out[..., 100:200] == 0)
 
 
 def test_single_key_is_exact(env):
     torch, orc, amla, wl = env
     case = wl.make_case("one", 25, batch=2, s_q=1, heads=16, seqlens=[1, 1])
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    for variant in VARIANTS:
-        out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant)
+    for variant in ALL:
+        out, lse = run_gpu(torch, amla, case, to_dev(torch, case), **kw_of(variant))
         assert np.array_equal(out, want)            # the bf16 value row itself
         assert np.abs(lse - want_lse).max() <= 1e-4
 
@@ -156,9 +177,9 @@ def test_permuted_pages_give_identical_bits(env):
     import copy
     case2 = copy.copy(case)
     case2.kv_bits, case2.block_table = kv2, tab2
-    for variant in VARIANTS:
-        o1, l1 = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant)
-        o2, l2 = run_gpu(torch, amla, case2, to_dev(torch, case2), variant=variant)
+    for variant in ALL:
+        o1, l1 = run_gpu(torch, amla, case, to_dev(torch, case), **kw_of(variant))
+        o2, l2 = run_gpu(torch, amla, case2, to_dev(torch, case2), **kw_of(variant))
         assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
@@ -166,9 +187,9 @@ def test_splits_agree_with_each_other(env):
     torch, orc, amla, wl = env
     case = wl.make_case("splits", 27, batch=3, s_q=1, heads=128, seqlens=[4096, 100, 2500])
     dev = to_dev(torch, case)
-    base_o, base_l = run_gpu(torch, amla, case, dev, variant=1, num_splits=1)
+    base_o, base_l = run_gpu(torch, amla, case, dev, variant=ADD, num_splits=1)
     for ns in (2, 5, 16, 64):
-        o, l = run_gpu(torch, amla, case, dev, variant=1, num_splits=ns)
+        o, l = run_gpu(torch, amla, case, dev, variant=ADD, num_splits=ns)
         assert np.abs(o - base_o).max() <= 2 ** -7 * max(1.0, np.abs(base_o).max())   # one bf16 ulp
         assert np.abs(l - base_l).max() <= 1e-5
 
@@ -202,25 +223,25 @@ def test_full_size_configs_all_rows(env, index):
           f"sum kv_len={case.total_kv}", flush=True)
     dev = to_dev(torch, case)
     results = {}
-    for variant in VARIANTS:
-        results[variant] = run_gpu(torch, amla, case, dev, variant=variant)
+    for variant in ALL:
+        results[variant] = run_gpu(torch, amla, case, dev, **kw_of(variant))
     # oracle one sequence at a time to bound host memory
-    worst = {v: [0.0, 0.0] for v in VARIANTS}
+    worst = {v: [0.0, 0.0] for v in ALL}
     big = 0
-    fro_num = {v: 0.0 for v in VARIANTS}
+    fro_num = {v: 0.0 for v in ALL}
     fro_den = 0.0
     for b in range(case.batch):
         want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens,
                                     case.softmax_scale, seq_ids=[b])
         fro_den += float((want[b] ** 2).sum())
         big += int(np.sum(np.abs(want[b]) >= 4.0))
-        for v in VARIANTS:
+        for v in ALL:
             out, lse = results[v]
             assert np.all(np.abs(out[b] - want[b]) <= out_tolerance(want[b])), (index, b, v)
             worst[v][0] = max(worst[v][0], float(np.abs(out[b] - want[b]).max()))
             worst[v][1] = max(worst[v][1], float(np.abs(lse[b] - want_lse[b]).max()))
             fro_num[v] += float(((out[b] - want[b]) ** 2).sum())
-    for v in VARIANTS:
+    for v in ALL:
         E = (fro_num[v] / fro_den) ** 0.5
         print(f"  variant {v}: max|out err| {worst[v][0]:.3e} max|lse err| {worst[v][1]:.3e} "
               f"rel Frobenius {E:.3e}", flush=True)
