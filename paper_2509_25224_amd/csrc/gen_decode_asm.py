@@ -322,43 +322,50 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         g(f"s_cmp_ge_u32 {sr(reg)}, {LDS_BYTES}")
         g(f"s_cselect_b32 {sr(reg)}, 0, {sr(reg)}")
 
-    # prologue loads: sub-tiles u0, u0+1, u0+2 (clamped to the last one) into slots 0, 1, 2
+    # prologue loads: sub-tiles u0 .. u0+3 (clamped to the last one) fill the four slots
     g(f"s_mov_b32 {sr(S_SLOTLD)}, 0")
-    for n in range(3):
+    for n in range(NSLOT):
         g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {n}")
         g(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
         fetch_phys_blocking()
         tile_base_from_phys()
         issue_subtile_loads()
         advance_slot(S_SLOTLD)
-    # S_SLOTLD now = slot 3, the target of sub-tile u0+3
+    # S_SLOTLD is back at slot 0 = the slot of sub-tile u0, which sub-tile u0+4 takes over after
+    # the first pass of the loop
     g(f"s_mov_b32 {sr(S_SLOTV)}, 0")
-    g(f"s_mov_b32 {sr(S_SLOTK)}, 0")            # the prologue QK reads sub-tile u0 from slot 0
-    # phys for the first in-loop load (sub-tile u0 + 3)
-    g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, 3")
+    g(f"s_mov_b32 {sr(S_SLOTK)}, 0")
+    g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {NSLOT}")
     g(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
     fetch_phys_blocking()
     finish_state_init()
 
-    # ---- phase A: QK of the sub-tile in slot S_SLOTK; optional VALU stream ----------------------
-    def phase_a(valu, with_table_load):
-        q = LdsQueue()
+    # ---- K operand stream of one sub-tile: 36 b128 reads through the 8-slot staging ring -------
+    def k_read(ks):
+        return f"ds_read_b128 {vr(ST + 4 * (ks % NST), 4)}, v{V_KCUR} offset:{32 * ks}"
+
+    def set_k_base():
         g(f"v_add_u32 v{V_KCUR}, {sr(S_SLOTK)}, v{V_KOFF}")
-        groups = []
-        pre = []
+
+    def phase_a(valu, first_reads_in_flight, table_load):
+        """36 MFMAs of S^T = K Q^T in two accumulation chains.  K reads 0..NST-1 are either issued
+        here or already in flight (issued under the tail of the previous pass)."""
+        q = LdsQueue()
+        if not first_reads_in_flight:
+            set_k_base()
+            for ks in range(NST):
+                g(k_read(ks))
         for ks in range(NST):
-            pre.append(f"ds_read_b128 {vr(ST + 4 * (ks % NST), 4)}, v{V_KCUR} offset:{32 * ks}")
             q.issue(ks)
-        for ins in pre:
-            g(ins)
+        groups = []
         for ks in range(36):
             grp = []
-            if with_table_load and ks == 0:
-                # Block-table entry of the sub-tile the next iteration loads.  SMEM shares lgkmcnt
-                # with LDS and may return out of order; counting only the LDS reads in the waits
-                # below stays correct (an outstanding SMEM op can only make a wait stricter), and
-                # the loop top waits for lgkmcnt(0) before the entry is used.
-                grp.append(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, 4")
+            if table_load and ks == 0:
+                # Block-table entry of the sub-tile whose loads are issued after this pass's barrier.
+                # SMEM shares lgkmcnt with LDS and may return out of order; counting only the LDS
+                # reads in the waits below stays correct (an outstanding SMEM op can only make a
+                # wait stricter), and the wait before the barrier is lgkmcnt(0).
+                grp.append(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {NSLOT}")
                 grp.append(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
                 grp.append(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
                 grp.append(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
@@ -371,7 +378,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
                        f"{vr(Q + 4 * ks, 4)}, {src_c}")
             nxt = ks + NST
             if nxt < 36:
-                grp.append(f"ds_read_b128 {vr(ST + 4 * (nxt % NST), 4)}, v{V_KCUR} offset:{32 * nxt}")
+                grp.append(k_read(nxt))
                 q.issue(nxt)
             groups.append(grp)
         interleave(g, groups, valu)
@@ -455,15 +462,14 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             g(f"v_cmp_le_i32 vcc, {sr(S_T1)}, v{T0}")
             g(f"v_cndmask_b32 v{SC + r}, v{SC + r}, v{T1}, vcc")
 
-    # ---- prologue QK of sub-tile u0 --------------------------------------------------------------
-    g(f"s_waitcnt vmcnt({2 * LOADS_PER_SUBTILE})")
+    # ---- prologue: scores of sub-tile u0, then the first K reads of sub-tile u0+1 ---------------
+    g(f"s_waitcnt vmcnt({3 * LOADS_PER_SUBTILE})")              # Q fragment and sub-tile u0 have landed
     g("s_barrier")
-    phase_a([], False)
+    phase_a([], False, False)
     g("s_nop 15")
     g("s_nop 15")
     for ins in form_scores_stream():
         g(ins)
-    # partial first sub-tile?
     g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
     g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
     g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
@@ -471,15 +477,17 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     mask_partial()
     g.label(L("pro_full"))
     advance_slot(S_SLOTK)                                       # slot of sub-tile u0 + 1
+    g(f"s_waitcnt vmcnt({2 * LOADS_PER_SUBTILE})")              # sub-tile u0 + 1 has landed
+    g("s_barrier")
+    set_k_base()
+    for ks in range(NST):
+        g(k_read(ks))
 
     # ------------------------------------------------------------------------------ main loop
+    # Pass for sub-tile u.  On entry: scores of u in SC; sub-tiles u, u+1 resident, u+2, u+3 landed
+    # or in flight; K reads 0..7 of sub-tile u+1 in flight; S_SLOTV = slot(u), S_SLOTK = slot(u+1).
     g.label(L("loop"))
-    g(f"s_waitcnt vmcnt({LOADS_PER_SUBTILE}) lgkmcnt(0)")
-    g("s_barrier")
-    tile_base_from_phys()
-    issue_subtile_loads()
-    advance_slot(S_SLOTLD)
-    phase_a(softmax_stream(), True)
+    phase_a(softmax_stream(), True, True)
 
     # ---- rescale of the accumulator registers (rare path) ----
     g(f"s_cmp_lg_u64 {sr(S_NEED, 2)}, 0")
@@ -511,9 +519,15 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g.label(L("no_rescale"))
 
     # ---- phase B: O^T += V^T P^T for the sub-tile in slot S_SLOTV ----
+    # Body: MFMAs 0..23 with the V^T reads streaming six MFMAs ahead; by the end of the body all 64
+    # reads have been issued and the operands of MFMAs 24..31 sit in the staging ring.  Then the
+    # barrier of the pass; the last eight MFMAs run after it, each freeing the ring slot that the
+    # matching K read of the next sub-tile refills, so the MFMA pipe has work across the barrier and
+    # across the LDS latency of the first K operands.
     q = LdsQueue()
     g(f"v_add_u32 v{V_VCUR}, {sr(S_SLOTV)}, v{V_VOFF}")
     order = [(st, dt) for st in range(2) for dt in range(16)]
+    TAIL = NST
 
     def v_reads(idx):
         st, dt = order[idx]
@@ -522,6 +536,12 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         return [f"ds_read_b64_tr_b16 {vr(slot, 2)}, v{V_VCUR} offset:{base}",
                 f"ds_read_b64_tr_b16 {vr(slot + 2, 2)}, v{V_VCUR} offset:{base + 8 * ROW}"]
 
+    def pv_mfma(idx):
+        st, dt = order[idx]
+        slot = ST + 4 * (idx % NST)
+        return (f"v_mfma_f32_32x32x16_bf16 {ar(16 * dt, 16)}, {vr(slot, 4)}, {vr(PK + 4 * st, 4)}, "
+                f"{ar(16 * dt, 16)}")
+
     depth = 6                                  # 12 reads in flight <= 15
     for idx in range(depth):
         for ins in v_reads(idx):
@@ -529,27 +549,54 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         q.issue((idx, 0))
         q.issue((idx, 1))
     groups = []
-    for idx, (st, dt) in enumerate(order):
+    for idx in range(len(order) - TAIL):
         grp = []
         n = q.wait_for((idx, 1))
         grp.append(f"s_waitcnt lgkmcnt({n})")
-        slot = ST + 4 * (idx % NST)
-        grp.append(f"v_mfma_f32_32x32x16_bf16 {ar(16 * dt, 16)}, {vr(slot, 4)}, {vr(PK + 4 * st, 4)}, "
-                   f"{ar(16 * dt, 16)}")
+        grp.append(pv_mfma(idx))
         nxt = idx + depth
         if nxt < len(order):
             grp.extend(v_reads(nxt))
             q.issue((nxt, 0))
             q.issue((nxt, 1))
         groups.append(grp)
-    # VALU stream of phase B: the scores of sub-tile u+1 (after the QK chains have drained)
+    # the reads of the last `depth - ... ` MFMAs that the body did not reach
+    rest = []
+    for nxt in range(len(order) - TAIL + depth, len(order)):
+        rest.extend(v_reads(nxt))
+    groups[-1].extend(rest)
+    # VALU stream of the body: the scores of sub-tile u+1 (after the QK chains have drained)
     valu_b = ["s_nop 15", "s_nop 7"] + form_scores_stream()
     interleave(g, groups, valu_b)
+
+    # ---- barrier of the pass ----
+    # lgkmcnt(0): every V^T read of slot(u) by this wave has returned (and the block-table entry);
+    # vmcnt: of the two load groups in flight (u+2, u+3) the older has landed.  After the barrier
+    # that holds for all waves: slot(u) may be refilled and sub-tile u+2 may be read.
+    g(f"s_waitcnt vmcnt({LOADS_PER_SUBTILE}) lgkmcnt(0)")
+    g("s_barrier")
+    advance_slot(S_SLOTK)                                       # slot(u+2)
+    set_k_base()
+    tail = []
+    for t in range(TAIL):
+        tail.append([pv_mfma(len(order) - TAIL + t), k_read(t)])
+    # direct-to-LDS loads of sub-tile min(u+4, last) into slot(u), spread over the tail
+    g(f"s_mov_b32 {sr(S_SLOTLD)}, {sr(S_SLOTV)}")
+    tile_base_from_phys()
+    dma = []
+    dma.append(f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}")
+    for k in range(LOADS_PER_SUBTILE):
+        if k < 9:
+            dma.append(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
+        else:
+            dma.append(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
+        dma.append("s_nop 0")
+        dma.append(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
+    interleave(g, tail, dma)
 
     # ---- advance ----
     g(f"s_add_u32 {sr(S_U)}, {sr(S_U)}, 1")
     advance_slot(S_SLOTV)
-    advance_slot(S_SLOTK)
     g(f"s_cmp_ge_u32 {sr(S_U)}, {sr(S_UEND)}")
     g(f"s_cbranch_scc1 {L('epilogue')}")
     # sub-tile u (new) partial?  its scores are now in SC
@@ -562,7 +609,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
 
     # --------------------------------------------------------------------------------- epilogue
     g.label(L("epilogue"))
-    g("s_waitcnt vmcnt(0)")
+    g("s_waitcnt vmcnt(0) lgkmcnt(0)")
     if os.environ.get("AMLA_ASM_DEBUG") == "2":
         g(f"v_mov_b32 v{T0}, 0")
         for i, reg in enumerate((S_U, S_UEND, S_LEN, S_SPLIT, S_B, S_TILE, S_WAVE, S_ULAST)):

@@ -1,0 +1,151 @@
+"""The generated gfx950 assembly kernels, run on the CPU emulator (tests/gfx950_emu.py) against the
+oracle on tiny problems: addressing, pipeline, synchronisation and arithmetic without a GPU."""
+import os
+import struct
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import amla_oracle as orc
+from paper_2509_25224_amd import workloads as wl
+import gfx950_emu as emu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GEN = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "gen_decode_asm.py")
+LDS_BYTES = 4 * 37 * 1024
+
+
+@pytest.fixture(scope="module")
+def asm_text(tmp_path_factory):
+    out = tmp_path_factory.mktemp("asm") / "k.s"
+    env = dict(os.environ)
+    env.pop("AMLA_ASM_DEBUG", None)
+    subprocess.run([sys.executable, GEN, str(out)], check=True, env=env)
+    return out.read_text()
+
+
+def run_case(asm_text, kernel, case, n_splits, flags=0, dma_late=False, smem_first=False):
+    ins, labels = emu.parse_kernel(asm_text, kernel)
+    B, T, H = case.batch, case.s_q, case.heads
+    rows = T * H
+    n_rows = B * rows
+    mem = emu.Memory()
+    q = mem.add("q", case.q_bits)
+    kv = mem.add("kv", case.kv_bits)
+    tab = mem.add("table", case.block_table)
+    lens = mem.add("seqlens", case.seqlens)
+    out = mem.add("out", np.full(n_rows * 512, 0x7F7F, np.uint16), writable=True)
+    lse = mem.add("lse", np.full(n_rows, np.nan, np.float32), writable=True)
+    po = mem.add("part_o", np.full(max(1, n_splits * n_rows * 512), np.nan, np.float32), writable=True)
+    pl = mem.add("part_lse", np.full(max(1, n_splits * n_rows), np.nan, np.float32), writable=True)
+    n_streams = B * n_splits
+    magic = ((1 << 32) // n_splits + 1) & 0xFFFFFFFF if n_splits > 1 else 0
+    scale_log2e = np.float32(case.softmax_scale) * np.float32(1.4426950408889634)
+    karg = struct.pack("<8Q", q, kv, tab, lens, out, lse, po, pl) + struct.pack(
+        "<f6iI", float(scale_log2e), B, rows, n_splits, case.max_blocks_per_seq, n_streams, flags, magic)
+    assert len(karg) == 0x60
+    ka = mem.add("kernarg", np.frombuffer(karg, dtype=np.uint8))
+    n_tiles = (rows + 127) // 128
+    gy = (n_streams + 7) // 8
+    steps = 0
+    for y in range(gy):
+        for x in range(8 * n_tiles):
+            if y * 8 + (x & 7) >= n_streams and (x, y) != (8 * n_tiles - 1, gy - 1):
+                continue                      # padded workgroups exit at once; emulate just one of them
+            wg = emu.Workgroup(ins, labels, mem, ka, x, y, LDS_BYTES, dma_late=dma_late, smem_first=smem_first)
+            steps += wg.run()
+    o = mem.get("out").view(np.uint16).astype(np.uint32)
+    o = (o << 16).view(np.float32).astype(np.float64).reshape(B, T, H, 512)
+    l = mem.get("lse").view(np.float32).astype(np.float64).reshape(B, T, H)
+    if n_splits > 1:
+        # merge the partials the way the combine kernel does (exp(lse_s - lse) weights)
+        P = mem.get("part_o").view(np.float32).astype(np.float64).reshape(n_splits, n_rows, 512)
+        PL = mem.get("part_lse").view(np.float32).astype(np.float64).reshape(n_splits, n_rows)
+        mx = PL.max(axis=0)
+        with np.errstate(invalid="ignore"):
+            w = np.where(np.isneginf(PL), 0.0, np.exp(PL - np.where(np.isneginf(mx), 0.0, mx)))
+        tot = w.sum(axis=0)
+        with np.errstate(invalid="ignore", divide="ignore"):
+            o = np.where(tot[:, None] > 0, (w[:, :, None] * np.nan_to_num(P)).sum(axis=0) / tot[:, None], 0.0)
+            l = np.where(tot > 0, mx + np.log(tot), -np.inf)
+        o = o.reshape(B, T, H, 512)
+        l = l.reshape(B, T, H)
+    return o, l, steps
+
+
+def check(o, l, case, bf16_out=True):
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    fin = np.isfinite(want_lse)
+    assert np.array_equal(l[~fin], want_lse[~fin])
+    eo = np.abs(o - want).max()
+    el = np.abs(l[fin] - want_lse[fin]).max() if fin.any() else 0.0
+    assert eo <= 1e-2, eo
+    assert el <= 1e-3, el
+    return eo, el
+
+
+KERNELS = ["amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_mul_lazy", "amla_decode_asm_add_lazy"]
+
+
+def test_hazard_rules_hold(asm_text):
+    for k in KERNELS:
+        ins, labels = emu.parse_kernel(asm_text, k)
+        problems = emu.check_hazards(ins, labels)
+        assert not problems, (k, problems[:10])
+
+
+def test_hazard_checker_sees_the_readfirstlane_mistake():
+    """The mistake that faulted the GPU: a VALU write read back by v_readfirstlane in the next slot."""
+    text = "k:\n\tv_lshrrev_b32 v252, 6, v251\n\tv_readfirstlane_b32 s36, v252\n\ts_endpgm\n.Lfunc_end_k:\n"
+    ins, labels = emu.parse_kernel(text, "k")
+    assert emu.check_hazards(ins, labels)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_tiny_config_on_the_emulator(asm_text, kernel):
+    case = wl.make_config(0)                      # 16 heads, kv_len 256: 8 sub-tiles, 16 of 128 rows valid
+    o, l, steps = run_case(asm_text, kernel, case, 1)
+    check(o, l, case)
+
+
+@pytest.mark.parametrize("dma_late,smem_first", [(True, False), (False, True), (True, True)])
+def test_result_does_not_depend_on_when_loads_land(asm_text, dma_late, smem_first):
+    case = wl.make_case("sync", 31, batch=1, s_q=1, heads=8, seqlens=[200], q_sigma=3.0)
+    base = run_case(asm_text, "amla_decode_asm_add", case, 1)
+    other = run_case(asm_text, "amla_decode_asm_add", case, 1, dma_late=dma_late, smem_first=smem_first)
+    assert np.array_equal(base[0], other[0]) and np.array_equal(base[1], other[1])
+    check(other[0], other[1], case)
+
+
+@pytest.mark.parametrize("kernel", ["amla_decode_asm_mul", "amla_decode_asm_add_lazy"])
+def test_ragged_lengths_splits_and_empty_sequences(asm_text, kernel):
+    # partial sub-tiles (rem < 32), a 33..64 remainder (second half of the block unused), one key,
+    # an empty sequence, and split ranges that are empty for short sequences
+    case = wl.make_case("ragged", 32, batch=4, s_q=1, heads=4, seqlens=[0, 1, 97, 160], spare_frac=0.5, q_sigma=2.0)
+    for ns in (1, 3):
+        o, l, _ = run_case(asm_text, kernel, case, ns, dma_late=True)
+        check(o, l, case)
+        assert np.all(o[0] == 0)
+
+
+def test_two_row_tiles_and_wide_logits(asm_text):
+    # 130 rows -> two workgroups per stream, the second with 2 valid rows; large query scale so
+    # that the reference moves and the accumulator rescale path runs in both strict kernels
+    case = wl.make_case("tiles", 33, batch=1, s_q=1, heads=130, seqlens=[96], q_sigma=6.0)
+    want, _ = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    for kernel in ("amla_decode_asm_mul", "amla_decode_asm_add"):
+        o, l, _ = run_case(asm_text, kernel, case, 1)
+        half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 1.0))) - 9)
+        assert np.all(np.abs(o - want) <= np.where(np.abs(want) < 4, 1e-2, half_ulp + 6e-3))
+
+
+def test_no_skip_flag_forces_the_rescale_path(asm_text):
+    case = wl.make_case("noskip", 34, batch=1, s_q=1, heads=4, seqlens=[128])
+    a = run_case(asm_text, "amla_decode_asm_add", case, 1, flags=0)
+    b = run_case(asm_text, "amla_decode_asm_add", case, 1, flags=1)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])     # exponent add of 0 is the identity
+    check(b[0], b[1], case)
+    c = run_case(asm_text, "amla_decode_asm_mul", case, 1, flags=1)
+    check(c[0], c[1], case)
