@@ -34,7 +34,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
-    ap.add_argument("--variant", choices=["add", "mul"], default="add")
+    ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy"], default="auto",
+                    help="auto = add_lazy if its output agrees with the strict add variant on this input, else add")
     ap.add_argument("--splits", type=int, default=0, help="split-KV factor, 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ab", action="store_true", help="skip the ADD-vs-MUL side-by-side timing")
@@ -107,13 +108,34 @@ def main():
     ws_bytes = amla.amla_workspace_bytes(desc)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
-    def step(variant):
-        amla.amla_decode(q, kv, tab, lens, case.softmax_scale, out, lse, variant=variant,
+    VARIANTS = {"mul": (amla.AMLA_RESCALE_MUL, 0), "add": (amla.AMLA_RESCALE_ADD, 0),
+                "mul_lazy": (amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE),
+                "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE)}
+
+    def step(name, o=out, l=lse):
+        v, f = VARIANTS[name]
+        amla.amla_decode(q, kv, tab, lens, case.softmax_scale, o, l, variant=v, flags=f,
                          num_splits=args.splits, workspace=ws)
 
-    main_variant = amla.AMLA_RESCALE_ADD if args.variant == "add" else amla.AMLA_RESCALE_MUL
+    # The strict add variant is the one checked against the oracle on every row of this workload
+    # by the GPU tests.  The lazy variant becomes the headline only if, on this very input, its
+    # output stays within one bf16 step of the strict one and its lse within 1e-4.
+    chosen, self_check = args.variant, None
+    if args.variant == "auto":
+        o2 = torch.empty_like(out)
+        l2 = torch.empty_like(lse)
+        step("add")
+        step("add_lazy", o2, l2)
+        torch.cuda.synchronize()
+        a, b = out.float(), o2.float()
+        d_out = float(((a - b).abs() / a.abs().clamp(min=1.0)).max())
+        d_lse = float((lse - l2).abs().max())
+        ok = d_out <= 2.0 ** -7 and d_lse <= 1e-4
+        chosen = "add_lazy" if ok else "add"
+        self_check = {"max_rel_out_diff_vs_strict": d_out, "max_lse_diff_vs_strict": d_lse, "passed": ok}
+        del o2, l2
     torch.cuda.synchronize()
-    total_ms, per = time_steps(torch, lambda: step(main_variant), args.steps, args.warmup)
+    total_ms, per = time_steps(torch, lambda: step(chosen), args.steps, args.warmup)
     torch.cuda.synchronize()
 
     flops = acc.decode_flops(case.heads, case.s_q, case.total_kv)
@@ -130,7 +152,7 @@ def main():
         "config": {"workload": f"configs[{args.config}] {case.name}: batch {case.batch}, s_q {case.s_q}, "
                                f"{case.heads} heads, sum kv_len {case.total_kv}, paged bf16 latent cache "
                                f"(block 64, permuted table), d_qk 576 / d_v 512",
-                   "variant": args.variant, "kv_splits": splits, "seed": case.seed},
+                   "variant": chosen, "kv_splits": splits, "seed": case.seed},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
@@ -139,14 +161,21 @@ def main():
                      "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
     }
 
+    if self_check is not None:
+        result["config"]["lazy_self_check"] = self_check
     if not args.no_ab:
         ab = {}
-        for name, v in (("mul", amla.AMLA_RESCALE_MUL), ("add", amla.AMLA_RESCALE_ADD)) * 2:
-            t, _ = time_steps(torch, lambda: step(v), args.steps, 2)
+        for name in ("mul", "add", "mul_lazy", "add_lazy") * 2:
+            t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
             ab.setdefault(name, []).append(t / args.steps)
-        add_ms, mul_ms = min(ab["add"]), min(ab["mul"])
-        result["rescale"] = {"add_ms": add_ms, "mul_ms": mul_ms, "add_over_mul_speedup": mul_ms / add_ms,
-                             "note": "interleaved runs, best of 2 per variant, same binary"}
+        best = {k: min(v) for k, v in ab.items()}
+        result["rescale"] = {"add_ms": best["add"], "mul_ms": best["mul"], "add_lazy_ms": best["add_lazy"],
+                             "mul_lazy_ms": best["mul_lazy"],
+                             "add_over_mul_speedup": best["mul"] / best["add"],
+                             "add_lazy_over_mul_lazy_speedup": best["mul_lazy"] / best["add_lazy"],
+                             "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in best.items()},
+                             "note": "interleaved runs, best of 2 per variant, same binary; strict = reference "
+                                     "moves with every new row max, lazy = only past 2^8"}
 
     if not args.no_cpu_baseline:
         per_seq = [acc.decode_flops(case.heads, case.s_q, int(L)) for L in case.seqlens]

@@ -54,7 +54,7 @@ enum {
                                    exceeds it by more than 2^8; in between the softmax weights may
                                    grow up to 2^8 (same relative precision in bf16 and FP32), so the
                                    accumulator rescale becomes a rare event.  Same result up to
-                                   rounding.  Only with AMLA_FLAG_ASM_KERNEL. */
+                                   rounding. */
   AMLA_FLAG_ASM_KERNEL = 4      /* run the hand-scheduled assembly kernels (32-key steps, explicit
                                    MFMA / VALU / LDS interleave) instead of the compiler-built HIP
                                    kernel (64-key steps).  SWITCHED OFF: rejected with

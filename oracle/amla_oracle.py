@@ -206,10 +206,12 @@ def _round_bf16(x32: np.ndarray) -> np.ndarray:
     return r.view(np.float32)
 
 
-def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30):
+def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None):
     """Q, K, V are float32 arrays holding bf16-exact values.  Uses base-2 exponentials
     (t = s * scale * log2 e), mu_i = rint(max t) (= -n_i), P = 2^(t - mu_i) rounded to BF16
-    for the PV product, FP32 row sum for l, exponent add for the rescale."""
+    for the PV product, FP32 row sum for l, exponent add for the rescale.  With
+    `lazy_threshold` the reference mu is only moved when the row max exceeds it by more than
+    that many base-2 units (the weights may then grow up to 2^threshold)."""
     f32 = np.float32
     G, L = Q.shape[0], K.shape[0]
     O = np.zeros((G, V.shape[1]), dtype=f32)
@@ -222,6 +224,8 @@ def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30):
         t = (Q @ Kb.T).astype(f32) * c
         m = np.maximum(m, t.max(axis=1))
         mu_new = np.rint(m)
+        if lazy_threshold is not None and mu is not None:
+            mu_new = np.where(m > mu + lazy_threshold, mu_new, mu)
         P = np.exp2((t - mu_new[:, None]).astype(f32)).astype(f32)
         if mu is not None:
             d = np.maximum(mu - mu_new, clamp).astype(np.int64)      # <= 0

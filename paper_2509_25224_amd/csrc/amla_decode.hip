@@ -118,7 +118,9 @@ __device__ __forceinline__ void issue_tile_loads(const uint8_t* block_base, LDS_
   }
 }
 
-template <int VARIANT>
+constexpr float kLazyThreshold = 8.f;   // base-2 units: the weights may grow to 2^8 before the reference moves
+
+template <int VARIANT, bool LAZY>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void amla_decode_kernel(const DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
@@ -232,11 +234,12 @@ void amla_decode_kernel(const DecodeParams p) {
     float ref_new;
     float alpha = 1.f;   // MUL: factor on the old accumulator
     int n23 = 0;         // ADD: (n_i - n_{i-1}) << 23, <= 0
+    ref_new = VARIANT == AMLA_RESCALE_MUL ? m_new : __builtin_rintf(m_new);
+    // lazy: keep the old reference (factor 1, shift 0) until the row max exceeds it by 2^8
+    if (LAZY && !first && !(m_new > ref + kLazyThreshold)) ref_new = ref;
     if (VARIANT == AMLA_RESCALE_MUL) {
-      ref_new = m_new;
       if (!first) alpha = fast_exp2(ref - ref_new);
     } else {
-      ref_new = __builtin_rintf(m_new);
       if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
     }
     m_run = m_new;
@@ -435,7 +438,6 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL)) != 0) return false;
-  if ((d->flags & AMLA_FLAG_LAZY_RESCALE) && !(d->flags & AMLA_FLAG_ASM_KERNEL)) return false;
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
@@ -515,8 +517,10 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
   if (!(desc->flags & AMLA_FLAG_ASM_KERNEL)) {
     const long long grid = streams_pad * p.n_tiles;
     if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
-    auto kern = desc->variant == AMLA_RESCALE_ADD ? amla_decode_kernel<AMLA_RESCALE_ADD>
-                                                  : amla_decode_kernel<AMLA_RESCALE_MUL>;
+    const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
+    auto kern = desc->variant == AMLA_RESCALE_ADD
+                    ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
+                    : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kLdsBytes) != hipSuccess) {
       (void)hipGetLastError();
