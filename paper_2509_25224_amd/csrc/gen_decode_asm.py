@@ -131,13 +131,14 @@ class LdsQueue:
         return n
 
 
-def interleave(g, groups, valu, tail_first=0):
-    """Emit MFMA groups with the VALU stream spread between them, both in their own order."""
+def interleave(g, groups, valu, first_group=0):
+    """Emit MFMA groups with the VALU stream spread between them, both in their own order.  The
+    VALU stream starts after group `first_group`."""
     n = len(groups)
     per = [0] * n
     m = len(valu)
     for i in range(m):
-        per[(i * n) // m if m else 0] += 1
+        per[first_group + (i * (n - first_group)) // m] += 1
     vi = 0
     for gi, grp in enumerate(groups):
         for ins in grp:
@@ -392,9 +393,9 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             v.append(f"v_max3_f32 v{T0}, v{T0}, v{sc[i]}, v{sc[i + 1]}")
         v.append(f"v_max_f32 v{T0}, v{T0}, v{sc[15]}")
         v.append(f"v_mov_b32 v{T1}, v{T0}")
-        v.append("s_nop 1")
+        v.append("s_nop 3")
         v.append(f"v_permlane32_swap_b32 v{T0}, v{T1}")
-        v.append("s_nop 1")
+        v.append("s_nop 3")
         v.append(f"v_max_f32 v{T0}, v{T0}, v{T1}")
         v.append(f"v_mul_f32 v{T0}, {sr(S_C)}, v{T0}")
         v.append(f"v_max_f32 v{T0}, v{V_M}, v{T0}")                      # m_new
@@ -432,7 +433,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             v.append(f"v_cvt_pk_bf16_f32 v{PK + i}, v{sc[2 * i]}, v{sc[2 * i + 1]}")
         v.append(f"v_mov_b32 v{T3}, 0")
         for i in range(8):
-            v.append(f"v_dot2_f32_bf16 v{T3}, v{PK + i}, {sr(S_ONES)}, v{T3}")
+            v.append(f"v_dot2c_f32_bf16 v{T3}, {sr(S_ONES)}, v{PK + i}")      # T3 += lo + hi of the packed pair
         if rescale == "mul":
             v.append(f"v_fma_f32 v{V_L32}, v{V_L32}, v{V_FAC}, v{T2}")
             v.append(f"v_fma_f32 v{V_L16}, v{V_L16}, v{V_FAC}, v{T3}")
@@ -566,8 +567,9 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         rest.extend(v_reads(nxt))
     groups[-1].extend(rest)
     # VALU stream of the body: the scores of sub-tile u+1 (after the QK chains have drained)
-    valu_b = ["s_nop 15", "s_nop 7"] + form_scores_stream()
-    interleave(g, groups, valu_b)
+    # The adds read the results of the last QK MFMAs: they start four groups into the body, i.e.
+    # more than 30 issue slots after the last QK MFMA, instead of waiting in s_nop.
+    interleave(g, groups, form_scores_stream(), first_group=4)
 
     # ---- barrier of the pass ----
     # lgkmcnt(0): every V^T read of slot(u) by this wave has returned (and the block-table entry);
@@ -625,9 +627,9 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     # totals over the two lane halves
     for reg in (V_L32, V_L16):
         g(f"v_mov_b32 v{T1}, v{reg}")
-        g("s_nop 1")
+        g("s_nop 3")
         g(f"v_permlane32_swap_b32 v{reg}, v{T1}")
-        g("s_nop 1")
+        g("s_nop 3")
         g(f"v_add_f32 v{reg}, v{reg}, v{T1}")
     g(f"v_rcp_f32 v{T2}, v{V_L16}")
     g(f"v_cmp_lt_f32 vcc, 0, v{V_L16}")

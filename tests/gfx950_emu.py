@@ -715,6 +715,12 @@ class Wave:
                 lo, hi = f32_to_bf16(f32(V(ops[1]))), f32_to_bf16(f32(V(ops[2])))
                 self.vdst(ops[0], (lo | (hi << np.uint32(16))).astype(U32))
                 return nxt
+            if mnem == "v_dot2c_f32_bf16":
+                a, b, c = V(ops[1]), V(ops[2]), f32(V(ops[0])).astype(np.float64)
+                r = (bf16_to_f32(a & np.uint32(0xFFFF)).astype(np.float64) * bf16_to_f32(b & np.uint32(0xFFFF))
+                     + bf16_to_f32(a >> np.uint32(16)).astype(np.float64) * bf16_to_f32(b >> np.uint32(16)) + c)
+                self.vdst(ops[0], bits(r.astype(np.float32)))
+                return nxt
             if mnem == "v_dot2_f32_bf16":
                 a, b, c = V(ops[1]), V(ops[2]), f32(V(ops[3])).astype(np.float64)
                 r = (bf16_to_f32(a & np.uint32(0xFFFF)).astype(np.float64) * bf16_to_f32(b & np.uint32(0xFFFF))
@@ -813,6 +819,8 @@ def _dst_src(mnem, ops):
     if mnem == "v_permlane32_swap_b32":
         wr |= _regs_of(ops[1])
         start = 0
+    if mnem == "v_dot2c_f32_bf16":
+        start = 0
     rd = set()
     for o in ops[start:]:
         rd |= _regs_of(o)
@@ -820,49 +828,61 @@ def _dst_src(mnem, ops):
 
 
 def check_hazards(ins, labels):
-    """Returns a list of strings describing violated rules.  Wait states are counted as one per
-    instruction plus the count of `s_nop`; labels reset nothing (the straight-line distance is a
-    lower bound only for fall-through paths, and every rule's window here lies inside one)."""
+    """Returns a list of strings describing violated rules.  From every producer the following 40
+    issue slots are walked along the fall-through path and along every branch target (forward or
+    backward), counting one wait state per instruction plus the count of `s_nop`."""
     problems = []
+    WINDOW = 40
 
-    def states(i, j):
-        n = 0
-        for k in range(i + 1, j):
-            m, o, _ = ins[k]
-            n += (int(o[0], 0) + 1) if m == "s_nop" else 1
-        return n
+    def cost(k):
+        m, o, _ = ins[k]
+        return (int(o[0], 0) + 1) if m == "s_nop" else 1
 
-    for i, (m, ops, mods) in enumerate(ins):
-        wr, _ = _dst_src(m, ops)
-        if not wr:
-            continue
-        for j in range(i + 1, min(i + 40, len(ins))):
+    def visit(i, m, ops, wr, j, gap, seen):
+        """Walk consumers starting at instruction j, `gap` wait states after producer i."""
+        while j < len(ins) and gap < WINDOW and wr:
+            if (j, frozenset(wr)) in seen:
+                return
+            seen.add((j, frozenset(wr)))
             m2, ops2, _ = ins[j]
             wr2, rd2 = _dst_src(m2, ops2)
-            gap = states(i, j)
             hit = wr & rd2
             if hit:
-                if _is_valu(m) and m2 in ("v_readfirstlane_b32", "v_readlane_b32", "v_permlane32_swap_b32") and gap < 1:
+                if _is_valu(m) and m2 in ("v_readfirstlane_b32", "v_readlane_b32") and gap < 1:
                     problems.append(f"{i}:{m} -> {j}:{m2}: needs a wait state")
+                if _is_valu(m) and m2 == "v_permlane32_swap_b32" and gap < 2:
+                    problems.append(f"{i}:{m} -> {j}:{m2}: needs two wait states")
                 if m in TRANS and _is_valu(m2) and gap < 1:
                     problems.append(f"{i}:{m} -> {j}:{m2}: trans result used by the next VALU op")
                 if m.startswith("v_mfma") and not m2.startswith("v_mfma") and gap < 18:
                     problems.append(f"{i}:{m} -> {j}:{m2}: MFMA result read after {gap} wait states")
                 if m.startswith("v_mfma") and m2.startswith("v_mfma"):
-                    # only the accumulate-into-itself form is allowed back to back
-                    a2 = _regs_of(ops2[1]) | _regs_of(ops2[2])
+                    a2 = _regs_of(ops2[1]) | _regs_of(ops2[2])     # only accumulate-into-itself may follow closely
                     if wr & a2 and gap < 18:
                         problems.append(f"{i}:{m} -> {j}:{m2}: MFMA result used as A/B operand")
                 if _is_valu(m) and m2.startswith("v_mfma") and gap < 2:
                     problems.append(f"{i}:{m} -> {j}:{m2}: VALU result feeds MFMA after {gap} wait states")
-                if m.startswith("v_cmp") or m == "v_readfirstlane_b32":
-                    if m2.startswith("global_") and gap < 5 and any(k == "s" for k, _ in hit):
-                        problems.append(f"{i}:{m} -> {j}:{m2}: VALU-written SGPR used by VMEM")
-            if ops and ops[0] == "m0" and m.startswith("s_") and m2 == "global_load_lds_dwordx4" and gap < 1 and j == i + 1:
+                if (m.startswith("v_cmp") or m == "v_readfirstlane_b32") and m2.startswith("global_") and gap < 5 \
+                        and any(k == "s" for k, _ in hit):
+                    problems.append(f"{i}:{m} -> {j}:{m2}: VALU-written SGPR used by VMEM")
+            if ops and ops[0] == "m0" and m.startswith("s_") and m2 == "global_load_lds_dwordx4" and gap < 1:
                 problems.append(f"{i}:{m} -> {j}:{m2}: M0 write directly before LDS DMA")
-            if wr & wr2 and not hit:
-                # a later overwrite ends this producer's window for these registers
-                wr = wr - wr2
-                if not wr:
-                    break
-    return problems
+            wr = wr - wr2 if not hit else wr                       # a later overwrite ends the window
+            if m2 == "s_endpgm":
+                return
+            if m2 == "s_branch":
+                j = labels[ops2[0]]
+                gap += 1
+                continue
+            if m2.startswith("s_cbranch"):
+                visit(i, m, ops, set(wr), labels[ops2[0]], gap + 1, seen)
+            gap += cost(j)
+            j += 1
+
+    for i, (m, ops, mods) in enumerate(ins):
+        wr, _ = _dst_src(m, ops)
+        if ops and ops[0] == "m0":
+            wr = wr | {("m", 0)}
+        if wr:
+            visit(i, m, ops, set(wr), i + 1, 0, set())
+    return sorted(set(problems))

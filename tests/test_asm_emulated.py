@@ -103,6 +103,36 @@ def test_hazard_checker_sees_the_readfirstlane_mistake():
     assert emu.check_hazards(ins, labels)
 
 
+def _problems(body):
+    ins, labels = emu.parse_kernel("k:\n" + body + "\ts_endpgm\n.Lfunc_end_k:\n", "k")
+    return emu.check_hazards(ins, labels)
+
+
+def test_hazard_checker_follows_branches_and_counts_nops():
+    mfma = "\tv_mfma_f32_32x32x16_bf16 v[144:159], v[200:203], v[0:3], 0\n"
+    use = "\tv_add_f32 v176, v144, v160\n"
+    assert _problems(mfma + use)                                              # result read at once
+    assert _problems(mfma + "\ts_cbranch_scc1 .L_x\n" + "\ts_nop 15\n" * 3 + ".L_x:\n" + use)   # short taken path
+    assert not _problems(mfma + "\ts_nop 15\n\ts_nop 3\n" + use)
+    assert _problems("\ts_add_u32 m0, s59, 0\n\tglobal_load_lds_dwordx4 v241, s[46:47]\n")
+    assert not _problems("\ts_add_u32 m0, s59, 0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v241, s[46:47]\n")
+    assert _problems("\tv_exp_f32 v176, v176\n\tv_add_f32 v253, v176, v177\n")
+    assert _problems("\tv_mov_b32 v252, v251\n\ts_nop 0\n\tv_permlane32_swap_b32 v251, v252\n")
+
+
+def test_emulator_reports_a_missing_wait():
+    """A consumer that does not wait for its LDS read is an error, not a silently stale value."""
+    text = ("k:\n\tv_mov_b32 v1, 0\n\tds_read_b128 v[200:203], v1 offset:0\n"
+            "\tv_add_f32 v2, v200, v200\n\ts_endpgm\n.Lfunc_end_k:\n")
+    ins, labels = emu.parse_kernel(text, "k")
+    mem = emu.Memory()
+    ka = mem.add("kernarg", np.zeros(16, np.uint8))
+    wg = emu.Workgroup(ins, labels, mem, ka, 0, 0, 1024)
+    wg.lds_write(0, np.zeros(1024, np.uint8))
+    with pytest.raises(emu.EmuError):
+        wg.run()
+
+
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_tiny_config_on_the_emulator(asm_text, kernel):
     case = wl.make_config(0)                      # 16 heads, kv_len 256: 8 sub-tiles, 16 of 128 rows valid
