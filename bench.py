@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
     ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy"], default="auto",
                     help="auto = add_lazy if its output agrees with the strict add variant on this input, else add")
+    ap.add_argument("--impl", choices=["compiler", "asm"], default="compiler",
+                    help="compiler = the HIP C++ kernel (default); asm = the hand-scheduled kernels, which the "
+                         "library only runs when AMLA_ENABLE_ASM_KERNELS=1")
     ap.add_argument("--splits", type=int, default=0, help="split-KV factor, 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ab", action="store_true", help="skip the ADD-vs-MUL side-by-side timing")
@@ -112,8 +115,11 @@ def main():
                 "mul_lazy": (amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE),
                 "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE)}
 
+    impl_flag = amla.AMLA_FLAG_ASM_KERNEL if args.impl == "asm" else 0
+
     def step(name, o=out, l=lse):
         v, f = VARIANTS[name]
+        f |= impl_flag
         amla.amla_decode(q, kv, tab, lens, case.softmax_scale, o, l, variant=v, flags=f,
                          num_splits=args.splits, workspace=ws)
 
@@ -152,11 +158,12 @@ def main():
         "config": {"workload": f"configs[{args.config}] {case.name}: batch {case.batch}, s_q {case.s_q}, "
                                f"{case.heads} heads, sum kv_len {case.total_kv}, paged bf16 latent cache "
                                f"(block 64, permuted table), d_qk 576 / d_v 512",
-                   "variant": chosen, "kv_splits": splits, "seed": case.seed},
+                   "variant": chosen, "kernel_build": args.impl, "kv_splits": splits, "seed": case.seed},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "amla_decode_kernel", "kernel_ms": kern_ms,
+                     "kernel": "amla_decode_kernel" if args.impl == "compiler" else "amla_decode_asm_" + chosen,
+                     "kernel_ms": kern_ms,
                      "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": abytes,
                      "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
     }

@@ -802,6 +802,22 @@ def main():
     g.lines.append("\t.text")
     for name, rescale, lazy in KERNELS:
         kernel(g, name, rescale, lazy)
+    if os.environ.get("AMLA_ASM_SAFE") == "1":
+        # Diagnostic build: every wait is a full drain and every instruction is followed by idle
+        # issue slots, so that a wrong result that disappears here points at a timing hazard.
+        safe = []
+        for ln in g.lines:
+            t = ln.strip()
+            if t.startswith("s_waitcnt"):
+                safe.append("\ts_waitcnt vmcnt(0) lgkmcnt(0)")
+                continue
+            safe.append(ln)
+            if t.startswith("v_mfma"):
+                safe.append("\ts_nop 15")
+                safe.append("\ts_nop 3")
+            elif t.startswith(("v_", "ds_", "global_", "s_add_u32 m0")):
+                safe.append("\ts_nop 4")
+        g.lines = safe
     text = "\n".join(g.lines) + "\n" + metadata([k[0] for k in KERNELS]) + "\n"
     with open(out_path, "w") as f:
         f.write(text)
