@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
     ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy"], default="auto",
                     help="auto = add_lazy if its output agrees with the strict add variant on this input, else add")
+    ap.add_argument("--table5", default=None, metavar="SQ,SK",
+                    help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
+                         "s_q SQ, every sequence SK keys, contiguous cache")
     ap.add_argument("--impl", choices=["compiler", "asm"], default="compiler",
                     help="compiler = the HIP C++ kernel (default); asm = the hand-scheduled kernels, which the "
                          "library only runs when AMLA_ENABLE_ASM_KERNELS=1")
@@ -96,7 +99,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    case = wl.make_config(args.config)
+    if args.table5:
+        sq, sk = (int(x) for x in args.table5.split(","))
+        case = wl.make_table5_case(sq, sk)
+        workload_tag = f"paper Table 5 shape {case.name}"
+    else:
+        case = wl.make_config(args.config)
+        workload_tag = f"configs[{args.config}] {case.name}"
     dev = torch.device("cuda:0")
     q = torch.from_numpy(case.q_bits.view(np.int16)).to(dev).view(torch.bfloat16)
     kv = torch.from_numpy(case.kv_bits.view(np.int16)).to(dev).view(torch.bfloat16)
@@ -155,9 +164,9 @@ def main():
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {case.name}: batch {case.batch}, s_q {case.s_q}, "
+        "config": {"workload": f"{workload_tag}: batch {case.batch}, s_q {case.s_q}, "
                                f"{case.heads} heads, sum kv_len {case.total_kv}, paged bf16 latent cache "
-                               f"(block 64, permuted table), d_qk 576 / d_v 512",
+                               f"(block 64), d_qk 576 / d_v 512",
                    "variant": chosen, "kernel_build": args.impl, "kv_splits": splits, "seed": case.seed},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -20,6 +20,7 @@ What it holds
                                                 condition (see below).
 * `amla_fp32_emulation` Algorithm 2's loop in FP32 with BF16 P and the INT32 exponent add,
                        without the BF16 scale compensation (lines 7-9 are the follow-up).
+* `flash_fp32_emulation` Algorithm 1 in FP32 with BF16 P (the paper's "Base", Section 5.1).
 * `frobenius_error`    the error metric of Section 5.1.
 
 Pins (tests/test_oracle_*.py): the worked example of Section 3.2 (0.5 <-> 126 * 2^23),
@@ -236,6 +237,30 @@ def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None
         mu = mu_new
     out = O / l[:, None]
     lse = (mu.astype(np.float64) + np.log2(l.astype(np.float64))) * LN2
+    return out, lse
+
+
+def flash_fp32_emulation(Q, K, V, scale, block=64):
+    """Algorithm 1 ("Base") in FP32 with the exact row max as reference and BF16 P for the PV
+    product, the way a mixed-precision kernel runs it (Section 5.1's Base).  Same conventions as
+    `amla_fp32_emulation`; returns (out FP32, lse FP64)."""
+    f32 = np.float32
+    G, L = Q.shape[0], K.shape[0]
+    O = np.zeros((G, V.shape[1]), dtype=f32)
+    l = np.zeros(G, dtype=f32)
+    m = np.full(G, -np.inf, dtype=f32)
+    c = f32(scale * math.log2(math.e))
+    for lo in range(0, L, block):
+        Kb, Vb = K[lo:lo + block], V[lo:lo + block]
+        t = (Q @ Kb.T).astype(f32) * c
+        m_new = np.maximum(m, t.max(axis=1))
+        alpha = np.exp2((m - m_new).astype(f32)).astype(f32)
+        P = np.exp2((t - m_new[:, None]).astype(f32)).astype(f32)
+        l = (l * alpha + P.sum(axis=1, dtype=f32)).astype(f32)
+        O = (O * alpha[:, None] + (_round_bf16(P) @ Vb).astype(f32)).astype(f32)
+        m = m_new
+    out = O / l[:, None]
+    lse = (m.astype(np.float64) + np.log2(l.astype(np.float64))) * LN2
     return out, lse
 
 

@@ -156,3 +156,10 @@ def make_config(index: int) -> DecodeCase:
     if index == 4:
         return make_case("long_b8", 4, 8, 4, 128, [65536] * 8, q_sigma=4.0)
     raise IndexError(index)
+
+
+def make_table5_case(s_q: int, s_k: int, seed: int = 5) -> DecodeCase:
+    """A shape of the paper's performance table (Section 5.2, Table 5): batch 96, 128 query heads on
+    one shared KV head, BF16, every sequence s_k long, s_q in {1, 2}, cache laid out contiguously
+    (identity block table)."""
+    return make_case(f"table5_sq{s_q}_sk{s_k}", seed, 96, s_q, 128, [s_k] * 96, table="identity")
