@@ -118,17 +118,29 @@ class LdsQueue:
 
     def __init__(self):
         self.pending = []
+        self.retired = set()
 
     def issue(self, tag):
+        self.retired.discard(tag)
         self.pending.append(tag)
         assert len(self.pending) <= 15
 
     def wait_for(self, tag):
-        """Returns the lgkmcnt value after which `tag` has returned."""
+        """Returns the lgkmcnt value after which `tag` has returned (everything issued before it
+        has then returned too).  A tag that an earlier wait already covered needs no wait: the
+        value returned is the number of reads outstanding, which the counter cannot exceed."""
+        if tag not in self.pending:
+            assert tag in self.retired, tag
+            return len(self.pending)
         i = self.pending.index(tag)
         n = len(self.pending) - 1 - i
+        self.retired.update(self.pending[: i + 1])
         del self.pending[: i + 1]
         return n
+
+    def drain(self):
+        self.retired.update(self.pending)
+        self.pending.clear()
 
 
 def interleave(g, groups, valu, first_group=0):
@@ -341,48 +353,55 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     fetch_phys_blocking()
     finish_state_init()
 
-    # ---- K operand stream of one sub-tile: 36 b128 reads through the 8-slot staging ring -------
-    def k_read(ks):
-        return f"ds_read_b128 {vr(ST + 4 * (ks % NST), 4)}, v{V_KCUR} offset:{32 * ks}"
+    # ---- operand ring -------------------------------------------------------------------------
+    # One pass consumes 68 MFMA operands from LDS: K_0..K_35 (one b128 read each) for S^T(u+1), then
+    # V_0..V_31 (two transposing b64 reads each) for O^T(u).  Operand number n of a pass of parity p
+    # lives in ring slot (n + 4 p) % 8, and the fetch of operand n + 8 is issued right after the MFMA
+    # that consumed operand n, into the slot that MFMA just freed.  68 % 8 = 4, so the slot phase
+    # alternates between passes; the loop body is unrolled twice (p = 0, 1).
+    def ring(n, p):
+        return ST + 4 * ((n + 4 * p) % NST)
+
+    def k_fetch(ks, p):
+        return [f"ds_read_b128 {vr(ring(ks, p), 4)}, v{V_KCUR} offset:{32 * ks}"]
+
+    order = [(st, dt) for st in range(2) for dt in range(16)]
+
+    def v_fetch(idx, p):
+        st, dt = order[idx]
+        slot = ring(36 + idx, p)
+        base = st * 16 * ROW + dt * 64
+        return [f"ds_read_b64_tr_b16 {vr(slot, 2)}, v{V_VCUR} offset:{base}",
+                f"ds_read_b64_tr_b16 {vr(slot + 2, 2)}, v{V_VCUR} offset:{base + 8 * ROW}"]
+
+    def qk_mfma(ks, p):
+        dst = SA if ks % 2 == 0 else SB
+        src_c = "0" if ks < 2 else vr(dst, 16)
+        return (f"v_mfma_f32_32x32x16_bf16 {vr(dst, 16)}, {vr(ring(ks, p), 4)}, {vr(Q + 4 * ks, 4)}, {src_c}")
+
+    def pv_mfma(idx, p):
+        st, dt = order[idx]
+        return (f"v_mfma_f32_32x32x16_bf16 {ar(16 * dt, 16)}, {vr(ring(36 + idx, p), 4)}, "
+                f"{vr(PK + 4 * st, 4)}, {ar(16 * dt, 16)}")
 
     def set_k_base():
         g(f"v_add_u32 v{V_KCUR}, {sr(S_SLOTK)}, v{V_KOFF}")
 
-    def phase_a(valu, first_reads_in_flight, table_load):
-        """36 MFMAs of S^T = K Q^T in two accumulation chains.  K reads 0..NST-1 are either issued
-        here or already in flight (issued under the tail of the previous pass)."""
+    def prologue_qk():
+        """S^T of the first sub-tile, not overlapped with anything: its own K fetches, parity 0."""
         q = LdsQueue()
-        if not first_reads_in_flight:
-            set_k_base()
-            for ks in range(NST):
-                g(k_read(ks))
+        set_k_base()
         for ks in range(NST):
+            for ins in k_fetch(ks, 0):
+                g(ins)
             q.issue(ks)
-        groups = []
         for ks in range(36):
-            grp = []
-            if table_load and ks == 0:
-                # Block-table entry of the sub-tile whose loads are issued after this pass's barrier.
-                # SMEM shares lgkmcnt with LDS and may return out of order; counting only the LDS
-                # reads in the waits below stays correct (an outstanding SMEM op can only make a
-                # wait stricter), and the wait before the barrier is lgkmcnt(0).
-                grp.append(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {NSLOT}")
-                grp.append(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
-                grp.append(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
-                grp.append(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
-                grp.append(f"s_load_dword {sr(S_PHYS)}, {sr(S_TABB, 2)}, {sr(S_T1)}")
-            n = q.wait_for(ks)
-            grp.append(f"s_waitcnt lgkmcnt({n})")
-            dst = SA if ks % 2 == 0 else SB
-            src_c = "0" if ks < 2 else vr(dst, 16)
-            grp.append(f"v_mfma_f32_32x32x16_bf16 {vr(dst, 16)}, {vr(ST + 4 * (ks % NST), 4)}, "
-                       f"{vr(Q + 4 * ks, 4)}, {src_c}")
-            nxt = ks + NST
-            if nxt < 36:
-                grp.append(k_read(nxt))
-                q.issue(nxt)
-            groups.append(grp)
-        interleave(g, groups, valu)
+            g(f"s_waitcnt lgkmcnt({q.wait_for(ks)})")
+            g(qk_mfma(ks, 0))
+            if ks + NST < 36:
+                for ins in k_fetch(ks + NST, 0):
+                    g(ins)
+                q.issue(ks + NST)
 
     # ---- softmax of the scores in SC (VALU stream) -------------------------------------------
     def softmax_stream():
@@ -463,10 +482,10 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             g(f"v_cmp_le_i32 vcc, {sr(S_T1)}, v{T0}")
             g(f"v_cndmask_b32 v{SC + r}, v{SC + r}, v{T1}, vcc")
 
-    # ---- prologue: scores of sub-tile u0, then the first K reads of sub-tile u0+1 ---------------
+    # ---- prologue: scores of sub-tile u0, then the first K fetches of sub-tile u0+1 --------------
     g(f"s_waitcnt vmcnt({3 * LOADS_PER_SUBTILE})")              # Q fragment and sub-tile u0 have landed
     g("s_barrier")
-    phase_a([], False, False)
+    prologue_qk()
     g("s_nop 15")
     g("s_nop 15")
     for ins in form_scores_stream():
@@ -481,132 +500,164 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"s_waitcnt vmcnt({2 * LOADS_PER_SUBTILE})")              # sub-tile u0 + 1 has landed
     g("s_barrier")
     set_k_base()
+    lq = LdsQueue()                                             # carried through both passes of the loop body
     for ks in range(NST):
-        g(k_read(ks))
+        for ins in k_fetch(ks, 0):
+            g(ins)
+        lq.issue(("K", 0, ks))
+
+    def rescale_path(tag):
+        """Accumulator rescale (rare path), eight registers at a time through SC, which is free
+        between the end of the softmax and the score adds of the second half of the pass."""
+        g(f"s_cmp_lg_u64 {sr(S_NEED, 2)}, 0")
+        g(f"s_cselect_b32 {sr(S_T0)}, 1, 0")
+        g(f"s_andn2_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_FIRST)}")
+        g(f"s_bitcmp1_b32 {sr(S_FLAGS)}, 0")                     # AMLA_FLAG_NO_SKIP
+        g(f"s_cselect_b32 {sr(S_T1)}, 1, 0")
+        g(f"s_andn2_b32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_FIRST)}")
+        g(f"s_or_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_T1)}")
+        g(f"s_mov_b32 {sr(S_FIRST)}, 0")
+        g(f"s_cmp_eq_u32 {sr(S_T0)}, 0")
+        g(f"s_cbranch_scc1 {L('no_rescale' + tag)}")
+        for base in range(0, 256, 8):
+            for r in range(8):
+                g(f"v_accvgpr_read_b32 v{SC + r}, a{base + r}")
+            if rescale == "mul":
+                for r in range(8):
+                    g(f"v_mul_f32 v{SC + r}, v{SC + r}, v{V_FAC}")
+            else:
+                for r in range(8):
+                    g(f"v_and_b32 v{SC + 8 + r}, 0x80000000, v{SC + r}")
+                for r in range(8):
+                    g(f"v_add_i32 v{SC + r}, v{SC + r}, v{V_FAC} clamp")
+                for r in range(8):
+                    g(f"v_max_i32 v{SC + r}, v{SC + r}, v{SC + 8 + r}")
+            for r in range(8):
+                g(f"v_accvgpr_write_b32 a{base + r}, v{SC + r}")
+        g("s_nop 7")
+        g.label(L("no_rescale" + tag))
+
+    def dma_stream():
+        v = [f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}"]
+        for k in range(LOADS_PER_SUBTILE):
+            if k < 9:
+                v.append(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
+            else:
+                v.append(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
+            v.append("s_nop 0")
+            v.append(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
+        return v
+
+    N_K, N_V = 36, 32
+    N_USE = N_K + N_V
+    BARRIER_AFTER = N_K + 24          # the barrier of the pass follows the MFMA of operand V_24
+
+    def one_pass(p):
+        """Pass for sub-tile u with ring parity p.  On entry: scores of u in SC; sub-tiles u and u+1
+        resident, u+2 and u+3 landed or in flight; K_0..K_7 of sub-tile u+1 in flight;
+        S_SLOTV = slot(u), V_KCUR = K base of slot(u+1)."""
+        tag = f"_p{p}"
+        g(f"v_add_u32 v{V_VCUR}, {sr(S_SLOTV)}, v{V_VOFF}")
+        ready = []                     # fetches whose ring slot is free, in order: (tag, instructions)
+
+        def fetch_of(n):
+            """Fetch of operand n of this pass, or of operand n - 68 of the next pass."""
+            if n < N_K:
+                return ("K", p, n), k_fetch(n, p), False
+            if n < N_USE:
+                return ("V", p, n - N_K), v_fetch(n - N_K, p), False
+            return ("K", 1 - p, n - N_USE), k_fetch(n - N_USE, 1 - p), True      # next sub-tile: only after the barrier
+
+        def consume(n, barrier_passed):
+            grp = []
+            kind = ("K", p, n) if n < N_K else (("V", p, n - N_K), 1)      # a V operand is complete with its second read
+            grp.append(f"s_waitcnt lgkmcnt({min(lq.wait_for(kind), 15)})")
+            grp.append(qk_mfma(n, p) if n < N_K else pv_mfma(n - N_K, p))
+            ready.append(fetch_of(n + NST))
+            while ready:
+                t, instrs, after_barrier = ready[0]
+                if after_barrier and not barrier_passed:
+                    break
+                if len(lq.pending) + len(instrs) > 15:
+                    break
+                ready.pop(0)
+                grp.extend(instrs)
+                for k in range(len(instrs)):
+                    lq.issue(t if len(instrs) == 1 else (t, k))
+            return grp
+
+        # -- first half: QK of sub-tile u+1 under the softmax of sub-tile u; from K_28 on the freed
+        #    ring slots already take V^T operands of the second half, which moves a quarter of the
+        #    transposing reads into the half whose LDS load is light
+        groups = []
+        for n in range(N_K):
+            grp = []
+            if n == 0:
+                # Block-table entry of the sub-tile whose loads are issued after this pass's barrier.
+                # SMEM shares lgkmcnt with LDS and may return out of order; counting only the LDS
+                # reads in the waits stays correct (an outstanding SMEM op can only make a wait
+                # stricter), and the wait before the barrier is lgkmcnt(0).
+                grp.append(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {NSLOT}")
+                grp.append(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
+                grp.append(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
+                grp.append(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
+                grp.append(f"s_load_dword {sr(S_PHYS)}, {sr(S_TABB, 2)}, {sr(S_T1)}")
+            grp.extend(consume(n, False))
+            groups.append(grp)
+        interleave(g, groups, softmax_stream())
+
+        rescale_path(tag)
+
+        # -- second half, body: PV MFMAs 0..24 with the remaining V^T fetches
+        groups = [consume(n, False) for n in range(N_K, BARRIER_AFTER + 1)]
+        # the score adds read the results of the last QK MFMAs: they start four groups in, more than
+        # 30 issue slots after the last QK MFMA
+        interleave(g, groups, form_scores_stream(), first_group=4)
+        assert all(not (t[0] == "V") for t, _, _ in ready), "every V fetch must be out before the barrier"
+
+        # -- barrier of the pass.  lgkmcnt(0): every V^T read of slot(u) by this wave has returned (and
+        #    the block-table entry); vmcnt: of the two load groups in flight (u+2, u+3) the older has
+        #    landed.  After the barrier that holds for all waves: slot(u) may be refilled and
+        #    sub-tile u+2 may be read.
+        g(f"s_waitcnt vmcnt({LOADS_PER_SUBTILE}) lgkmcnt(0)")
+        lq.drain()
+        g("s_barrier")
+        advance_slot(S_SLOTK)                                   # slot(u+2)
+        set_k_base()
+        g(f"s_mov_b32 {sr(S_SLOTLD)}, {sr(S_SLOTV)}")
+        tile_base_from_phys()
+        # -- second half, tail: the last PV MFMAs run after the barrier, each freeing the ring slot
+        #    that the next K fetch of sub-tile u+2 refills; the direct-to-LDS loads of sub-tile
+        #    min(u+4, last) into slot(u) are issued in between
+        first = []
+        while ready and len(lq.pending) + len(ready[0][1]) <= 15:
+            t, instrs, _ = ready.pop(0)
+            first.extend(instrs)
+            lq.issue(t)
+        for ins in first:
+            g(ins)
+        groups = [consume(n, True) for n in range(BARRIER_AFTER + 1, N_USE)]
+        interleave(g, groups, dma_stream())
+        assert not ready
+
+        # -- advance
+        g(f"s_add_u32 {sr(S_U)}, {sr(S_U)}, 1")
+        advance_slot(S_SLOTV)
+        g(f"s_cmp_ge_u32 {sr(S_U)}, {sr(S_UEND)}")
+        g(f"s_cbranch_scc1 {L('epilogue')}")
+        # sub-tile u (new) partial?  its scores are now in SC
+        g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
+        g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
+        g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
+        g(f"s_cbranch_scc1 {L('full' + tag)}")
+        mask_partial()
+        g.label(L("full" + tag))
 
     # ------------------------------------------------------------------------------ main loop
-    # Pass for sub-tile u.  On entry: scores of u in SC; sub-tiles u, u+1 resident, u+2, u+3 landed
-    # or in flight; K reads 0..7 of sub-tile u+1 in flight; S_SLOTV = slot(u), S_SLOTK = slot(u+1).
     g.label(L("loop"))
-    phase_a(softmax_stream(), True, True)
-
-    # ---- rescale of the accumulator registers (rare path) ----
-    g(f"s_cmp_lg_u64 {sr(S_NEED, 2)}, 0")
-    g(f"s_cselect_b32 {sr(S_T0)}, 1, 0")
-    g(f"s_andn2_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_FIRST)}")
-    g(f"s_bitcmp1_b32 {sr(S_FLAGS)}, 0")                         # AMLA_FLAG_NO_SKIP
-    g(f"s_cselect_b32 {sr(S_T1)}, 1, 0")
-    g(f"s_andn2_b32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_FIRST)}")
-    g(f"s_or_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_T1)}")
-    g(f"s_mov_b32 {sr(S_FIRST)}, 0")
-    g(f"s_cmp_eq_u32 {sr(S_T0)}, 0")
-    g(f"s_cbranch_scc1 {L('no_rescale')}")
-    for base in range(0, 256, 16):
-        for r in range(16):
-            g(f"v_accvgpr_read_b32 v{ST + r}, a{base + r}")
-        if rescale == "mul":
-            for r in range(16):
-                g(f"v_mul_f32 v{ST + r}, v{ST + r}, v{V_FAC}")
-        else:
-            for r in range(16):
-                g(f"v_and_b32 v{ST + 16 + r}, 0x80000000, v{ST + r}")
-            for r in range(16):
-                g(f"v_add_i32 v{ST + r}, v{ST + r}, v{V_FAC} clamp")
-            for r in range(16):
-                g(f"v_max_i32 v{ST + r}, v{ST + r}, v{ST + 16 + r}")
-        for r in range(16):
-            g(f"v_accvgpr_write_b32 a{base + r}, v{ST + r}")
-    g("s_nop 7")
-    g.label(L("no_rescale"))
-
-    # ---- phase B: O^T += V^T P^T for the sub-tile in slot S_SLOTV ----
-    # Body: MFMAs 0..23 with the V^T reads streaming six MFMAs ahead; by the end of the body all 64
-    # reads have been issued and the operands of MFMAs 24..31 sit in the staging ring.  Then the
-    # barrier of the pass; the last eight MFMAs run after it, each freeing the ring slot that the
-    # matching K read of the next sub-tile refills, so the MFMA pipe has work across the barrier and
-    # across the LDS latency of the first K operands.
-    q = LdsQueue()
-    g(f"v_add_u32 v{V_VCUR}, {sr(S_SLOTV)}, v{V_VOFF}")
-    order = [(st, dt) for st in range(2) for dt in range(16)]
-    TAIL = NST
-
-    def v_reads(idx):
-        st, dt = order[idx]
-        slot = ST + 4 * (idx % NST)
-        base = st * 16 * ROW + dt * 64
-        return [f"ds_read_b64_tr_b16 {vr(slot, 2)}, v{V_VCUR} offset:{base}",
-                f"ds_read_b64_tr_b16 {vr(slot + 2, 2)}, v{V_VCUR} offset:{base + 8 * ROW}"]
-
-    def pv_mfma(idx):
-        st, dt = order[idx]
-        slot = ST + 4 * (idx % NST)
-        return (f"v_mfma_f32_32x32x16_bf16 {ar(16 * dt, 16)}, {vr(slot, 4)}, {vr(PK + 4 * st, 4)}, "
-                f"{ar(16 * dt, 16)}")
-
-    depth = 6                                  # 12 reads in flight <= 15
-    for idx in range(depth):
-        for ins in v_reads(idx):
-            g(ins)
-        q.issue((idx, 0))
-        q.issue((idx, 1))
-    groups = []
-    for idx in range(len(order) - TAIL):
-        grp = []
-        n = q.wait_for((idx, 1))
-        grp.append(f"s_waitcnt lgkmcnt({n})")
-        grp.append(pv_mfma(idx))
-        nxt = idx + depth
-        if nxt < len(order):
-            grp.extend(v_reads(nxt))
-            q.issue((nxt, 0))
-            q.issue((nxt, 1))
-        groups.append(grp)
-    # the reads of the last `depth - ... ` MFMAs that the body did not reach
-    rest = []
-    for nxt in range(len(order) - TAIL + depth, len(order)):
-        rest.extend(v_reads(nxt))
-    groups[-1].extend(rest)
-    # VALU stream of the body: the scores of sub-tile u+1 (after the QK chains have drained)
-    # The adds read the results of the last QK MFMAs: they start four groups into the body, i.e.
-    # more than 30 issue slots after the last QK MFMA, instead of waiting in s_nop.
-    interleave(g, groups, form_scores_stream(), first_group=4)
-
-    # ---- barrier of the pass ----
-    # lgkmcnt(0): every V^T read of slot(u) by this wave has returned (and the block-table entry);
-    # vmcnt: of the two load groups in flight (u+2, u+3) the older has landed.  After the barrier
-    # that holds for all waves: slot(u) may be refilled and sub-tile u+2 may be read.
-    g(f"s_waitcnt vmcnt({LOADS_PER_SUBTILE}) lgkmcnt(0)")
-    g("s_barrier")
-    advance_slot(S_SLOTK)                                       # slot(u+2)
-    set_k_base()
-    tail = []
-    for t in range(TAIL):
-        tail.append([pv_mfma(len(order) - TAIL + t), k_read(t)])
-    # direct-to-LDS loads of sub-tile min(u+4, last) into slot(u), spread over the tail
-    g(f"s_mov_b32 {sr(S_SLOTLD)}, {sr(S_SLOTV)}")
-    tile_base_from_phys()
-    dma = []
-    dma.append(f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}")
-    for k in range(LOADS_PER_SUBTILE):
-        if k < 9:
-            dma.append(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
-        else:
-            dma.append(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
-        dma.append("s_nop 0")
-        dma.append(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
-    interleave(g, tail, dma)
-
-    # ---- advance ----
-    g(f"s_add_u32 {sr(S_U)}, {sr(S_U)}, 1")
-    advance_slot(S_SLOTV)
-    g(f"s_cmp_ge_u32 {sr(S_U)}, {sr(S_UEND)}")
-    g(f"s_cbranch_scc1 {L('epilogue')}")
-    # sub-tile u (new) partial?  its scores are now in SC
-    g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
-    g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
-    g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
-    g(f"s_cbranch_scc1 {L('loop')}")
-    mask_partial()
+    one_pass(0)
+    one_pass(1)
+    assert [t for t in lq.pending] == [("K", 0, ks) for ks in range(NST)], lq.pending
     g(f"s_branch {L('loop')}")
 
     # --------------------------------------------------------------------------------- epilogue
