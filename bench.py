@@ -44,6 +44,10 @@ def parse():
                          "library only runs when AMLA_ENABLE_ASM_KERNELS=1")
     ap.add_argument("--splits", type=int, default=0, help="split-KV factor, 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true", help="skip the measured-MFMA-peak probe")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="instead of the benchmark: copy a buffer of this many MiB `steps` times with a plain "
+                         "copy kernel (torch copy_), for scaling the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-ab", action="store_true", help="skip the ADD-vs-MUL side-by-side timing")
     return ap.parse_args()
 
@@ -99,6 +103,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.copy_probe_mib:
+        n = args.copy_probe_mib << 20
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": True, "bytes_read_per_launch": n, "bytes_written_per_launch": n,
+                          "launches": args.steps}))
+        return
     if args.table5:
         sq, sk = (int(x) for x in args.table5.split(","))
         case = wl.make_table5_case(sq, sk)
@@ -193,6 +207,17 @@ def main():
                              "note": "interleaved runs, best of 2 per variant, same binary; strict = reference "
                                      "moves with every new row max, lazy = only past 2^8"}
 
+    if not args.no_mfma_probe:
+        # sustained rate of a register-resident MFMA loop on this device, same process, right after
+        # the timed region: what the chip delivers under its power limit
+        probe_flops = [0.0]
+
+        def probe():
+            probe_flops[0] = amla.amla_mfma_probe(20000, 256)
+        t, _ = time_steps(torch, probe, 5, 2)
+        measured = probe_flops[0] / (t / 5 * 1e-3) / 1e12
+        result["roofline"]["measured_mfma_peak"] = measured
+        result["roofline"]["frac_of_measured_peak"] = achieved / measured
     if not args.no_cpu_baseline:
         per_seq = [acc.decode_flops(case.heads, case.s_q, int(L)) for L in case.seqlens]
         result["cpu_baseline"] = cpu_baseline(case, per_seq)

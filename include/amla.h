@@ -136,6 +136,16 @@ int amla_effective_splits(const amla_desc* desc);
  */
 int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* stream);
 
+/*
+ * amla_mfma_probe -- measurement support: enqueues `workgroups` workgroups of 4 waves that each run
+ * `iters` iterations of four independent register-resident v_mfma_f32_32x32x16_bf16 (no memory
+ * traffic), and writes the number of floating-point operations that launch performs to *flops
+ * (host).  Timing the launch gives the sustained MFMA rate of the device under its power limit,
+ * the measured counterpart of the datasheet peak that utilisation is quoted against (the paper
+ * quotes both a theoretical and a throttled peak).  1 <= iters <= 2^22, 1 <= workgroups <= 65535.
+ */
+int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stream);
+
 /* amla_status_string -- static, NUL-terminated description of a status code (host). */
 const char* amla_status_string(int status);
 

@@ -23,7 +23,7 @@ AMLA_FLAG_LAZY_RESCALE = 2
 AMLA_FLAG_ASM_KERNEL = 4
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
-           "amla_status_string")
+           "amla_mfma_probe", "amla_status_string")
 
 
 class AmlaDesc(ctypes.Structure):
@@ -53,6 +53,8 @@ lib.amla_effective_splits.argtypes = [ctypes.POINTER(AmlaDesc)]
 lib.amla_exponent_add.restype = ctypes.c_int
 lib.amla_exponent_add.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
                                   ctypes.c_void_p]
+lib.amla_mfma_probe.restype = ctypes.c_int
+lib.amla_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
 lib.amla_status_string.restype = ctypes.c_char_p
 lib.amla_status_string.argtypes = [ctypes.c_int]
 
@@ -140,3 +142,15 @@ def amla_exponent_add(x, delta: int, y=None):
     if st != AMLA_OK:
         raise AmlaError(st)
     return y
+
+
+def amla_mfma_probe(iters: int, workgroups: int) -> float:
+    """Enqueue the register-resident MFMA loop on torch's current stream; returns its FLOP count."""
+    import torch
+
+    flops = ctypes.c_double(0.0)
+    st = lib.amla_mfma_probe(int(iters), int(workgroups), ctypes.byref(flops),
+                             torch.cuda.current_stream().cuda_stream)
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return flops.value

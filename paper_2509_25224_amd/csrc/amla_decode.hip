@@ -363,6 +363,25 @@ __global__ __launch_bounds__(128) void amla_combine_kernel(const float* __restri
   if (lse != nullptr && threadIdx.x == 0) lse[row] = tot > 0.f ? mx + __logf(tot) : -INFINITY;
 }
 
+// Register-resident MFMA loop: the measured-peak denominator beside the datasheet peak (the
+// paper's footnote makes the same distinction between a theoretical and a throttled peak).
+__global__ __launch_bounds__(256) void amla_mfma_probe_kernel(float* out, int iters) {
+  bf16x8 a, b;
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)(threadIdx.x % 3);
+    b[e] = (__bf16)(float)(threadIdx.x % 5);
+  }
+  f32x16 c[4];
+  for (int n = 0; n < 4; ++n) c[n] = f32x16{0};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) c[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[n], 0, 0, 0);
+  }
+  float s = 0.f;
+  for (int n = 0; n < 4; ++n) s += c[n][0];
+  if (s == 12345.678f && out != nullptr) out[0] = s;   // keeps the loop alive; never true for these operands
+}
+
 __global__ void amla_exponent_add_kernel(const float* x, float* y, size_t n, int n23) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) y[i] = exponent_add(x[i], n23);
@@ -580,6 +599,17 @@ int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* s
   hipLaunchKernelGGL(amla_exponent_add_kernel, dim3((unsigned)blocks), dim3(256), 0,
                      static_cast<hipStream_t>(stream), x, y, n, delta * (1 << 23));
   return hipGetLastError() == hipSuccess ? AMLA_OK : AMLA_ERR_LAUNCH;
+}
+
+int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stream) {
+  if (flops == nullptr) return AMLA_ERR_NULL_ARG;
+  if (iters < 1 || iters > (1 << 22) || workgroups < 1 || workgroups > 65535) return AMLA_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(amla_mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<float*>(nullptr), iters);
+  if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  // 4 waves per workgroup, 4 MFMAs of 32 x 32 x 16 multiply-adds per iteration and wave
+  *flops = (double)iters * 4.0 * 4.0 * (2.0 * 32 * 32 * 16) * (double)workgroups;
+  return AMLA_OK;
 }
 
 const char* amla_status_string(int status) {
