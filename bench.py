@@ -151,18 +151,21 @@ def main():
     # output stays within one bf16 step of the strict one and its lse within 1e-4.
     chosen, self_check = args.variant, None
     if args.variant == "auto":
-        o2 = torch.empty_like(out)
-        l2 = torch.empty_like(lse)
-        step("add")
-        step("add_lazy", o2, l2)
-        torch.cuda.synchronize()
-        a, b = out.float(), o2.float()
-        d_out = float(((a - b).abs() / a.abs().clamp(min=1.0)).max())
-        d_lse = float((lse - l2).abs().max())
-        ok = d_out <= 2.0 ** -7 and d_lse <= 1e-4
-        chosen = "add_lazy" if ok else "add"
-        self_check = {"max_rel_out_diff_vs_strict": d_out, "max_lse_diff_vs_strict": d_lse, "passed": ok}
-        del o2, l2
+        try:
+            o2 = torch.empty_like(out)
+            l2 = torch.empty_like(lse)
+            step("add")
+            step("add_lazy", o2, l2)
+            torch.cuda.synchronize()
+            a, b = out.float(), o2.float()
+            d_out = float(((a - b).abs() / a.abs().clamp(min=1.0)).max())
+            d_lse = float((lse - l2).abs().max())
+            ok = d_out <= 2.0 ** -7 and d_lse <= 1e-4
+            chosen = "add_lazy" if ok else "add"
+            self_check = {"max_rel_out_diff_vs_strict": d_out, "max_lse_diff_vs_strict": d_lse, "passed": ok}
+            del o2, l2
+        except Exception as e:  # noqa: BLE001  (fall back to the variant every GPU test covers)
+            chosen, self_check = "add", {"passed": False, "error": repr(e)}
     torch.cuda.synchronize()
     total_ms, per = time_steps(torch, lambda: step(chosen), args.steps, args.warmup)
     torch.cuda.synchronize()
@@ -193,34 +196,46 @@ def main():
 
     if self_check is not None:
         result["config"]["lazy_self_check"] = self_check
+    notes = []
     if not args.no_ab:
-        ab = {}
-        for name in ("mul", "add", "mul_lazy", "add_lazy") * 2:
-            t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
-            ab.setdefault(name, []).append(t / args.steps)
-        best = {k: min(v) for k, v in ab.items()}
-        result["rescale"] = {"add_ms": best["add"], "mul_ms": best["mul"], "add_lazy_ms": best["add_lazy"],
-                             "mul_lazy_ms": best["mul_lazy"],
-                             "add_over_mul_speedup": best["mul"] / best["add"],
-                             "add_lazy_over_mul_lazy_speedup": best["mul_lazy"] / best["add_lazy"],
-                             "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in best.items()},
-                             "note": "interleaved runs, best of 2 per variant, same binary; strict = reference "
-                                     "moves with every new row max, lazy = only past 2^8"}
+        try:
+            ab = {}
+            for name in ("mul", "add", "mul_lazy", "add_lazy") * 2:
+                t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
+                ab.setdefault(name, []).append(t / args.steps)
+            best = {k: min(v) for k, v in ab.items()}
+            result["rescale"] = {"add_ms": best["add"], "mul_ms": best["mul"], "add_lazy_ms": best["add_lazy"],
+                                 "mul_lazy_ms": best["mul_lazy"],
+                                 "add_over_mul_speedup": best["mul"] / best["add"],
+                                 "add_lazy_over_mul_lazy_speedup": best["mul_lazy"] / best["add_lazy"],
+                                 "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in best.items()},
+                                 "note": "interleaved runs, best of 2 per variant, same binary; strict = "
+                                         "reference moves with every new row max, lazy = only past 2^8"}
+        except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
+            notes.append(f"rescale side-by-side failed: {e!r}")
 
     if not args.no_mfma_probe:
-        # sustained rate of a register-resident MFMA loop on this device, same process, right after
-        # the timed region: what the chip delivers under its power limit
-        probe_flops = [0.0]
+        try:
+            # sustained rate of a register-resident MFMA loop on this device, same process: what the
+            # chip delivers under its power limit
+            probe_flops = [0.0]
 
-        def probe():
-            probe_flops[0] = amla.amla_mfma_probe(20000, 256)
-        t, _ = time_steps(torch, probe, 5, 2)
-        measured = probe_flops[0] / (t / 5 * 1e-3) / 1e12
-        result["roofline"]["measured_mfma_peak"] = measured
-        result["roofline"]["frac_of_measured_peak"] = achieved / measured
+            def probe():
+                probe_flops[0] = amla.amla_mfma_probe(20000, 256)
+            t, _ = time_steps(torch, probe, 5, 2)
+            measured = probe_flops[0] / (t / 5 * 1e-3) / 1e12
+            result["roofline"]["measured_mfma_peak"] = measured
+            result["roofline"]["frac_of_measured_peak"] = achieved / measured
+        except Exception as e:  # noqa: BLE001
+            notes.append(f"mfma probe failed: {e!r}")
     if not args.no_cpu_baseline:
-        per_seq = [acc.decode_flops(case.heads, case.s_q, int(L)) for L in case.seqlens]
-        result["cpu_baseline"] = cpu_baseline(case, per_seq)
+        try:
+            per_seq = [acc.decode_flops(case.heads, case.s_q, int(L)) for L in case.seqlens]
+            result["cpu_baseline"] = cpu_baseline(case, per_seq)
+        except Exception as e:  # noqa: BLE001
+            notes.append(f"cpu baseline failed: {e!r}")
+    if notes:
+        result["notes"] = notes
 
     print(json.dumps(result))
 
