@@ -31,6 +31,7 @@ touches per clock fall into distinct banks), 37 KiB per slot.
 """
 from __future__ import annotations
 
+import collections
 import os
 import sys
 
@@ -81,7 +82,12 @@ S_ULD = 55       # sub-tile index the next load targets
 S_SAVE = 56      # 2
 S_REM = 58
 S_M0BASE = 59
-S_NEXT_FREE = 64
+S_PHYS2 = 45     # block-table entry fetched one pass ahead
+S_ULD2 = 60      # the sub-tile index it belongs to
+S_DOIT = 61      # accumulator rescale wanted in this pass
+S_GB2 = 62       # 2: global base of the next sub-tile to load
+S_UPART = 64     # index of the sub-tile with fewer than 32 keys in range, or -1
+S_NEXT_FREE = 66
 
 KARG_SIZE = 0x60
 
@@ -143,22 +149,34 @@ class LdsQueue:
         self.pending.clear()
 
 
+def issue_cost(ins):
+    """Approximate issue cost in cycles of one instruction of the VALU/SALU stream (quarter-rate
+    transcendentals, four cycles for everything else, the count of an s_nop)."""
+    m = ins.split()[0]
+    if m in ("v_exp_f32", "v_log_f32", "v_rcp_f32"):
+        return 16
+    if m == "s_nop":
+        return int(ins.split()[1]) + 1
+    return 4
+
+
 def interleave(g, groups, valu, first_group=0):
-    """Emit MFMA groups with the VALU stream spread between them, both in their own order.  The
-    VALU stream starts after group `first_group`."""
+    """Emit MFMA groups with the VALU stream spread between them, both in their own order, so that
+    the stream's issue cost is spread evenly over the groups from `first_group` on."""
     n = len(groups)
-    per = [0] * n
-    m = len(valu)
-    for i in range(m):
-        per[first_group + (i * (n - first_group)) // m] += 1
-    vi = 0
+    total = sum(issue_cost(x) for x in valu)
+    vi, spent = 0, 0
     for gi, grp in enumerate(groups):
         for ins in grp:
             g(ins)
-        for _ in range(per[gi]):
+        if gi < first_group:
+            continue
+        target = total * (gi - first_group + 1) / (n - first_group)
+        while vi < len(valu) and (spent + issue_cost(valu[vi]) / 2 <= target or gi == n - 1):
             g(valu[vi])
+            spent += issue_cost(valu[vi])
             vi += 1
-    assert vi == m
+    assert vi == len(valu)
 
 
 def kernel(g: Gen, name: str, rescale: str, lazy: bool):
@@ -285,6 +303,12 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"s_lshl_b32 {sr(S_UEND)}, {sr(S_T3)}, 1")
     g(f"s_min_u32 {sr(S_UEND)}, {sr(S_UEND)}, {sr(S_T1)}")
     g(f"s_sub_u32 {sr(S_ULAST)}, {sr(S_UEND)}, 1")
+    # only the last sub-tile of the sequence can be partial: S_REM = kv_len - 32 * (n32 - 1) keys
+    g(f"s_sub_u32 {sr(S_T2)}, {sr(S_T1)}, 1")                    # n32 - 1
+    g(f"s_lshl_b32 {sr(S_T3)}, {sr(S_T2)}, 5")
+    g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T3)}")
+    g(f"s_cmp_lt_i32 {sr(S_REM)}, 32")
+    g(f"s_cselect_b32 {sr(S_UPART)}, {sr(S_T2)}, -1")
     # state
     g(f"v_mov_b32 v{V_M}, 0xff800000")
     g(f"v_mov_b32 v{V_REF}, 0xff800000")
@@ -302,27 +326,36 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g.label(L("nonempty"))
 
     # ---- direct-to-LDS load of one sub-tile ---------------------------------------------------
-    def tile_base_from_phys():
-        """S_GB = kv + phys * 73728 + (S_ULD & 1) * 36864."""
-        g(f"s_mul_i32 {sr(S_T2)}, {sr(S_PHYS)}, 73728")
-        g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_PHYS)}, 73728")
-        g(f"s_and_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
-        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, 36864")
-        g(f"s_add_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_T1)}")
-        g(f"s_addc_u32 {sr(S_T3)}, {sr(S_T3)}, 0")
-        g(f"s_add_u32 {sr(S_GB)}, {sr(S_KVP)}, {sr(S_T2)}")
-        g(f"s_addc_u32 {sr(S_GB + 1)}, {sr(S_KVP + 1)}, {sr(S_T3)}")
+    def tile_base_code(dst=S_GB, phys=S_PHYS, uld=S_ULD):
+        """dst = kv + phys * 73728 + (uld & 1) * 36864."""
+        return [f"s_mul_i32 {sr(S_T2)}, {sr(phys)}, 73728",
+                f"s_mul_hi_u32 {sr(S_T3)}, {sr(phys)}, 73728",
+                f"s_and_b32 {sr(S_T1)}, {sr(uld)}, 1",
+                f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, 36864",
+                f"s_add_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_T1)}",
+                f"s_addc_u32 {sr(S_T3)}, {sr(S_T3)}, 0",
+                f"s_add_u32 {sr(dst)}, {sr(S_KVP)}, {sr(S_T2)}",
+                f"s_addc_u32 {sr(dst + 1)}, {sr(S_KVP + 1)}, {sr(S_T3)}"]
 
-    def issue_subtile_loads():
-        """10 loads per wave into slot S_SLOTLD from S_GB."""
-        g(f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}")
-        for k in range(LOADS_PER_SUBTILE):
+    def tile_base_from_phys():
+        for ins in tile_base_code():
+            g(ins)
+
+    def dma_code(k_lo, k_hi):
+        """Loads k_lo .. k_hi-1 of the 10 per wave, into slot S_SLOTLD from S_GB."""
+        v = [f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}"]
+        for k in range(k_lo, k_hi):
             if k < 9:
-                g(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
+                v.append(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
             else:
-                g(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
-            g("s_nop 0")
-            g(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
+                v.append(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
+            v.append("s_nop 0")
+            v.append(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
+        return v
+
+    def issue_subtile_loads(k_lo=0, k_hi=LOADS_PER_SUBTILE):
+        for ins in dma_code(k_lo, k_hi):
+            g(ins)
 
     def fetch_phys_blocking():
         g(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
@@ -335,22 +368,30 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         g(f"s_cmp_ge_u32 {sr(reg)}, {LDS_BYTES}")
         g(f"s_cselect_b32 {sr(reg)}, 0, {sr(reg)}")
 
-    # prologue loads: sub-tiles u0 .. u0+3 (clamped to the last one) fill the four slots
+    # prologue loads: sub-tiles u0 .. u0+3 (clamped to the last one) fill the four slots.  Of the last
+    # group only the first half is issued here; the first pass of the loop issues the second half
+    # at the place where every later pass completes the group its predecessor started.
+    DMA_SPLIT = 5
     g(f"s_mov_b32 {sr(S_SLOTLD)}, 0")
     for n in range(NSLOT):
         g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {n}")
         g(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
         fetch_phys_blocking()
         tile_base_from_phys()
-        issue_subtile_loads()
-        advance_slot(S_SLOTLD)
-    # S_SLOTLD is back at slot 0 = the slot of sub-tile u0, which sub-tile u0+4 takes over after
-    # the first pass of the loop
+        if n < NSLOT - 1:
+            issue_subtile_loads()
+            advance_slot(S_SLOTLD)
+        else:
+            issue_subtile_loads(0, DMA_SPLIT)                    # S_GB and S_SLOTLD stay set for the second half
     g(f"s_mov_b32 {sr(S_SLOTV)}, 0")
     g(f"s_mov_b32 {sr(S_SLOTK)}, 0")
-    g(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {NSLOT}")
-    g(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
-    fetch_phys_blocking()
+    # block-table entry of sub-tile min(u0+4, last), whose loads the first pass starts after its barrier
+    g(f"s_add_u32 {sr(S_ULD2)}, {sr(S_U)}, {NSLOT}")
+    g(f"s_min_u32 {sr(S_ULD2)}, {sr(S_ULD2)}, {sr(S_ULAST)}")
+    g(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD2)}, 1")
+    g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
+    g(f"s_load_dword {sr(S_PHYS2)}, {sr(S_TABB, 2)}, {sr(S_T1)}")
+    g("s_waitcnt lgkmcnt(0)")
     finish_state_init()
 
     # ---- operand ring -------------------------------------------------------------------------
@@ -440,19 +481,29 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             v.append(f"v_lshlrev_b32 v{V_FAC}, 23, v{T4}")
             v.append(f"v_cmp_ne_u32 {sr(S_NEED, 2)}, 0, v{V_FAC}")
         v.append(f"v_mov_b32 v{V_REF}, v{T1}")
-        # weights 2^(s * c - ref)
+        # weights 2^(s * c - ref), their FP32 sum, the bf16 pack and the sum of the rounded weights.
+        # The quarter-rate exponentials are spaced out between the cheaper instructions that
+        # consume earlier results (each at least two instructions after its producer).
+        work = collections.deque()           # cheap consumers waiting to be placed
         for r in range(16):
             v.append(f"v_fma_f32 v{sc[r]}, v{sc[r]}, {sr(S_C)}, -v{T1}")
-        for r in range(16):
+            if work:
+                v.append(work.popleft())
             v.append(f"v_exp_f32 v{sc[r]}, v{sc[r]}")
-        v.append(f"v_add_f32 v{T2}, v{sc[0]}, v{sc[1]}")
-        for r in range(2, 16):
-            v.append(f"v_add_f32 v{T2}, v{T2}, v{sc[r]}")
-        for i in range(8):
-            v.append(f"v_cvt_pk_bf16_f32 v{PK + i}, v{sc[2 * i]}, v{sc[2 * i + 1]}")
-        v.append(f"v_mov_b32 v{T3}, 0")
-        for i in range(8):
-            v.append(f"v_dot2c_f32_bf16 v{T3}, {sr(S_ONES)}, v{PK + i}")      # T3 += lo + hi of the packed pair
+            if work:
+                v.append(work.popleft())
+            if r == 1:
+                work.append(f"v_add_f32 v{T2}, v{sc[0]}, v{sc[1]}")
+            elif r > 1:
+                work.append(f"v_add_f32 v{T2}, v{T2}, v{sc[r]}")
+            if r % 2 == 1:
+                i = r // 2
+                work.append(f"v_cvt_pk_bf16_f32 v{PK + i}, v{sc[2 * i]}, v{sc[2 * i + 1]}")
+                if i == 0:
+                    work.append(f"v_mov_b32 v{T3}, 0")
+                work.append(f"v_dot2c_f32_bf16 v{T3}, {sr(S_ONES)}, v{PK + i}")      # T3 += lo + hi of the packed pair
+        v.append("s_nop 0")
+        v.extend(work)
         if rescale == "mul":
             v.append(f"v_fma_f32 v{V_L32}, v{V_L32}, v{V_FAC}, v{T2}")
             v.append(f"v_fma_f32 v{V_L16}, v{V_L16}, v{V_FAC}, v{T3}")
@@ -483,21 +534,19 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             g(f"v_cndmask_b32 v{SC + r}, v{SC + r}, v{T1}, vcc")
 
     # ---- prologue: scores of sub-tile u0, then the first K fetches of sub-tile u0+1 --------------
-    g(f"s_waitcnt vmcnt({3 * LOADS_PER_SUBTILE})")              # Q fragment and sub-tile u0 have landed
+    g(f"s_waitcnt vmcnt({2 * LOADS_PER_SUBTILE + DMA_SPLIT})")  # Q fragment and sub-tile u0 have landed
     g("s_barrier")
     prologue_qk()
     g("s_nop 15")
     g("s_nop 15")
     for ins in form_scores_stream():
         g(ins)
-    g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
-    g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
-    g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
+    g(f"s_cmp_lg_u32 {sr(S_U)}, {sr(S_UPART)}")
     g(f"s_cbranch_scc1 {L('pro_full')}")
     mask_partial()
     g.label(L("pro_full"))
     advance_slot(S_SLOTK)                                       # slot of sub-tile u0 + 1
-    g(f"s_waitcnt vmcnt({2 * LOADS_PER_SUBTILE})")              # sub-tile u0 + 1 has landed
+    g(f"s_waitcnt vmcnt({LOADS_PER_SUBTILE + DMA_SPLIT})")      # sub-tile u0 + 1 has landed
     g("s_barrier")
     set_k_base()
     lq = LdsQueue()                                             # carried through both passes of the loop body
@@ -509,15 +558,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     def rescale_path(tag):
         """Accumulator rescale (rare path), eight registers at a time through SC, which is free
         between the end of the softmax and the score adds of the second half of the pass."""
-        g(f"s_cmp_lg_u64 {sr(S_NEED, 2)}, 0")
-        g(f"s_cselect_b32 {sr(S_T0)}, 1, 0")
-        g(f"s_andn2_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_FIRST)}")
-        g(f"s_bitcmp1_b32 {sr(S_FLAGS)}, 0")                     # AMLA_FLAG_NO_SKIP
-        g(f"s_cselect_b32 {sr(S_T1)}, 1, 0")
-        g(f"s_andn2_b32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_FIRST)}")
-        g(f"s_or_b32 {sr(S_T0)}, {sr(S_T0)}, {sr(S_T1)}")
-        g(f"s_mov_b32 {sr(S_FIRST)}, 0")
-        g(f"s_cmp_eq_u32 {sr(S_T0)}, 0")
+        g(f"s_cmp_eq_u32 {sr(S_DOIT)}, 0")
         g(f"s_cbranch_scc1 {L('no_rescale' + tag)}")
         for base in range(0, 256, 8):
             for r in range(8):
@@ -537,20 +578,19 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         g("s_nop 7")
         g.label(L("no_rescale" + tag))
 
-    def dma_stream():
-        v = [f"s_add_u32 {sr(S_M0BASE)}, {sr(S_SLOTLD)}, {sr(S_WAVELDS)}"]
-        for k in range(LOADS_PER_SUBTILE):
-            if k < 9:
-                v.append(f"s_add_u32 m0, {sr(S_M0BASE)}, {4096 * k}")
-            else:
-                v.append(f"s_add_u32 m0, {sr(S_SLOTLD)}, {36 * 1024}")
-            v.append("s_nop 0")
-            v.append(f"global_load_lds_dwordx4 v{V_LD + k}, {sr(S_GB, 2)}")
-        return v
+    def rescale_flag_code():
+        """S_DOIT = (some row of the wave moved its reference, or NO_SKIP) and not the first pass."""
+        return [f"s_cmp_lg_u64 {sr(S_NEED, 2)}, 0",
+                f"s_cselect_b32 {sr(S_DOIT)}, 1, 0",
+                f"s_bitcmp1_b32 {sr(S_FLAGS)}, 0",                # AMLA_FLAG_NO_SKIP
+                f"s_cselect_b32 {sr(S_T1)}, 1, 0",
+                f"s_or_b32 {sr(S_DOIT)}, {sr(S_DOIT)}, {sr(S_T1)}",
+                f"s_andn2_b32 {sr(S_DOIT)}, {sr(S_DOIT)}, {sr(S_FIRST)}",
+                f"s_mov_b32 {sr(S_FIRST)}, 0"]
 
     N_K, N_V = 36, 32
     N_USE = N_K + N_V
-    BARRIER_AFTER = N_K + 24          # the barrier of the pass follows the MFMA of operand V_24
+    BARRIER_AFTER = N_K + 26          # the barrier of the pass follows the MFMA of operand V_26
 
     def one_pass(p):
         """Pass for sub-tile u with ring parity p.  On entry: scores of u in SC; sub-tiles u and u+1
@@ -592,19 +632,23 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         groups = []
         for n in range(N_K):
             grp = []
-            if n == 0:
-                # Block-table entry of the sub-tile whose loads are issued after this pass's barrier.
-                # SMEM shares lgkmcnt with LDS and may return out of order; counting only the LDS
-                # reads in the waits stays correct (an outstanding SMEM op can only make a wait
-                # stricter), and the wait before the barrier is lgkmcnt(0).
-                grp.append(f"s_add_u32 {sr(S_ULD)}, {sr(S_U)}, {NSLOT}")
-                grp.append(f"s_min_u32 {sr(S_ULD)}, {sr(S_ULD)}, {sr(S_ULAST)}")
-                grp.append(f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD)}, 1")
-                grp.append(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
-                grp.append(f"s_load_dword {sr(S_PHYS)}, {sr(S_TABB, 2)}, {sr(S_T1)}")
             grp.extend(consume(n, False))
             groups.append(grp)
-        interleave(g, groups, softmax_stream())
+        # VALU/SALU stream of the first half: the second half of the direct-to-LDS loads that the
+        # previous pass started, the softmax, the rescale decision
+        # The block-table entry fetched during the previous pass (its arrival was covered by that
+        # pass's lgkmcnt(0)) gives the base of the sub-tile whose loads start after this pass's
+        # barrier; then the entry for the pass after is fetched.  SMEM shares lgkmcnt with LDS and may
+        # return out of order; counting only the LDS reads in the waits stays correct (an outstanding
+        # SMEM op can only make a wait stricter), and the wait before the barrier is lgkmcnt(0).
+        table_code = tile_base_code(S_GB2, S_PHYS2, S_ULD2) + [
+            f"s_add_u32 {sr(S_ULD2)}, {sr(S_U)}, {NSLOT + 1}",
+            f"s_min_u32 {sr(S_ULD2)}, {sr(S_ULD2)}, {sr(S_ULAST)}",
+            f"s_lshr_b32 {sr(S_T1)}, {sr(S_ULD2)}, 1",
+            f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2",
+            f"s_load_dword {sr(S_PHYS2)}, {sr(S_TABB, 2)}, {sr(S_T1)}"]
+        interleave(g, groups, dma_code(DMA_SPLIT, LOADS_PER_SUBTILE) + table_code + softmax_stream()
+                   + rescale_flag_code())
 
         rescale_path(tag)
 
@@ -625,7 +669,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         advance_slot(S_SLOTK)                                   # slot(u+2)
         set_k_base()
         g(f"s_mov_b32 {sr(S_SLOTLD)}, {sr(S_SLOTV)}")
-        tile_base_from_phys()
+        g(f"s_mov_b64 {sr(S_GB, 2)}, {sr(S_GB2, 2)}")
         # -- second half, tail: the last PV MFMAs run after the barrier, each freeing the ring slot
         #    that the next K fetch of sub-tile u+2 refills; the direct-to-LDS loads of sub-tile
         #    min(u+4, last) into slot(u) are issued in between
@@ -637,18 +681,17 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         for ins in first:
             g(ins)
         groups = [consume(n, True) for n in range(BARRIER_AFTER + 1, N_USE)]
-        interleave(g, groups, dma_stream())
+        advance = [f"s_add_u32 {sr(S_U)}, {sr(S_U)}, 1",
+                   f"s_add_u32 {sr(S_SLOTV)}, {sr(S_SLOTV)}, {SLOT}",
+                   f"s_cmp_ge_u32 {sr(S_SLOTV)}, {LDS_BYTES}",
+                   f"s_cselect_b32 {sr(S_SLOTV)}, 0, {sr(S_SLOTV)}"]
+        interleave(g, groups, dma_code(0, DMA_SPLIT) + advance)
         assert not ready
 
-        # -- advance
-        g(f"s_add_u32 {sr(S_U)}, {sr(S_U)}, 1")
-        advance_slot(S_SLOTV)
+        # -- next pass, the end, or first the mask of a partial last sub-tile (its scores are in SC now)
         g(f"s_cmp_ge_u32 {sr(S_U)}, {sr(S_UEND)}")
         g(f"s_cbranch_scc1 {L('epilogue')}")
-        # sub-tile u (new) partial?  its scores are now in SC
-        g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_U)}, 5")
-        g(f"s_sub_i32 {sr(S_REM)}, {sr(S_LEN)}, {sr(S_T0)}")
-        g(f"s_cmp_ge_i32 {sr(S_REM)}, 32")
+        g(f"s_cmp_lg_u32 {sr(S_U)}, {sr(S_UPART)}")
         g(f"s_cbranch_scc1 {L('full' + tag)}")
         mask_partial()
         g.label(L("full" + tag))

@@ -381,7 +381,7 @@ class Wave:
             return nxt
 
         # ---------------- SALU
-        if mnem in ("s_mov_b32",):
+        if mnem in ("s_mov_b32", "s_mov_b64"):
             self.sdst(ops[0], S(ops[1]))
             return nxt
         if mnem in ("s_and_b32", "s_or_b32", "s_andn2_b32", "s_and_b64", "s_or_b64"):
