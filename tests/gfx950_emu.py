@@ -746,6 +746,10 @@ class Workgroup:
             wave.s[2] = wg_x
             wave.s[3] = wg_y
             # uninitialised registers hold arbitrary values: poison them so a stale read shows
+            wave.s[4:] = 0xBAD00000 + np.arange(4, 128, dtype=U32)
+            wave.vcc = 0xBAD0BAD0BAD0BAD0
+            wave.m0 = 0xBAD0BAD0
+            wave.scc = 1
             wave.v[:] = 0xDEAD0000 + np.arange(512, dtype=U32)[:, None]
             wave.v[0] = np.arange(LANES, dtype=U32) + 64 * w
             self.waves.append(wave)

@@ -171,6 +171,25 @@ def test_two_row_tiles_and_wide_logits(asm_text):
         assert np.all(np.abs(o - want) <= np.where(np.abs(want) < 4, 1e-2, half_ulp + 6e-3))
 
 
+@pytest.mark.parametrize("kernel", ["amla_decode_asm_mul_lazy", "amla_decode_asm_add_lazy"])
+def test_lazy_reference_moves_when_the_max_outruns_it(asm_text, kernel):
+    """Logits spread over tens of base-2 units and keys ordered so that the row max keeps growing:
+    the lazy kernels must take the deferred update (and the accumulator rescale) several times."""
+    case = wl.make_case("lazy", 35, batch=1, s_q=1, heads=8, seqlens=[256], q_sigma=8.0, table="identity")
+    # sort the keys of the first head's logits ascending so that later sub-tiles hold larger logits
+    q0 = wl.bf16_bits_to_f32(case.q_bits[0, 0, 0]).astype(np.float64)
+    kv = wl.bf16_bits_to_f32(case.kv_bits).astype(np.float64).reshape(-1, 576)
+    order = np.argsort(kv @ q0)
+    case.kv_bits[...] = case.kv_bits.reshape(-1, 576)[order].reshape(case.kv_bits.shape)
+    logits = np.sort(kv @ q0) * case.softmax_scale * 1.4426950408889634
+    assert logits[-1] - logits[31] > 24                       # the max of sub-tile 0 is outrun by > 3 thresholds
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    o, l, _ = run_case(asm_text, kernel, case, 1)
+    half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 1.0))) - 9)
+    assert np.all(np.abs(o - want) <= np.where(np.abs(want) < 4, 1e-2, half_ulp + 6e-3))
+    assert np.abs(l - want_lse).max() <= 1e-3
+
+
 def test_no_skip_flag_forces_the_rescale_path(asm_text):
     case = wl.make_case("noskip", 34, batch=1, s_q=1, heads=4, seqlens=[128])
     a = run_case(asm_text, "amla_decode_asm_add", case, 1, flags=0)
