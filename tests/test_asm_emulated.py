@@ -11,6 +11,7 @@ import pytest
 from oracle import amla_oracle as orc
 from paper_2509_25224_amd import workloads as wl
 import gfx950_emu as emu
+import gfx950_timing as timing
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 GEN = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "gen_decode_asm.py")
@@ -198,3 +199,15 @@ def test_no_skip_flag_forces_the_rescale_path(asm_text):
     check(b[0], b[1], case)
     c = run_case(asm_text, "amla_decode_asm_mul", case, 1, flags=1)
     check(c[0], c[1], case)
+
+
+def test_modelled_pass_time_of_the_lazy_kernel(asm_text):
+    """Schedule regression guard: in the cycle model a pass (32 keys) of the lazy kernel stays within
+    10 % of the 68 back-to-back MFMAs (2176 cycles) it contains."""
+    kernel = "amla_decode_asm_add_lazy"
+    case = wl.make_case("model", 41, batch=1, s_q=1, heads=128, seqlens=[384])       # 12 passes
+    ins, labels = emu.parse_kernel(asm_text, kernel)
+    trace = timing.record_trace(lambda: run_case(asm_text, kernel, case, 1))
+    per_pass, stall = timing.cycles_per_pass(ins, labels, trace, f".L_{kernel}_loop")
+    print(f"modelled cycles per pass: {per_pass:.0f}, stalls {dict(stall)}")
+    assert 2176 <= per_pass <= 2176 * 1.10
