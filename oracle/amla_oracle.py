@@ -21,6 +21,9 @@ What it holds
 * `amla_fp32_emulation` Algorithm 2's loop in FP32 with BF16 P and the INT32 exponent add,
                        without the BF16 scale compensation (lines 7-9 are the follow-up).
 * `flash_fp32_emulation` Algorithm 1 in FP32 with BF16 P (the paper's "Base", Section 5.1).
+* `amla_alg2_emulation` Algorithm 2 with its BF16 scale compensation, line by line in the paper's
+                       notation, with either printed definition of c_i (numerics study only: the
+                       kernels use two row sums instead).
 * `frobenius_error`    the error metric of Section 5.1.
 
 Pins (tests/test_oracle_*.py): the worked example of Section 3.2 (0.5 <-> 126 * 2^23),
@@ -238,6 +241,47 @@ def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None
     out = O / l[:, None]
     lse = (mu.astype(np.float64) + np.log2(l.astype(np.float64))) * LN2
     return out, lse
+
+
+def amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="appendix", guard=1e-6):
+    """Algorithm 2 step by step in FP32, in the paper's notation, with its BF16 scale compensation
+    (lines 7-12): S32 = exp(ln2 (n_i + m_i / ln2)), S16 = BF16(S32), c_i, eps = 1.5 (c_i / c_{i-1} - 1),
+    P <- BF16(P * S16), N = Cast_to_int32((max(n_i - n_{i-1}, -30) + eps + 1e-6) * 2^23), O <- AS_FP32(
+    AS_INT32(O) + N), O += P V, and O / (l_N * S16) at the end.
+
+    `c_reading` selects between the two definitions of c_i the paper gives: "algorithm" is line 9 as
+    printed (c_i = S32 / S16), "appendix" is Appendix A (c_i = r_i / r'_i = S16 / S32, since
+    S32 = 1 / r_i and S16 = 1 / r'_i).  Block size 512 is the paper's (Section 4.2)."""
+    f32 = np.float32
+    G, L = Q.shape[0], K.shape[0]
+    O = np.zeros((G, V.shape[1]), dtype=f32)
+    l = np.zeros(G, dtype=f32)
+    m = np.full(G, -np.inf, dtype=f32)
+    n_prev = None
+    c_prev = np.ones(G, dtype=f32)
+    S16 = np.ones(G, dtype=f32)
+    ln2 = f32(LN2)
+    for i, lo in enumerate(range(0, L, block)):
+        Kb, Vb = K[lo:lo + block], V[lo:lo + block]
+        S = ((Q @ Kb.T).astype(f32) * f32(scale)).astype(f32)
+        m_new = np.maximum(m, S.max(axis=1))
+        M_up = np.exp((m - m_new).astype(f32)).astype(f32)
+        n = np.rint(-m_new / ln2).astype(f32)
+        P = np.exp((S - m_new[:, None]).astype(f32)).astype(f32)
+        l = (l * M_up + P.sum(axis=1, dtype=f32)).astype(f32)
+        S32 = np.exp((ln2 * (n + m_new / ln2)).astype(f32)).astype(f32)
+        S16 = _round_bf16(S32)
+        c = (S32 / S16 if c_reading == "algorithm" else S16 / S32).astype(f32)
+        eps = (f32(1.5) * (c / c_prev - f32(1))).astype(f32)
+        Pb = _round_bf16((P * S16[:, None]).astype(f32))
+        if i > 0:
+            N = (np.maximum(n - n_prev, f32(-30)) + eps + f32(guard)).astype(f32)
+            Nint = np.trunc(N.astype(np.float64) * 2.0 ** 23).astype(np.int64)
+            I = as_int32(O).astype(np.int64) + Nint[:, None]
+            O = as_fp32((((I + (1 << 31)) % (1 << 32)) - (1 << 31)).astype(np.int32)).copy()
+        O = (O + (Pb @ Vb).astype(f32)).astype(f32)
+        m, n_prev, c_prev = m_new, n, c
+    return (O / (l * S16)[:, None]).astype(f32)
 
 
 def flash_fp32_emulation(Q, K, V, scale, block=64):
