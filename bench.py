@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
-    ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy"], default="auto",
+    ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy", "add_comp"], default="auto",
                     help="auto = add_lazy if its output agrees with the strict add variant on this input, else add")
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
                     help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
@@ -136,7 +136,8 @@ def main():
 
     VARIANTS = {"mul": (amla.AMLA_RESCALE_MUL, 0), "add": (amla.AMLA_RESCALE_ADD, 0),
                 "mul_lazy": (amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE),
-                "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE)}
+                "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE),
+                "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0)}
 
     impl_flag = amla.AMLA_FLAG_ASM_KERNEL if args.impl == "asm" else 0
 
@@ -200,7 +201,8 @@ def main():
     if not args.no_ab:
         try:
             ab = {}
-            for name in ("mul", "add", "mul_lazy", "add_lazy") * 2:
+            names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ())
+            for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)
             best = {k: min(v) for k, v in ab.items()}
@@ -210,7 +212,8 @@ def main():
                                  "add_lazy_over_mul_lazy_speedup": best["mul_lazy"] / best["add_lazy"],
                                  "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in best.items()},
                                  "note": "interleaved runs, best of 2 per variant, same binary; strict = "
-                                         "reference moves with every new row max, lazy = only past 2^8"}
+                                         "reference moves with every new row max, lazy = only past 2^8, "
+                                         "add_comp = Algorithm 2 with its BF16 scale compensation"}
         except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
             notes.append(f"rescale side-by-side failed: {e!r}")
 

@@ -20,6 +20,13 @@
  *                     (Eq. (4), Lemma 3.1, Algorithm 2 lines 5-6 and 11-15), the INT32 add
  *                     guarded so that an exponent that would drop to or below zero yields
  *                     a signed zero instead of a wrapped bit pattern.
+ *   AMLA_RESCALE_ADD_COMP  the ADD variant with the BF16 scale compensation of Algorithm 2
+ *                     lines 7-12 and Appendix A: the weights are 2^(t - m) * S16 with S16 the
+ *                     BF16 rounding of S32 = 2^(m - rint(m)), so the largest weight of a row is
+ *                     BF16-exact as in Algorithm 1; the same INT32 add then also carries
+ *                     rint(2^23 * 1.5 * (c_i / c_{i-1} - 1)), c_i = S16 / S32, which multiplies
+ *                     the old accumulator by approximately c_i / c_{i-1} (Appendix A's reading
+ *                     of c_i; Algorithm 2 line 9 prints the reciprocal).
  *
  * Every pointer below is a DEVICE pointer unless it says host.  The library allocates
  * no device memory, never synchronises the device, and enqueues all work on desc->stream.  The
@@ -44,7 +51,7 @@ enum {
   AMLA_ERR_LAUNCH = -4        /* the HIP runtime refused a launch */
 };
 
-enum { AMLA_RESCALE_MUL = 0, AMLA_RESCALE_ADD = 1 };
+enum { AMLA_RESCALE_MUL = 0, AMLA_RESCALE_ADD = 1, AMLA_RESCALE_ADD_COMP = 2 };
 
 /* desc->flags */
 enum {
@@ -54,10 +61,12 @@ enum {
                                    exceeds it by more than 2^8; in between the softmax weights may
                                    grow up to 2^8 (same relative precision in bf16 and FP32), so the
                                    accumulator rescale becomes a rare event.  Same result up to
-                                   rounding. */
+                                   rounding.  Not available with AMLA_RESCALE_ADD_COMP, whose
+                                   reference follows the row max by construction. */
   AMLA_FLAG_ASM_KERNEL = 4      /* run the hand-scheduled assembly kernels (32-key steps, explicit
                                    MFMA / VALU / LDS interleave) instead of the compiler-built HIP
-                                   kernel (64-key steps).  SWITCHED OFF: rejected with
+                                   kernel (64-key steps); MUL and ADD variants only.  SWITCHED OFF:
+                                   rejected with
                                    AMLA_ERR_UNSUPPORTED unless the environment variable
                                    AMLA_ENABLE_ASM_KERNELS is "1", because these kernels have not
                                    yet passed on hardware. */
@@ -72,7 +81,7 @@ typedef struct amla_desc {
   int32_t block_size;          /* keys per cache block, must be 64 */
   int32_t num_blocks;          /* physical blocks in kv_cache */
   int32_t max_blocks_per_seq;  /* row stride of block_table */
-  int32_t variant;             /* AMLA_RESCALE_MUL or AMLA_RESCALE_ADD */
+  int32_t variant;             /* AMLA_RESCALE_MUL, AMLA_RESCALE_ADD or AMLA_RESCALE_ADD_COMP */
   int32_t num_splits;          /* split-KV factor: each sequence's blocks are cut into this many
                                   contiguous ranges processed by separate workgroups and merged
                                   by a combine kernel.  0 = library chooses from the shape. */

@@ -22,8 +22,9 @@ What it holds
                        without the BF16 scale compensation (lines 7-9 are the follow-up).
 * `flash_fp32_emulation` Algorithm 1 in FP32 with BF16 P (the paper's "Base", Section 5.1).
 * `amla_alg2_emulation` Algorithm 2 with its BF16 scale compensation, line by line in the paper's
-                       notation, with either printed definition of c_i (numerics study only: the
-                       kernels use two row sums instead).
+                       notation, with either printed definition of c_i.
+* `amla_comp_fp32_emulation` the same compensation restated in base 2 with one reference per row
+                       and integer-built N (the form of the kernels' ADD_COMP variant).
 * `frobenius_error`    the error metric of Section 5.1.
 
 Pins (tests/test_oracle_*.py): the worked example of Section 3.2 (0.5 <-> 126 * 2^23),
@@ -282,6 +283,57 @@ def amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="appendix", guard=1
         O = (O + (Pb @ Vb).astype(f32)).astype(f32)
         m, n_prev, c_prev = m_new, n, c
     return (O / (l * S16)[:, None]).astype(f32)
+
+
+def amla_comp_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, with_eps=True):
+    """Algorithm 2 with its compensation (lines 7-12, Appendix A's c_i) restated in base 2 with one
+    reference per row, the form a register-resident kernel takes: mu = rint(m) = -n_i,
+    S32 = 2^(m - mu), S16 = BF16(S32), c = S16 / S32, weights P = 2^(t - ref) with
+    ref = m - log2 S16 (so P = 2^(t - m) S16 and the largest weight of a row is S16, BF16-exact),
+    N = ((mu_prev - mu) clamped at -30) * 2^23 + rint(2^23 * 1.5 (c / c_prev - 1)) built in integer
+    arithmetic (no 1e-6 guard: that guard protects a truncating float-to-int cast), guarded add of
+    N on the accumulator.  Two row sums relative to ref, rescaled by the exact factor 2^(ref_prev -
+    ref): the FP32 sum of the unrounded weights gives lse, the sum of the BF16-rounded weights
+    normalises the output.  `with_eps=False` drops the mantissa term (what the compensation buys
+    is then visible)."""
+    f32 = np.float32
+    G, L = Q.shape[0], K.shape[0]
+    O = np.zeros((G, V.shape[1]), dtype=f32)
+    l32 = np.zeros(G, dtype=f32)
+    l16 = np.zeros(G, dtype=f32)
+    m = np.full(G, -np.inf, dtype=f32)
+    mu = c_prev = ref = None
+    cl2 = f32(scale * math.log2(math.e))
+    for lo in range(0, L, block):
+        Kb, Vb = K[lo:lo + block], V[lo:lo + block]
+        t = (Q @ Kb.T).astype(f32) * cl2
+        m = np.maximum(m, t.max(axis=1))
+        mu_new = np.rint(m)
+        S32 = np.exp2((m - mu_new).astype(f32)).astype(f32)
+        S16 = _round_bf16(S32)
+        c = (S16 / S32).astype(f32)
+        ref_new = (m - np.log2(S16).astype(f32)).astype(f32)
+        P = np.exp2((t - ref_new[:, None]).astype(f32)).astype(f32)
+        Pb = _round_bf16(P)
+        if mu is not None:
+            N = np.maximum(mu - mu_new, clamp).astype(np.int64) << 23
+            if with_eps:
+                eps = (f32(1.5) * ((c / c_prev).astype(f32) - f32(1))).astype(f32)
+                N = N + np.rint((eps * f32(2.0 ** 23)).astype(f32)).astype(np.int64)
+            I = as_int32(O).astype(np.int64)
+            R = np.clip(I + N[:, None], -(1 << 31), (1 << 31) - 1)       # saturating INT32 add
+            R = np.maximum(R, np.where(I < 0, -(1 << 31), 0))            # never below the signed zero
+            O = as_fp32(R.astype(np.int32)).copy()
+            a = np.exp2((ref - ref_new).astype(f32)).astype(f32)
+            l32 = (l32 * a).astype(f32)
+            l16 = (l16 * a).astype(f32)
+        l32 = (l32 + P.sum(axis=1, dtype=f32)).astype(f32)
+        l16 = (l16 + Pb.sum(axis=1, dtype=f32)).astype(f32)
+        O = (O + (Pb @ Vb).astype(f32)).astype(f32)
+        mu, c_prev, ref = mu_new, c, ref_new
+    out = O / l16[:, None]
+    lse = (ref.astype(np.float64) + np.log2(l32.astype(np.float64))) * LN2
+    return out, lse
 
 
 def flash_fp32_emulation(Q, K, V, scale, block=64):

@@ -14,8 +14,9 @@
 //   [V1]  online softmax in base 2; P rounded to bf16 straight into the B-operand layout of
 //         the second product (no cross-lane movement).
 //   [V2]  rescale of the accumulator registers: FP32 multiply (MUL variant) or guarded INT32
-//         add on the exponent field (ADD variant, Lemma 3.1), skipped when no row of the
-//         wave changed its reference.
+//         add on the exponent field (ADD variants, Lemma 3.1; ADD_COMP adds Algorithm 2's
+//         mantissa term to the same integer), skipped when no row of the wave changed its
+//         reference.
 //   [C2]  O^T += V^T P^T : A = V^T from the same LDS tile through the transposing LDS read
 //         (ds_read_b64_tr_b16), B = P registers.
 // The KV block is brought HBM -> LDS by direct-to-LDS loads (global_load_lds_dwordx4), double
@@ -79,6 +80,8 @@ struct DecodeParams {
 // Lemma 3.1 with a guard: x * 2^delta as an integer add of n23 = delta << 23 (delta <= 0) on the
 // bit pattern.  The saturating add pins a negative float whose exponent would go below zero at
 // 0x80000000 (-0.0); the max with the sign bit turns a wrapped positive float into +0.0.
+// n23 may also carry a small mantissa term of either sign (Algorithm 2 line 12): the guard
+// only concerns sums that leave the float's own sign range.
 __device__ __forceinline__ float exponent_add(float x, int n23) {
   const int i = __float_as_int(x);
   int r = __builtin_elementwise_add_sat(i, n23);
@@ -168,7 +171,10 @@ void amla_decode_kernel(const DecodeParams p) {
   for (int dt = 0; dt < kDv / 32; ++dt) acc[dt] = f32x16{0};
 
   float m_run = -INFINITY;   // running row max of t = s * scale * log2 e
-  float ref = 0.f;           // reference subtracted in the exponent: m_run (MUL) or rint(m_run) (ADD)
+  float ref = 0.f;           // reference subtracted in the exponent: m_run (MUL), rint(m_run) (ADD),
+                             // m_run - log2 S16 (ADD_COMP)
+  float mu_run = 0.f;        // ADD_COMP: rint(m_run) = -n_i
+  float c_run = 1.f;         // ADD_COMP: c_i = S16 / S32
   float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse)
   float l_b16 = 0.f;         // sum of the bf16-rounded weights (normalises the output)
 
@@ -234,13 +240,31 @@ void amla_decode_kernel(const DecodeParams p) {
     float ref_new;
     float alpha = 1.f;   // MUL: factor on the old accumulator
     int n23 = 0;         // ADD: (n_i - n_{i-1}) << 23, <= 0
-    ref_new = VARIANT == AMLA_RESCALE_MUL ? m_new : __builtin_rintf(m_new);
-    // lazy: keep the old reference (factor 1, shift 0) until the row max exceeds it by 2^8
-    if (LAZY && !first && !(m_new > ref + kLazyThreshold)) ref_new = ref;
-    if (VARIANT == AMLA_RESCALE_MUL) {
-      if (!first) alpha = fast_exp2(ref - ref_new);
+    if (VARIANT == AMLA_RESCALE_ADD_COMP) {
+      // Algorithm 2 lines 7-12 in base 2: S32 = 2^(m - mu) in [2^-1/2, 2^1/2], S16 its BF16
+      // rounding, weights 2^(t - m) S16 = 2^(t - (m - log2 S16)); the shift of the exponent field
+      // and the mantissa nudge 1.5 eps 2^23 travel in one integer
+      const float mu = __builtin_rintf(m_new);
+      const float s32 = fast_exp2(m_new - mu);
+      const float s16 = __uint_as_float(pack_bf16(s32, 0.f) << 16);
+      const float c_new = s16 / s32;
+      ref_new = m_new - fast_log2(s16);
+      if (!first) {
+        const float eps = 1.5f * (c_new / c_run - 1.f);
+        n23 = max((int)(mu_run - mu), -30) * (1 << 23) + (int)__builtin_rintf(eps * 8388608.f);
+        alpha = fast_exp2(ref - ref_new);   // the two row sums are scalars: exact factor
+      }
+      mu_run = mu;
+      c_run = c_new;
     } else {
-      if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
+      ref_new = VARIANT == AMLA_RESCALE_MUL ? m_new : __builtin_rintf(m_new);
+      // lazy: keep the old reference (factor 1, shift 0) until the row max exceeds it by 2^8
+      if (LAZY && !first && !(m_new > ref + kLazyThreshold)) ref_new = ref;
+      if (VARIANT == AMLA_RESCALE_MUL) {
+        if (!first) alpha = fast_exp2(ref - ref_new);
+      } else {
+        if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
+      }
     }
     m_run = m_new;
     ref = ref_new;
@@ -275,8 +299,13 @@ void amla_decode_kernel(const DecodeParams p) {
           for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
       }
     } else {
-      l_f32 = exponent_add(l_f32, n23) + psum;
-      l_b16 = exponent_add(l_b16, n23) + bsum;
+      if (VARIANT == AMLA_RESCALE_ADD_COMP) {
+        l_f32 = l_f32 * alpha + psum;
+        l_b16 = l_b16 * alpha + bsum;
+      } else {
+        l_f32 = exponent_add(l_f32, n23) + psum;
+        l_b16 = exponent_add(l_b16, n23) + bsum;
+      }
       if (force || __builtin_amdgcn_ballot_w64(n23 != 0) != 0) {
 #pragma unroll
         for (int dt = 0; dt < kDv / 32; ++dt)
@@ -454,7 +483,9 @@ bool desc_supported(const amla_desc* d) {
   if (d == nullptr) return false;
   if (d->d_qk != kDqk || d->d_v != kDv || d->block_size != kBlock) return false;
   if (d->batch < 1 || d->s_q < 1 || d->num_heads < 1 || d->num_blocks < 1 || d->max_blocks_per_seq < 1) return false;
-  if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD) return false;
+  if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD && d->variant != AMLA_RESCALE_ADD_COMP)
+    return false;
+  if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL)) != 0) return false;
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
@@ -537,7 +568,9 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     const long long grid = streams_pad * p.n_tiles;
     if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
     const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
-    auto kern = desc->variant == AMLA_RESCALE_ADD
+    auto kern = desc->variant == AMLA_RESCALE_ADD_COMP
+                    ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
+                : desc->variant == AMLA_RESCALE_ADD
                     ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
                     : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -56,6 +56,10 @@ def test_argument_validation_error_codes(amla):
     assert _call(amla, good, q=24) == amla.AMLA_ERR_UNSUPPORTED          # misaligned pointer
     assert _call(amla, good, scale=float("nan")) == amla.AMLA_ERR_UNSUPPORTED
     assert _call(amla, good, scale=-1.0) == amla.AMLA_ERR_UNSUPPORTED
+    comp_lazy = amla.make_desc(2, 1, 16, 8, 4, variant=amla.AMLA_RESCALE_ADD_COMP,
+                               flags=amla.AMLA_FLAG_LAZY_RESCALE)
+    assert _call(amla, comp_lazy) == amla.AMLA_ERR_UNSUPPORTED           # the compensated reference follows the max
+    assert amla.amla_effective_splits(amla.make_desc(2, 1, 16, 8, 4, variant=amla.AMLA_RESCALE_ADD_COMP)) >= 1
     split = amla.make_desc(2, 1, 16, 8, 4, num_splits=2)
     assert _call(amla, split) == amla.AMLA_ERR_WORKSPACE                 # no workspace given
     split.workspace = 4096

@@ -207,6 +207,51 @@ def test_algorithm2_compensation_and_the_two_readings_of_c():
         assert e(bf(base)) <= e(bf(ours)) < 1.8 * e(bf(base)), (sigma, e(bf(ours)), e(bf(base)))
 
 
+def test_compensation_restated_in_base_two_matches_algorithm2():
+    """The one-reference-per-row form (ref = m - log2 S16, N built in integers, two row sums) is the
+    same method as Algorithm 2 line by line: its error against the fp64 definition is the line-by-line
+    emulation's and Base's within a few per cent, its lse is the definition's, and dropping the
+    mantissa term eps makes flat rows (many small maxima updates, no dominant key) measurably worse."""
+    rng = np.random.default_rng(12)
+    def bf(x):
+        return orc._round_bf16(x.astype(np.float32))
+    for sigma in (1.0, 4.0):
+        Q = bf(rng.standard_normal((16, 576)) * sigma)
+        K = bf(rng.standard_normal((4096, 576)))
+        V = K[:, :512]
+        want, want_lse = orc.attention_rows(Q.astype(np.float64), K.astype(np.float64), 192 ** -0.5)
+        e = lambda x: orc.frobenius_error(bf(x), want)
+        comp, lse = orc.amla_comp_fp32_emulation(Q, K, V, 192 ** -0.5)
+        alg2 = orc.amla_alg2_emulation(Q, K, V, 192 ** -0.5, block=64)
+        base, _ = orc.flash_fp32_emulation(Q, K, V, 192 ** -0.5)
+        assert abs(e(comp) - e(alg2)) < 0.03 * e(alg2), (sigma, e(comp), e(alg2))
+        assert abs(e(comp) - e(base)) < 0.06 * e(base), (sigma, e(comp), e(base))
+        assert np.abs(lse - want_lse).max() < 2e-5
+        assert np.abs(comp.astype(np.float64) - want).max() < 1e-2
+        if sigma == 1.0:
+            no_eps, _ = orc.amla_comp_fp32_emulation(Q, K, V, 192 ** -0.5, with_eps=False)
+            assert e(no_eps) > 1.05 * e(comp), (e(no_eps), e(comp))
+
+
+def test_compensation_survives_zero_values_and_the_clamp():
+    """Zero value columns stay at most a few subnormal steps from zero under the guarded add (a
+    positive mantissa term turns the bit pattern 0 into a subnormal, a negative one is caught by the
+    guard), and a row max that jumps by far more than 2^30 between blocks (old accumulator
+    irrelevant) still gives the definition's result."""
+    rng = np.random.default_rng(13)
+    def bf(x):
+        return orc._round_bf16(x.astype(np.float32))
+    Q = bf(rng.standard_normal((8, 576)) * 3)
+    K = bf(rng.standard_normal((512, 576)))
+    K[300] = bf(Q[0] * 4)             # a late key far above everything before it for row 0
+    K[:, 5] = 0.0
+    want, want_lse = orc.attention_rows(Q.astype(np.float64), K.astype(np.float64), 192 ** -0.5)
+    out, lse = orc.amla_comp_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5)
+    assert np.all(np.abs(out[:, 5]) < 2.0 ** -126)
+    assert np.abs(out.astype(np.float64) - want).max() < 1e-2 * max(1.0, np.abs(want).max())
+    assert np.abs(lse - want_lse).max() < 1e-4
+
+
 # -------------------------------------------------------------------- accounting pins
 def test_table2_arithmetic_intensity():
     for name, qh, kvh, sq, printed, kind in _rows("table2_arithmetic_intensity.txt"):
