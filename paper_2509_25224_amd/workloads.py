@@ -80,13 +80,19 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(stream)]))
 
 
-def _normal_bf16(rng: np.random.Generator, shape, sigma: float) -> np.ndarray:
+def _normal_bf16(rng: np.random.Generator, shape, sigma: float, dist: str = "normal") -> np.ndarray:
+    """dist = "normal": N(0, sigma^2); dist = "uniform": U(-sigma, sigma).  Drawn in FP32, rounded to bf16."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16)
     step = 1 << 24                      # bounded temporary memory for the big pools
     for lo in range(0, n, step):
         hi = min(n, lo + step)
-        x = rng.standard_normal(hi - lo, dtype=np.float32)
+        if dist == "normal":
+            x = rng.standard_normal(hi - lo, dtype=np.float32)
+        elif dist == "uniform":
+            x = rng.random(hi - lo, dtype=np.float32) * np.float32(2) - np.float32(1)
+        else:
+            raise ValueError(dist)
         if sigma != 1.0:
             x *= np.float32(sigma)
         out[lo:hi] = f32_to_bf16_bits(x)
@@ -96,8 +102,11 @@ def _normal_bf16(rng: np.random.Generator, shape, sigma: float) -> np.ndarray:
 def make_case(name: str, seed: int, batch: int, s_q: int, heads: int, seqlens,
               q_sigma: float = 1.0, kv_sigma: float = 1.0, table: str = "random",
               spare_frac: float = 0.0, softmax_scale: float = SOFTMAX_SCALE,
-              max_blocks_per_seq: int | None = None) -> DecodeCase:
+              max_blocks_per_seq: int | None = None, dist: str = "normal") -> DecodeCase:
     """Build one decode problem.
+
+    dist = "normal": q ~ N(0, q_sigma^2), cache ~ N(0, kv_sigma^2); dist = "uniform": U(-q_sigma, q_sigma)
+    and U(-kv_sigma, kv_sigma).
 
     table = "identity": sequence b owns consecutive physical blocks in order.
     table = "random"  : the physical blocks are a random permutation dealt to the
@@ -115,8 +124,8 @@ def make_case(name: str, seed: int, batch: int, s_q: int, heads: int, seqlens,
         assert max_blocks_per_seq >= mbs
         mbs = int(max_blocks_per_seq)
 
-    q_bits = _normal_bf16(_rng(seed, 0), (batch, s_q, heads, D_QK), q_sigma)
-    kv_bits = _normal_bf16(_rng(seed, 1), (num_blocks, BLOCK, D_QK), kv_sigma)
+    q_bits = _normal_bf16(_rng(seed, 0), (batch, s_q, heads, D_QK), q_sigma, dist)
+    kv_bits = _normal_bf16(_rng(seed, 1), (num_blocks, BLOCK, D_QK), kv_sigma, dist)
 
     if table == "identity":
         phys = np.arange(num_blocks, dtype=np.int32)
@@ -163,3 +172,13 @@ def make_table5_case(s_q: int, s_k: int, seed: int = 5) -> DecodeCase:
     one shared KV head, BF16, every sequence s_k long, s_q in {1, 2}, cache laid out contiguously
     (identity block table)."""
     return make_case(f"table5_sq{s_q}_sk{s_k}", seed, 96, s_q, 128, [s_k] * 96, table="identity")
+
+
+def make_accuracy_case(family: str, param: float, seed: int = 6, batch: int = 2, heads: int = 128) -> DecodeCase:
+    """An input of the paper's accuracy experiment (Section 5.1, Tables 3 and 4): Q and the cache drawn
+    from N(0, param^2) (family "n") or U(-param, param) (family "u"), context length 8K, BF16, V the
+    first 512 columns of the cached row, softmax scale 1 / sqrt(576) (Eq. (1) with D_k = 576; the
+    setting under which FP32 emulations of Algorithms 1 and 2 reproduce the printed errors)."""
+    dist = {"n": "normal", "u": "uniform"}[family]
+    return make_case(f"accuracy_{family}{param:g}", seed, batch, 1, heads, [8192] * batch, q_sigma=param,
+                     kv_sigma=param, softmax_scale=D_QK ** -0.5, dist=dist)

@@ -181,6 +181,44 @@ def test_accuracy_level_matches_the_papers_table():
     assert abs(e_amla - e_base) / e_base < 0.15
 
 
+def _accuracy_sample(family, param, seed, rows=32, keys=8192):
+    rng = np.random.default_rng(seed)
+    draw = (lambda shape: rng.standard_normal(shape) * param) if family == "n" else \
+           (lambda shape: rng.uniform(-param, param, shape))
+    Q = orc._round_bf16(draw((rows, 576)).astype(np.float32))
+    K = orc._round_bf16(draw((keys, 576)).astype(np.float32))
+    return Q, K
+
+
+@pytest.mark.parametrize("family,param,base_printed,amla_printed",
+                         [(f, float(p), float(b), float(a)) for f, p, b, a in _rows("table3_table4_accuracy.txt")])
+def test_emulations_reproduce_the_printed_accuracy_tables(family, param, base_printed, amla_printed):
+    """Tables 3 and 4: the FP32 emulation of Algorithm 1 ("Base") and the line-by-line emulation of
+    Algorithm 2 with Appendix A's c_i ("AMLA"), outputs rounded to BF16, land on the printed errors:
+    within 1.5 % on the two flat columns N(0,1) and U(-1,1), where one sample of 32 rows already has
+    0.5 % spread and the printed AMLA-minus-Base gap of 2 % is resolved, and within 7 % (mean of three
+    samples; the spread of one sample is 2-6 %) on the others.  With line 9's c_i as printed the same
+    emulation gives 3.1e-3 on N(0,1), 70 % above the printed 1.81e-3."""
+    scale = 576 ** -0.5
+    flat = param == 1.0
+    e_base, e_amla = [], []
+    for seed in ((100,) if flat else (100, 101, 102)):
+        Q, K = _accuracy_sample(family, param, seed)
+        V = K[:, :512]
+        want, _ = orc.attention_rows(Q.astype(np.float64), K.astype(np.float64), scale)
+        e = lambda x: orc.frobenius_error(orc._round_bf16(np.asarray(x, dtype=np.float32)), want)
+        e_base.append(e(orc.flash_fp32_emulation(Q, K, V, scale, block=512)[0]))
+        e_amla.append(e(orc.amla_alg2_emulation(Q, K, V, scale, block=512)))
+        if flat and family == "n":
+            printed_c = e(orc.amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="algorithm"))
+            assert printed_c > 1.5 * amla_printed, printed_c
+    tol = 0.015 if flat else 0.07
+    assert abs(np.mean(e_base) - base_printed) < tol * base_printed, (np.mean(e_base), base_printed)
+    assert abs(np.mean(e_amla) - amla_printed) < tol * amla_printed, (np.mean(e_amla), amla_printed)
+    if flat:
+        assert e_amla[0] > e_base[0]          # the printed ordering on these columns
+
+
 def test_algorithm2_compensation_and_the_two_readings_of_c():
     """Algorithm 2 line 9 prints c_i = S32 / S16, Appendix A defines c_i = r_i / r'_i = S16 / S32.  With
     the appendix's definition the compensated recurrence, outputs rounded to BF16, is as accurate as

@@ -97,3 +97,31 @@ def test_wrong_exponent_shift_is_caught():
         return orc.as_fp32(I.astype(np.int32))
     assert float(orc.exponent_add(np.float32(0.5), 1)) == 1.0
     assert float(bad_add(np.float32(0.5), 1)) != 1.0
+
+
+def test_truncating_bf16_cast_is_caught_by_the_printed_accuracy_tables(monkeypatch):
+    """Rounding P and the output to BF16 by truncation instead of round-to-nearest-even about doubles the
+    error of both emulations; Table 3's N(0,1) column no longer comes out."""
+    import test_oracle_method as method
+
+    def truncate(x32):
+        bits = np.asarray(x32, dtype=np.float32).view(np.uint32) & np.uint32(0xFFFF0000)
+        return bits.view(np.float32)
+    method.test_emulations_reproduce_the_printed_accuracy_tables("n", 1.0, 1.77e-3, 1.81e-3)
+    monkeypatch.setattr(orc, "_round_bf16", truncate)
+    with pytest.raises(AssertionError):
+        method.test_emulations_reproduce_the_printed_accuracy_tables("n", 1.0, 1.77e-3, 1.81e-3)
+
+
+def test_dropping_the_compensation_is_caught_by_the_printed_accuracy_tables(monkeypatch):
+    """Algorithm 2 without lines 7-9 and 12 (S16 = 1, eps = 0: the weights 2^(t - m) S32 are rounded as
+    they are) no longer reproduces the AMLA row of Table 3 on a peaked column."""
+    import test_oracle_method as method
+
+    def no_compensation(Q, K, V, scale, block=512, c_reading="appendix", guard=1e-6):
+        out, _ = orc.amla_fp32_emulation(Q, K, V, scale, block=block)
+        return out
+    method.test_emulations_reproduce_the_printed_accuracy_tables("n", 4.0, 1.51e-3, 1.51e-3)
+    monkeypatch.setattr(orc, "amla_alg2_emulation", no_compensation)
+    with pytest.raises(AssertionError):
+        method.test_emulations_reproduce_the_printed_accuracy_tables("n", 4.0, 1.51e-3, 1.51e-3)
