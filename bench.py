@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
+    ap.add_argument("--balanced", action="store_true",
+                    help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
+                         "means workers)")
     ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy", "add_comp"], default="auto",
                     help="auto = add_lazy if its output agrees with the strict add variant on this input, else add")
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
@@ -128,8 +131,11 @@ def main():
     out = torch.empty((case.batch, case.s_q, case.heads, 512), dtype=torch.bfloat16, device=dev)
     lse = torch.empty((case.batch, case.s_q, case.heads), dtype=torch.float32, device=dev)
 
+    impl_flag = amla.AMLA_FLAG_ASM_KERNEL if args.impl == "asm" else 0
+    if args.balanced:
+        impl_flag |= amla.AMLA_FLAG_BALANCED
     desc = amla.make_desc(case.batch, case.s_q, case.heads, case.num_blocks, case.max_blocks_per_seq,
-                          num_splits=args.splits)
+                          num_splits=args.splits, flags=impl_flag)
     splits = amla.amla_effective_splits(desc)
     ws_bytes = amla.amla_workspace_bytes(desc)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
@@ -138,8 +144,6 @@ def main():
                 "mul_lazy": (amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE),
                 "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE),
                 "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0)}
-
-    impl_flag = amla.AMLA_FLAG_ASM_KERNEL if args.impl == "asm" else 0
 
     def step(name, o=out, l=lse):
         v, f = VARIANTS[name]
@@ -185,7 +189,8 @@ def main():
         "config": {"workload": f"{workload_tag}: batch {case.batch}, s_q {case.s_q}, "
                                f"{case.heads} heads, sum kv_len {case.total_kv}, paged bf16 latent cache "
                                f"(block 64), d_qk 576 / d_v 512",
-                   "variant": chosen, "kernel_build": args.impl, "kv_splits": splits, "seed": case.seed},
+                   "variant": chosen, "kernel_build": args.impl, "kv_splits": splits, "balanced": bool(args.balanced),
+                   "seed": case.seed},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,

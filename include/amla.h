@@ -72,6 +72,20 @@ enum {
                                    yet passed on hardware. */
 };
 
+/* desc->flags, continued */
+enum {
+  AMLA_FLAG_BALANCED = 8        /* decomposition for ragged batches (compiler-built kernel only): the 64-key
+                                   blocks of all sequences are laid end to end and cut into equal
+                                   ranges, one per worker workgroup; a worker walks its range sequence
+                                   by sequence, and the pieces of a sequence are merged like split-KV
+                                   partials.  desc->num_splits then means the number of workers
+                                   (0 = library chooses), and the workspace holds one slot per piece
+                                   (amla_workspace_bytes answers for this flag too).  SWITCHED OFF:
+                                   rejected with AMLA_ERR_UNSUPPORTED unless the environment variable
+                                   AMLA_ENABLE_BALANCED is "1", because this index arithmetic has not
+                                   yet run on hardware. */
+};
+
 typedef struct amla_desc {
   int32_t batch;               /* B >= 1 */
   int32_t s_q;                 /* query tokens per sequence, >= 1 */
@@ -154,6 +168,19 @@ int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* s
  * quotes both a theoretical and a throttled peak).  1 <= iters <= 2^22, 1 <= workgroups <= 65535.
  */
 int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stream);
+
+/*
+ * amla_plan_segments -- host-only view of the balanced decomposition (AMLA_FLAG_BALANCED), computed
+ * with the same integer routines the kernels use; for tests and for sizing.  `seqlens` is a HOST
+ * array of `batch` lengths.  Writes up to `capacity` pieces as rows of six int32
+ * (worker, sequence, first block, end block, workspace slot, covers-whole-sequence) to `pieces`
+ * (host) in the order the workers produce them, the number of pieces to *n_pieces, and for every
+ * sequence the first and last worker that meet it (as the combine kernel derives them; -1, -1 for
+ * an empty sequence) to seq_workers[2 * batch] (host).  Returns AMLA_ERR_WORKSPACE when
+ * `capacity` was too small (*n_pieces is still the full count).
+ */
+int amla_plan_segments(const int32_t* seqlens, int32_t batch, int32_t workers, int32_t* pieces, int32_t capacity,
+                       int32_t* n_pieces, int32_t* seq_workers);
 
 /* amla_status_string -- static, NUL-terminated description of a status code (host). */
 const char* amla_status_string(int status);

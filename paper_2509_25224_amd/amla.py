@@ -22,9 +22,10 @@ AMLA_RESCALE_ADD_COMP = 2
 AMLA_FLAG_NO_SKIP = 1
 AMLA_FLAG_LAZY_RESCALE = 2
 AMLA_FLAG_ASM_KERNEL = 4
+AMLA_FLAG_BALANCED = 8
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
-           "amla_mfma_probe", "amla_status_string")
+           "amla_mfma_probe", "amla_plan_segments", "amla_status_string")
 
 
 class AmlaDesc(ctypes.Structure):
@@ -56,6 +57,9 @@ lib.amla_exponent_add.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_siz
                                   ctypes.c_void_p]
 lib.amla_mfma_probe.restype = ctypes.c_int
 lib.amla_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+lib.amla_plan_segments.restype = ctypes.c_int
+lib.amla_plan_segments.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                   ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
 lib.amla_status_string.restype = ctypes.c_char_p
 lib.amla_status_string.argtypes = [ctypes.c_int]
 
@@ -155,3 +159,22 @@ def amla_mfma_probe(iters: int, workgroups: int) -> float:
     if st != AMLA_OK:
         raise AmlaError(st)
     return flops.value
+
+
+def amla_plan_segments(seqlens, workers: int):
+    """Host view of the balanced decomposition for the given lengths (any int sequence): returns
+    (pieces int32 [n, 6]: worker, sequence, first block, end block, slot, full; seq_workers int32
+    [batch, 2]: first and last worker meeting each sequence, -1 for an empty one)."""
+    import numpy as np
+
+    lens = np.ascontiguousarray(np.asarray(seqlens, dtype=np.int32))
+    batch = int(lens.shape[0])
+    cap = int(workers) + batch
+    pieces = np.zeros((cap, 6), dtype=np.int32)
+    seq_workers = np.zeros((batch, 2), dtype=np.int32)
+    n = ctypes.c_int32(0)
+    st = lib.amla_plan_segments(lens.ctypes.data, batch, int(workers), pieces.ctypes.data, cap, ctypes.byref(n),
+                                seq_workers.ctypes.data)
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return pieces[:n.value].copy(), seq_workers

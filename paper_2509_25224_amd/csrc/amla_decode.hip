@@ -30,6 +30,7 @@
 #include <mutex>
 
 #include "amla.h"
+#include "amla_plan.h"
 
 namespace {
 
@@ -73,8 +74,9 @@ struct DecodeParams {
   int32_t n_tiles;          // ceil(G / 128)
   int32_t n_splits;
   int32_t max_blocks;
-  int32_t n_streams;        // batch * n_splits
+  int32_t n_streams;        // batch * n_splits; balanced decomposition: number of workers
   int32_t flags;
+  int32_t num_blocks;       // physical blocks in the pool (the balanced kernel clamps table entries)
 };
 
 // Lemma 3.1 with a guard: x * 2^delta as an integer add of n23 = delta << 23 (delta <= 0) on the
@@ -154,212 +156,94 @@ void amla_decode_kernel(const DecodeParams p) {
   const bool row_ok = row < p.rows;
   const size_t grow = (size_t)b * p.rows + (row_ok ? row : 0);
 
-  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].
-  bf16x8 qf[kDqk / 16];
-  {
-    const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
+#define AMLA_PIECE_BALANCED 0
+#define AMLA_PIECE_PHYS(j) __builtin_amdgcn_readfirstlane(tab[j])
+#include "amla_decode_piece.inc"
+#undef AMLA_PIECE_PHYS
+#undef AMLA_PIECE_BALANCED
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
 #pragma unroll
-    for (int ks = 0; ks < kDqk / 16; ++ks) {
-      // rows past the end of the sequence's row range read row 0 (valid memory); their
-      // results are never stored
-      qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
-    }
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int u = __shfl_up(v, o);
+    if (lane >= o) v += u;
   }
+  return v;
+}
 
-  f32x16 acc[kDv / 32];
-#pragma unroll
-  for (int dt = 0; dt < kDv / 32; ++dt) acc[dt] = f32x16{0};
+// The same loop under the balanced decomposition: workgroup = (worker, row tile); the worker's share
+// of the batch's concatenated block list is walked piece by piece (amla_plan.h).  p.n_streams is the
+// number of workers.
+template <int VARIANT, bool LAZY>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void amla_decode_balanced_kernel(const DecodeParams p) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
+  LDS_PTR(uint8_t) smem = (LDS_PTR(uint8_t))smem_raw;
 
-  float m_run = -INFINITY;   // running row max of t = s * scale * log2 e
-  float ref = 0.f;           // reference subtracted in the exponent: m_run (MUL), rint(m_run) (ADD),
-                             // m_run - log2 S16 (ADD_COMP)
-  float mu_run = 0.f;        // ADD_COMP: rint(m_run) = -n_i
-  float c_run = 1.f;         // ADD_COMP: c_i = S16 / S32
-  float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse)
-  float l_b16 = 0.f;         // sum of the bf16-rounded weights (normalises the output)
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31;
+  const int h = lane >> 5;
 
-  const int32_t* tab = p.table + (size_t)b * p.max_blocks;
-  const uint8_t* kvb = reinterpret_cast<const uint8_t*>(p.kv);
-  const size_t blk_bytes = (size_t)kBlock * kRowBytes;
+  // workers go round-robin over the 8 XCDs; the row tiles of one worker sit next to each other on
+  // the same XCD and share the worker's KV blocks in that XCD's L2
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int stream = (slot / p.n_tiles) * 8 + xcd;
+  const int tile = slot % p.n_tiles;
+  if (stream >= p.n_streams) return;
 
-  if (j0 < j1) {
-    const int phys = __builtin_amdgcn_readfirstlane(tab[j0]);
-    issue_tile_loads(kvb + (size_t)phys * blk_bytes, smem, wave, lane);
+  const int row = tile * kRowsPerWg + wave * 32 + l32;       // row within the sequence
+  const bool row_ok = row < p.rows;
+
+  // total number of blocks of the batch, then this worker's range of the concatenated list
+  int total = 0;
+  for (int c = 0; c < p.batch; c += 64) {
+    const int i = c + lane;
+    total += wave_sum(i < p.batch ? plan_blocks_of(plan_len(p.seqlens[i], p.max_blocks, kBlock), kBlock) : 0);
   }
-
-  // per-lane LDS offsets of the operand reads
-  const int k_off = l32 * kLdsRow + h * 16;                       // K rows, A operand of [C1]
-  const int g16 = lane >> 4, i16 = lane & 15;
-  const int v_off = (4 * (g16 >> 1) + (i16 >> 2)) * kLdsRow + (16 * (g16 & 1) + 4 * (i16 & 3)) * 2;
-
-  for (int j = j0; j < j1; ++j) {
-    LDS_PTR(uint8_t) buf = smem + ((j - j0) & 1) * kTileBytes;
-    // Block j has landed for this wave; the barrier makes that true for all waves and also
-    // guarantees everyone is done reading the other buffer, which is refilled next.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (j + 1 < j1) {
-      const int phys = __builtin_amdgcn_readfirstlane(tab[j + 1]);
-      issue_tile_loads(kvb + (size_t)phys * blk_bytes, smem + ((j + 1 - j0) & 1) * kTileBytes, wave, lane);
+  total = __builtin_amdgcn_readfirstlane(total);
+  const long long g0 = plan_worker_begin(stream, total, p.n_streams);
+  const long long g1 = plan_worker_begin(stream + 1, total, p.n_streams);
+  if (g0 >= g1) return;
+  // the sequence that holds global block g0, and g0's position in it
+  int b0 = -1, jstart = 0, base = 0;
+  for (int c = 0; c < p.batch && b0 < 0; c += 64) {
+    const int i = c + lane;
+    const int nbi = i < p.batch ? plan_blocks_of(plan_len(p.seqlens[i], p.max_blocks, kBlock), kBlock) : 0;
+    const int incl = wave_inclusive_scan(nbi, lane);
+    const int excl = incl - nbi;
+    const bool hit = (long long)base + excl <= g0 && g0 < (long long)base + incl;
+    const unsigned long long mask = __builtin_amdgcn_ballot_w64(hit);
+    if (mask != 0) {
+      const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(mask));
+      b0 = c + l;
+      jstart = (int)(g0 - ((long long)base + __builtin_amdgcn_readlane(excl, l)));
     }
-
-    // ---- [C1] S^T[64 keys x 32 rows] ----
-    f32x16 s[2];
-    s[0] = f32x16{0};
-    s[1] = f32x16{0};
-#pragma unroll
-    for (int ks = 0; ks < kDqk / 16; ++ks) {
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        const bf16x8 a = *(LDS_PTR(bf16x8))(buf + k_off + kt * 32 * kLdsRow + ks * 32);
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kt], 0, 0, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // ---- [V1] online softmax ----
-    const int rem = kv_len - j * kBlock;           // valid keys in this block (>= 1)
-    if (rem < kBlock) {
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = 32 * kt + 4 * h + 8 * (r >> 2) + (r & 3);
-          if (key >= rem) s[kt][r] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * p.scale_log2e);
-
-    const bool first = (j == j0);
-    float ref_new;
-    float alpha = 1.f;   // MUL: factor on the old accumulator
-    int n23 = 0;         // ADD: (n_i - n_{i-1}) << 23, <= 0
-    if (VARIANT == AMLA_RESCALE_ADD_COMP) {
-      // Algorithm 2 lines 7-12 in base 2: S32 = 2^(m - mu) in [2^-1/2, 2^1/2], S16 its BF16
-      // rounding, weights 2^(t - m) S16 = 2^(t - (m - log2 S16)); the shift of the exponent field
-      // and the mantissa nudge 1.5 eps 2^23 travel in one integer
-      const float mu = __builtin_rintf(m_new);
-      const float s32 = fast_exp2(m_new - mu);
-      const float s16 = __uint_as_float(pack_bf16(s32, 0.f) << 16);
-      const float c_new = s16 / s32;
-      ref_new = m_new - fast_log2(s16);
-      if (!first) {
-        const float eps = 1.5f * (c_new / c_run - 1.f);
-        n23 = max((int)(mu_run - mu), -30) * (1 << 23) + (int)__builtin_rintf(eps * 8388608.f);
-        alpha = fast_exp2(ref - ref_new);   // the two row sums are scalars: exact factor
-      }
-      mu_run = mu;
-      c_run = c_new;
-    } else {
-      ref_new = VARIANT == AMLA_RESCALE_MUL ? m_new : __builtin_rintf(m_new);
-      // lazy: keep the old reference (factor 1, shift 0) until the row max exceeds it by 2^8
-      if (LAZY && !first && !(m_new > ref + kLazyThreshold)) ref_new = ref;
-      if (VARIANT == AMLA_RESCALE_MUL) {
-        if (!first) alpha = fast_exp2(ref - ref_new);
-      } else {
-        if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
-      }
-    }
-    m_run = m_new;
-    ref = ref_new;
-
-    float psum = 0.f;
-    unsigned pk[16];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const float p0 = fast_exp2(__builtin_fmaf(s[kt][r], p.scale_log2e, -ref_new));
-        const float p1 = fast_exp2(__builtin_fmaf(s[kt][r + 1], p.scale_log2e, -ref_new));
-        psum += p0 + p1;
-        pk[kt * 8 + (r >> 1)] = pack_bf16(p0, p1);
-      }
-    float bsum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-      bsum += __uint_as_float(pk[i] << 16) + __uint_as_float(pk[i] & 0xffff0000u);
-    psum += __shfl_xor(psum, 32);
-    bsum += __shfl_xor(bsum, 32);
-
-    // ---- [V2] rescale the accumulator registers ----
-    const bool force = (p.flags & AMLA_FLAG_NO_SKIP) && !first;
-    if (VARIANT == AMLA_RESCALE_MUL) {
-      l_f32 = l_f32 * alpha + psum;
-      l_b16 = l_b16 * alpha + bsum;
-      if (force || __builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
-#pragma unroll
-        for (int dt = 0; dt < kDv / 32; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
-      }
-    } else {
-      if (VARIANT == AMLA_RESCALE_ADD_COMP) {
-        l_f32 = l_f32 * alpha + psum;
-        l_b16 = l_b16 * alpha + bsum;
-      } else {
-        l_f32 = exponent_add(l_f32, n23) + psum;
-        l_b16 = exponent_add(l_b16, n23) + bsum;
-      }
-      if (force || __builtin_amdgcn_ballot_w64(n23 != 0) != 0) {
-#pragma unroll
-        for (int dt = 0; dt < kDv / 32; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[dt][r] = exponent_add(acc[dt][r], n23);
-      }
-    }
-
-    // ---- [C2] O^T[512 x 32 rows] += V^T P^T ----
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      const i32x4 pb = {(int)pk[4 * st], (int)pk[4 * st + 1], (int)pk[4 * st + 2], (int)pk[4 * st + 3]};
-      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
-#pragma unroll
-      for (int dt = 0; dt < kDv / 32; ++dt) {
-        LDS_PTR(uint8_t) va = buf + v_off + st * 16 * kLdsRow + dt * 64;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))va);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(va + 8 * kLdsRow));
-        const i32x2 lo2 = __builtin_bit_cast(i32x2, lo), hi2 = __builtin_bit_cast(i32x2, hi);
-        const i32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
-        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pfrag, acc[dt], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
+    base += __builtin_amdgcn_readlane(incl, 63);
   }
-
-  // ---- epilogue (Algorithm 1 line 9 / Algorithm 2 line 20) ----
-  const float inv = l_b16 > 0.f ? 1.f / l_b16 : 0.f;
-  const float lse = l_f32 > 0.f ? (ref + fast_log2(l_f32)) * 0.6931471805599453f : -INFINITY;
-  if (!row_ok) return;
-  if (p.n_splits == 1) {
-    uint16_t* orow = p.out + grow * kDv;
-#pragma unroll
-    for (int dt = 0; dt < kDv / 32; ++dt)
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const unsigned w0 = pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv);
-        const unsigned w1 = pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv);
-        const i32x2 w = {(int)w0, (int)w1};
-        *reinterpret_cast<i32x2*>(orow + dt * 32 + 4 * h + 8 * rg) = w;
-      }
-    if (p.lse != nullptr && h == 0) p.lse[grow] = lse;
-  } else {
-    const size_t prow = (size_t)split * p.batch * p.rows + grow;
-    float* orow = p.part_o + prow * kDv;
-#pragma unroll
-    for (int dt = 0; dt < kDv / 32; ++dt)
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const f32x4 w = {acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv, acc[dt][4 * rg + 2] * inv,
-                         acc[dt][4 * rg + 3] * inv};
-        *reinterpret_cast<f32x4*>(orow + dt * 32 + 4 * h + 8 * rg) = w;
-      }
-    if (h == 0) p.part_lse[prow] = lse;
+  if (b0 < 0) return;   // unreachable when g0 < total
+  PlanWalk walk = {b0, jstart, g1 - g0};
+  while (walk.left > 0 && walk.b < p.batch) {
+    const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[walk.b]), p.max_blocks, kBlock);
+    PlanPiece piece;
+    if (!plan_next(&walk, plan_blocks_of(kv_len, kBlock), &piece)) continue;
+    [&](const int b, const int j0, const int j1, const bool to_final) __attribute__((always_inline)) {
+    const size_t slot_row = ((size_t)stream + b) * p.rows;   // slot worker + sequence < n_streams + batch - 1
+    const size_t grow = (size_t)b * p.rows + (row_ok ? row : 0);
+#define AMLA_PIECE_BALANCED 1
+#define AMLA_PIECE_PHYS(j) min(max(__builtin_amdgcn_readfirstlane(tab[j]), 0), p.num_blocks - 1)
+#include "amla_decode_piece.inc"
+#undef AMLA_PIECE_PHYS
+#undef AMLA_PIECE_BALANCED
+    }(piece.b, piece.j0, piece.j1, piece.full != 0);
   }
 }
 
@@ -390,6 +274,57 @@ __global__ __launch_bounds__(128) void amla_combine_kernel(const float* __restri
   const i32x2 w = {(int)pack_bf16(o[0] * inv, o[1] * inv), (int)pack_bf16(o[2] * inv, o[3] * inv)};
   *reinterpret_cast<i32x2*>(out + (size_t)row * kDv + 4 * threadIdx.x) = w;
   if (lse != nullptr && threadIdx.x == 0) lse[row] = tot > 0.f ? mx + __logf(tot) : -INFINITY;
+}
+
+// The same merge for the balanced decomposition: the pieces of sequence b are those of the workers
+// whose ranges meet the sequence's span of the concatenated block list; piece (w, b) sits in slot
+// w + b.  A sequence with a single piece was written in final form by the decode kernel; a
+// sequence without blocks gets its zeros here.  One 128-thread workgroup per row.
+__global__ __launch_bounds__(128) void amla_combine_balanced_kernel(const float* __restrict__ part_o,
+                                                                   const float* __restrict__ part_lse,
+                                                                   const int32_t* __restrict__ seqlens,
+                                                                   uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                                   int batch, int rows, int workers, int max_blocks) {
+  const int b = blockIdx.x / rows;
+  const int r = blockIdx.x - b * rows;
+  if (b >= batch) return;
+  const int lane = threadIdx.x & 63;
+  int total = 0, before = 0;
+  for (int c = 0; c < batch; c += 64) {
+    const int i = c + lane;
+    const int nbi = i < batch ? plan_blocks_of(plan_len(seqlens[i], max_blocks, kBlock), kBlock) : 0;
+    total += wave_sum(nbi);
+    before += wave_sum(i < b ? nbi : 0);
+  }
+  const int nb = plan_blocks_of(plan_len(seqlens[b], max_blocks, kBlock), kBlock);
+  const size_t grow = (size_t)b * rows + r;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  float tot = 0.f, mx = -INFINITY;
+  if (nb > 0) {
+    const int w_lo = (int)plan_worker_of_block(before, total, workers);
+    const int w_hi = (int)plan_worker_of_block((long long)before + nb - 1, total, workers);
+    if (w_lo == w_hi) return;   // a full piece: the decode kernel wrote out and lse itself
+    for (int w = w_lo; w <= w_hi; ++w) {
+      if (plan_worker_begin(w, total, workers) == plan_worker_begin(w + 1, total, workers)) continue;
+      mx = fmaxf(mx, part_lse[(size_t)(w + b) * rows + r]);
+    }
+    if (mx > -INFINITY) {
+      for (int w = w_lo; w <= w_hi; ++w) {
+        if (plan_worker_begin(w, total, workers) == plan_worker_begin(w + 1, total, workers)) continue;
+        const size_t prow = (size_t)(w + b) * rows + r;
+        const float ls = part_lse[prow];
+        if (ls == -INFINITY) continue;
+        const float wgt = __expf(ls - mx);
+        tot += wgt;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(part_o + prow * kDv + 4 * threadIdx.x);
+        o += v * wgt;
+      }
+    }
+  }
+  const float inv = tot > 0.f ? 1.f / tot : 0.f;
+  const i32x2 w2 = {(int)pack_bf16(o[0] * inv, o[1] * inv), (int)pack_bf16(o[2] * inv, o[3] * inv)};
+  *reinterpret_cast<i32x2*>(out + grow * kDv + 4 * threadIdx.x) = w2;
+  if (lse != nullptr && threadIdx.x == 0) lse[grow] = tot > 0.f ? mx + __logf(tot) : -INFINITY;
 }
 
 // Register-resident MFMA loop: the measured-peak denominator beside the datasheet peak (the
@@ -479,6 +414,13 @@ bool asm_kernels_enabled() {
   return e != nullptr && std::strcmp(e, "1") == 0;
 }
 
+// The balanced decomposition has new index arithmetic that has not run on hardware yet; until it
+// has, a process must opt in.
+bool balanced_enabled() {
+  const char* e = std::getenv("AMLA_ENABLE_BALANCED");
+  return e != nullptr && std::strcmp(e, "1") == 0;
+}
+
 bool desc_supported(const amla_desc* d) {
   if (d == nullptr) return false;
   if (d->d_qk != kDqk || d->d_v != kDv || d->block_size != kBlock) return false;
@@ -487,8 +429,11 @@ bool desc_supported(const amla_desc* d) {
     return false;
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
-  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL)) != 0) return false;
+  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED)) != 0)
+    return false;
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
+  if ((d->flags & AMLA_FLAG_BALANCED) && ((d->flags & AMLA_FLAG_ASM_KERNEL) || !balanced_enabled())) return false;
+  if ((long long)d->batch * d->max_blocks_per_seq > (1ll << 31) - 1) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
   return true;
@@ -498,6 +443,13 @@ int choose_splits(const amla_desc* d) {
   if (d->num_splits > 0) return d->num_splits;
   const long long rows = (long long)d->s_q * d->num_heads;
   const long long tiles = (rows + kRowsPerWg - 1) / kRowsPerWg;
+  if (d->flags & AMLA_FLAG_BALANCED) {
+    // workers: one workgroup per CU over all row tiles, never more workers than blocks can exist
+    long long w = 256 / tiles > 0 ? 256 / tiles : 1;
+    const long long most = (long long)d->batch * d->max_blocks_per_seq;
+    if (w > most) w = most;
+    return (int)w;
+  }
   const long long base = (long long)d->batch * tiles;       // workgroups without splitting
   const long long cus = 256;
   if (base >= cus) return 1;
@@ -520,6 +472,11 @@ int amla_effective_splits(const amla_desc* desc) {
 size_t amla_workspace_bytes(const amla_desc* desc) {
   if (!desc_supported(desc)) return 0;
   const int ns = choose_splits(desc);
+  if (desc->flags & AMLA_FLAG_BALANCED) {
+    // one slot of s_q * num_heads partial rows per (worker, sequence) piece: slot ids < workers + batch - 1
+    const size_t slots = (size_t)ns + desc->batch - 1;
+    return slots * desc->s_q * desc->num_heads * (kDv + 1) * sizeof(float);
+  }
   if (ns <= 1) return 0;
   const size_t rows = (size_t)desc->batch * desc->s_q * desc->num_heads;
   return (size_t)ns * rows * (kDv + 1) * sizeof(float);
@@ -537,7 +494,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
 
   const int ns = choose_splits(desc);
   const size_t need = amla_workspace_bytes(desc);
-  if (ns > 1) {
+  const bool balanced = (desc->flags & AMLA_FLAG_BALANCED) != 0;
+  if (ns > 1 || balanced) {
     if (desc->workspace == nullptr || desc->workspace_bytes < need) return AMLA_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(desc->workspace) & 15) return AMLA_ERR_WORKSPACE;
   }
@@ -554,12 +512,14 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
   p.n_tiles = (p.rows + kRowsPerWg - 1) / kRowsPerWg;
   p.n_splits = ns;
   p.max_blocks = desc->max_blocks_per_seq;
-  p.n_streams = desc->batch * ns;
+  p.n_streams = balanced ? ns : desc->batch * ns;
   p.flags = desc->flags;
+  p.num_blocks = desc->num_blocks;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   const size_t n_rows = (size_t)desc->batch * p.rows;
-  p.part_o = ns > 1 ? static_cast<float*>(desc->workspace) : nullptr;
+  p.part_o = (ns > 1 || balanced) ? static_cast<float*>(desc->workspace) : nullptr;
   p.part_lse = ns > 1 ? p.part_o + (size_t)ns * n_rows * kDv : nullptr;
+  if (balanced) p.part_lse = p.part_o + ((size_t)ns + desc->batch - 1) * p.rows * kDv;
 
   hipStream_t stream = static_cast<hipStream_t>(desc->stream);
   const long long streams_pad = ((long long)p.n_streams + 7) / 8 * 8;
@@ -568,11 +528,19 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     const long long grid = streams_pad * p.n_tiles;
     if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
     const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
-    auto kern = desc->variant == AMLA_RESCALE_ADD_COMP
-                    ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
-                : desc->variant == AMLA_RESCALE_ADD
-                    ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
-                    : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
+    void (*kern)(const DecodeParams) = nullptr;
+    if (!balanced) {
+      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
+             : desc->variant == AMLA_RESCALE_ADD
+                 ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
+                 : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
+    } else {
+      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
+             : desc->variant == AMLA_RESCALE_ADD ? (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD, true>
+                                                         : amla_decode_balanced_kernel<AMLA_RESCALE_ADD, false>)
+                                                 : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
+                                                         : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
+    }
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kLdsBytes) != hipSuccess) {
       (void)hipGetLastError();
@@ -615,7 +583,11 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
       return AMLA_ERR_LAUNCH;
     }
   }
-  if (ns > 1) {
+  if (balanced) {
+    hipLaunchKernelGGL(amla_combine_balanced_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o,
+                       p.part_lse, p.seqlens, p.out, p.lse, p.batch, p.rows, ns, p.max_blocks);
+    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  } else if (ns > 1) {
     hipLaunchKernelGGL(amla_combine_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
                        p.out, p.lse, (int)n_rows, ns);
     if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
@@ -643,6 +615,47 @@ int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stre
   // 4 waves per workgroup, 4 MFMAs of 32 x 32 x 16 multiply-adds per iteration and wave
   *flops = (double)iters * 4.0 * 4.0 * (2.0 * 32 * 32 * 16) * (double)workgroups;
   return AMLA_OK;
+}
+
+int amla_plan_segments(const int32_t* seqlens, int32_t batch, int32_t workers, int32_t* pieces, int32_t capacity,
+                       int32_t* n_pieces, int32_t* seq_workers) {
+  if (seqlens == nullptr || pieces == nullptr || n_pieces == nullptr || seq_workers == nullptr) return AMLA_ERR_NULL_ARG;
+  if (batch < 1 || workers < 1 || capacity < 0) return AMLA_ERR_UNSUPPORTED;
+  long long total = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seqlens[b] < 0) return AMLA_ERR_UNSUPPORTED;
+    total += plan_blocks_of(seqlens[b], kBlock);
+  }
+  if (total > (1ll << 31) - 1) return AMLA_ERR_UNSUPPORTED;
+  int n = 0;
+  for (int w = 0; w < workers; ++w) {
+    const long long g0 = plan_worker_begin(w, total, workers), g1 = plan_worker_begin(w + 1, total, workers);
+    if (g0 >= g1) continue;
+    // the sequence that holds global block g0 (the kernel finds it with a wave-wide scan)
+    long long base = 0;
+    int b0 = 0;
+    while (base + plan_blocks_of(seqlens[b0], kBlock) <= g0) base += plan_blocks_of(seqlens[b0++], kBlock);
+    PlanWalk walk = {b0, (int32_t)(g0 - base), g1 - g0};
+    while (walk.left > 0 && walk.b < batch) {
+      PlanPiece piece;
+      if (!plan_next(&walk, plan_blocks_of(seqlens[walk.b], kBlock), &piece)) continue;
+      if (n < capacity) {
+        int32_t* row = pieces + 6 * (size_t)n;
+        row[0] = w; row[1] = piece.b; row[2] = piece.j0; row[3] = piece.j1; row[4] = w + piece.b; row[5] = piece.full;
+      }
+      ++n;
+    }
+  }
+  *n_pieces = n;
+  // what the combine kernel derives for each sequence: first and last worker that meet it (-1, -1 if empty)
+  long long before = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int nb = plan_blocks_of(seqlens[b], kBlock);
+    seq_workers[2 * b] = nb > 0 ? (int32_t)plan_worker_of_block(before, total, workers) : -1;
+    seq_workers[2 * b + 1] = nb > 0 ? (int32_t)plan_worker_of_block(before + nb - 1, total, workers) : -1;
+    before += nb;
+  }
+  return n <= capacity ? AMLA_OK : AMLA_ERR_WORKSPACE;
 }
 
 const char* amla_status_string(int status) {

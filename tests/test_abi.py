@@ -73,6 +73,20 @@ def test_assembly_kernels_are_gated_off(amla, monkeypatch):
     assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
 
 
+def test_balanced_decomposition_is_gated_off_and_sized(amla, monkeypatch):
+    monkeypatch.delenv("AMLA_ENABLE_BALANCED", raising=False)
+    d = amla.make_desc(32, 2, 128, 5000, 256, flags=amla.AMLA_FLAG_BALANCED)
+    assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
+    assert amla.amla_effective_splits(d) == 0 and amla.amla_workspace_bytes(d) == 0
+    monkeypatch.setenv("AMLA_ENABLE_BALANCED", "1")
+    workers = amla.amla_effective_splits(d)
+    assert workers == 128                                    # 256 workgroups over two row tiles
+    assert amla.amla_workspace_bytes(d) == (workers + 32 - 1) * 256 * 513 * 4
+    assert _call(amla, d) == amla.AMLA_ERR_WORKSPACE         # pieces always need their slots
+    d.flags |= amla.AMLA_FLAG_ASM_KERNEL
+    assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
+
+
 def test_workspace_and_split_queries(amla):
     d = amla.make_desc(128, 2, 128, 8192, 64)
     assert amla.amla_effective_splits(d) == 1 and amla.amla_workspace_bytes(d) == 0

@@ -1,0 +1,72 @@
+"""GPU parity of the balanced decomposition (AMLA_FLAG_BALANCED): the batch's blocks laid end to end
+and cut into equal worker ranges, pieces merged per sequence.  SWITCHED OFF in the library until its
+index arithmetic has run on hardware: these cases are skipped unless the process sets
+AMLA_ENABLE_BALANCED=1 (the run that tests it).  The integer arithmetic itself is covered on the CPU
+by tests/test_plan.py."""
+import os
+
+import numpy as np
+import pytest
+
+from test_gpu_parity import ADD, LAZY, LSE_TOL, MUL, check, env, out_tolerance, run_gpu, to_dev  # noqa: F401
+
+pytestmark = [pytest.mark.gpu,
+              pytest.mark.skipif(os.environ.get("AMLA_ENABLE_BALANCED") != "1",
+                                 reason="balanced decomposition switched off: not yet run on hardware")]
+
+BALANCED = 8
+COMP = 2
+KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((ADD, LAZY), id="add_lazy"),
+         pytest.param((COMP, 0), id="add_comp")]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_tiny_config_balanced(env, kind):
+    torch, orc, amla, wl = env
+    case = wl.make_config(0)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=kind[0], flags=kind[1] | BALANCED)
+    check(out, lse, want, want_lse, f"tiny balanced {kind}")
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("workers", [0, 1, 3, 8, 41])
+def test_ragged_balanced(env, kind, workers):
+    """Lengths 0, 1, 63, 64, 65 and a few hundred to a thousand keys, 160 rows (two row tiles, the second
+    ragged), worker counts below, at and above the number of sequences, and one (41) above the
+    number of blocks."""
+    torch, orc, amla, wl = env
+    case = wl.make_case("edges", 41, batch=7, s_q=2, heads=80, seqlens=[1, 63, 0, 64, 65, 300, 1000], spare_frac=0.25)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=kind[0], flags=kind[1] | BALANCED,
+                       num_splits=workers)
+    check(out, lse, want, want_lse, f"edges balanced workers={workers} {kind}")
+
+
+def test_balanced_matches_equal_share_split_on_a_uniform_batch(env):
+    """On equal lengths with workers = sequences * splits the two decompositions cut at the same
+    blocks and merge in the same order; the outputs then agree to within one bf16 step and the lse to
+    FP32 rounding."""
+    torch, orc, amla, wl = env
+    case = wl.make_case("uniform", 42, batch=4, s_q=1, heads=128, seqlens=[2048] * 4)
+    dev = to_dev(torch, case)
+    a, la = run_gpu(torch, amla, case, dev, variant=ADD, num_splits=4)
+    b, lb = run_gpu(torch, amla, case, dev, variant=ADD, num_splits=16, flags=BALANCED)
+    assert np.all(np.abs(a - b) <= 2.0 ** -8 * np.maximum(np.abs(a), 2.0 ** -6))
+    assert np.abs(la - lb).max() <= 1e-6
+
+
+def test_full_size_ragged_config_balanced(env):
+    torch, orc, amla, wl = env
+    case = wl.make_config(3)
+    dev = to_dev(torch, case)
+    out, lse = run_gpu(torch, amla, case, dev, variant=ADD, flags=BALANCED)
+    worst = [0.0, 0.0]
+    for b in range(case.batch):
+        want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens,
+                                    case.softmax_scale, seq_ids=[b])
+        assert np.all(np.abs(out[b] - want[b]) <= out_tolerance(want[b])), b
+        worst[0] = max(worst[0], float(np.abs(out[b] - want[b]).max()))
+        worst[1] = max(worst[1], float(np.abs(lse[b] - want_lse[b]).max()))
+    print(f"config 3 balanced: max|out err| {worst[0]:.3e} max|lse err| {worst[1]:.3e}", flush=True)
+    assert worst[1] <= LSE_TOL
