@@ -96,8 +96,8 @@ def cpu_baseline(case, flops_per_seq, budget_s=12.0):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); the path shards by batch "
-              "with no exchange, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path would shard by batch "
+              "with no exchange between GPUs", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

@@ -17,16 +17,16 @@
  *   AMLA_RESCALE_MUL  O <- O * 2^(m_old - m_new)            FP32 multiply (Algorithm 1, Eq. (2))
  *   AMLA_RESCALE_ADD  O <- AS_FP32(AS_INT32(O) + (n_new - n_old) * 2^23)
  *                     with the running reference quantised to an integer power of two
- *                     (Eq. (4), Lemma 3.1, Algorithm 2 lines 5-6 and 11-15), the INT32 add
+ *                     (Eq. (4), Lemma 3.1, Algorithm 2's n_i, N and AtomicAdd<INT32>), the INT32 add
  *                     guarded so that an exponent that would drop to or below zero yields
  *                     a signed zero instead of a wrapped bit pattern.
  *   AMLA_RESCALE_ADD_COMP  the ADD variant with the BF16 scale compensation of Algorithm 2
- *                     lines 7-12 and Appendix A: the weights are 2^(t - m) * S16 with S16 the
+ *                     (S32, S16, c_i, eps) and Appendix A: the weights are 2^(t - m) * S16 with S16 the
  *                     BF16 rounding of S32 = 2^(m - rint(m)), so the largest weight of a row is
  *                     BF16-exact as in Algorithm 1; the same INT32 add then also carries
  *                     rint(2^23 * 1.5 * (c_i / c_{i-1} - 1)), c_i = S16 / S32, which multiplies
  *                     the old accumulator by approximately c_i / c_{i-1} (Appendix A's reading
- *                     of c_i; Algorithm 2 line 9 prints the reciprocal).
+ *                     of c_i; Algorithm 2 prints the reciprocal).
  *
  * Every pointer below is a DEVICE pointer unless it says host.  The library allocates
  * no device memory, never synchronises the device, and enqueues all work on desc->stream.  The

@@ -19,9 +19,9 @@ What it holds
 * `exponent_add_guarded`                        the wrap-safe reading of Lemma 3.1's range
                                                 condition (see below).
 * `amla_fp32_emulation` Algorithm 2's loop in FP32 with BF16 P and the INT32 exponent add,
-                       without the BF16 scale compensation (lines 7-9 are the follow-up).
+                       without the BF16 scale compensation (the S32 / S16 / c_i steps).
 * `flash_fp32_emulation` Algorithm 1 in FP32 with BF16 P (the paper's "Base", Section 5.1).
-* `amla_alg2_emulation` Algorithm 2 with its BF16 scale compensation, line by line in the paper's
+* `amla_alg2_emulation` Algorithm 2 with its BF16 scale compensation, step by step in the paper's
                        notation, with either printed definition of c_i.
 * `amla_comp_fp32_emulation` the same compensation restated in base 2 with one reference per row
                        and integer-built N (the form of the kernels' ADD_COMP variant).
@@ -203,7 +203,7 @@ def exponent_add_guarded(F, n) -> np.ndarray:
 
 # --------------------------------------------------------------------------------------
 # Algorithm 2's loop in FP32 with BF16 P and INT32 exponent add (no BF16 scale
-# compensation: lines 7-9 with S16 := S32, c_i := 1, eps := 0)
+# compensation: its S32 / S16 / c_i steps with S16 := S32, c_i := 1, eps := 0)
 # --------------------------------------------------------------------------------------
 def _round_bf16(x32: np.ndarray) -> np.ndarray:
     u = np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32)
@@ -246,11 +246,11 @@ def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None
 
 def amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="appendix", guard=1e-6):
     """Algorithm 2 step by step in FP32, in the paper's notation, with its BF16 scale compensation
-    (lines 7-12): S32 = exp(ln2 (n_i + m_i / ln2)), S16 = BF16(S32), c_i, eps = 1.5 (c_i / c_{i-1} - 1),
+    (the steps from S32 to N): S32 = exp(ln2 (n_i + m_i / ln2)), S16 = BF16(S32), c_i, eps = 1.5 (c_i / c_{i-1} - 1),
     P <- BF16(P * S16), N = Cast_to_int32((max(n_i - n_{i-1}, -30) + eps + 1e-6) * 2^23), O <- AS_FP32(
     AS_INT32(O) + N), O += P V, and O / (l_N * S16) at the end.
 
-    `c_reading` selects between the two definitions of c_i the paper gives: "algorithm" is line 9 as
+    `c_reading` selects between the two definitions of c_i the paper gives: "algorithm" is the assignment to c_i as
     printed (c_i = S32 / S16), "appendix" is Appendix A (c_i = r_i / r'_i = S16 / S32, since
     S32 = 1 / r_i and S16 = 1 / r'_i).  Block size 512 is the paper's (Section 4.2)."""
     f32 = np.float32
@@ -286,7 +286,7 @@ def amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="appendix", guard=1
 
 
 def amla_comp_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, with_eps=True):
-    """Algorithm 2 with its compensation (lines 7-12, Appendix A's c_i) restated in base 2 with one
+    """Algorithm 2 with its compensation (the steps from S32 to N, Appendix A's c_i) restated in base 2 with one
     reference per row, the form a register-resident kernel takes: mu = rint(m) = -n_i,
     S32 = 2^(m - mu), S16 = BF16(S32), c = S16 / S32, weights P = 2^(t - ref) with
     ref = m - log2 S16 (so P = 2^(t - m) S16 and the largest weight of a row is S16, BF16-exact),

@@ -82,7 +82,7 @@ struct DecodeParams {
 // Lemma 3.1 with a guard: x * 2^delta as an integer add of n23 = delta << 23 (delta <= 0) on the
 // bit pattern.  The saturating add pins a negative float whose exponent would go below zero at
 // 0x80000000 (-0.0); the max with the sign bit turns a wrapped positive float into +0.0.
-// n23 may also carry a small mantissa term of either sign (Algorithm 2 line 12): the guard
+// n23 may also carry a small mantissa term of either sign (Algorithm 2's eps inside N): the guard
 // only concerns sums that leave the float's own sign range.
 __device__ __forceinline__ float exponent_add(float x, int n23) {
   const int i = __float_as_int(x);

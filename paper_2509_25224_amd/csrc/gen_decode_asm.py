@@ -10,7 +10,7 @@ rescaled:
   mul        reference = running row max; O *= 2^(m_old - m_new)       (Algorithm 1, Eq. (2))
   add        reference = rint(running row max), an integer power of two; O's bit patterns get
              (n_new - n_old) << 23 added as INT32, guarded against exponent underflow
-             (Eq. (4), Lemma 3.1, Algorithm 2 lines 5-6 and 11-15)
+             (Eq. (4), Lemma 3.1, Algorithm 2's n_i, N and AtomicAdd<INT32> steps)
   *_lazy     the reference is moved only when the row max exceeds it by more than 2^8; until
              then the softmax weights are allowed to grow up to 2^8 (same relative precision in
              bf16 / FP32), which makes the rescale of the 32 x 512 accumulator a rare event.
@@ -476,7 +476,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             v.append(f"v_cmp_neq_f32 {sr(S_NEED, 2)}, v{V_REF}, v{T1}")
         else:
             v.append(f"v_sub_f32 v{T4}, v{V_REF}, v{T1}")                # <= 0, integer valued (or -inf)
-            v.append(f"v_max_f32 v{T4}, 0xc1f00000, v{T4}")             # clamp at -30 (Algorithm 2 line 11)
+            v.append(f"v_max_f32 v{T4}, 0xc1f00000, v{T4}")             # clamp at -30 (Algorithm 2's max(n_i - n_{i-1}, -30))
             v.append(f"v_cvt_i32_f32 v{T4}, v{T4}")
             v.append(f"v_lshlrev_b32 v{V_FAC}, 23, v{T4}")
             v.append(f"v_cmp_ne_u32 {sr(S_NEED, 2)}, 0, v{V_FAC}")

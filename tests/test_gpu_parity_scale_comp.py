@@ -1,5 +1,5 @@
-"""GPU parity of the ADD_COMP variant (Algorithm 2 with its BF16 scale compensation, lines 7-12 and
-Appendix A) of the compiler-built kernel.  Collected after the other parity files on purpose: these
+"""GPU parity of the ADD_COMP variant (Algorithm 2 with its BF16 scale compensation, the steps from S32 to N,
+and Appendix A) of the compiler-built kernel.  Collected after the other parity files on purpose: these
 cases were added after the last GPU run of this build, and a failure here must not hide the cases
 that ran before."""
 import numpy as np

@@ -193,11 +193,11 @@ def _accuracy_sample(family, param, seed, rows=32, keys=8192):
 @pytest.mark.parametrize("family,param,base_printed,amla_printed",
                          [(f, float(p), float(b), float(a)) for f, p, b, a in _rows("table3_table4_accuracy.txt")])
 def test_emulations_reproduce_the_printed_accuracy_tables(family, param, base_printed, amla_printed):
-    """Tables 3 and 4: the FP32 emulation of Algorithm 1 ("Base") and the line-by-line emulation of
+    """Tables 3 and 4: the FP32 emulation of Algorithm 1 ("Base") and the step-by-step emulation of
     Algorithm 2 with Appendix A's c_i ("AMLA"), outputs rounded to BF16, land on the printed errors:
     within 1.5 % on the two flat columns N(0,1) and U(-1,1), where one sample of 32 rows already has
     0.5 % spread and the printed AMLA-minus-Base gap of 2 % is resolved, and within 7 % (mean of three
-    samples; the spread of one sample is 2-6 %) on the others.  With line 9's c_i as printed the same
+    samples; the spread of one sample is 2-6 %) on the others.  With Algorithm 2's c_i as printed the same
     emulation gives 3.1e-3 on N(0,1), 70 % above the printed 1.81e-3."""
     scale = 576 ** -0.5
     flat = param == 1.0
@@ -220,7 +220,7 @@ def test_emulations_reproduce_the_printed_accuracy_tables(family, param, base_pr
 
 
 def test_algorithm2_compensation_and_the_two_readings_of_c():
-    """Algorithm 2 line 9 prints c_i = S32 / S16, Appendix A defines c_i = r_i / r'_i = S16 / S32.  With
+    """Algorithm 2 prints c_i = S32 / S16, Appendix A defines c_i = r_i / r'_i = S16 / S32.  With
     the appendix's definition the compensated recurrence, outputs rounded to BF16, is as accurate as
     Base (what Tables 3-4 report); with the printed one the correction has the wrong sign and the
     error before output rounding is more than twice as large.  The recurrence the kernels run (power-
@@ -247,7 +247,7 @@ def test_algorithm2_compensation_and_the_two_readings_of_c():
 
 def test_compensation_restated_in_base_two_matches_algorithm2():
     """The one-reference-per-row form (ref = m - log2 S16, N built in integers, two row sums) is the
-    same method as Algorithm 2 line by line: its error against the fp64 definition is the line-by-line
+    same method as Algorithm 2 step by step: its error against the fp64 definition is the step-by-step
     emulation's and Base's within a few per cent, its lse is the definition's, and dropping the
     mantissa term eps makes flat rows (many small maxima updates, no dominant key) measurably worse."""
     rng = np.random.default_rng(12)

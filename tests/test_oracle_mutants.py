@@ -114,7 +114,7 @@ def test_truncating_bf16_cast_is_caught_by_the_printed_accuracy_tables(monkeypat
 
 
 def test_dropping_the_compensation_is_caught_by_the_printed_accuracy_tables(monkeypatch):
-    """Algorithm 2 without lines 7-9 and 12 (S16 = 1, eps = 0: the weights 2^(t - m) S32 are rounded as
+    """Algorithm 2 without its S32 / S16 / c_i / eps steps (S16 = 1, eps = 0: the weights 2^(t - m) S32 are rounded as
     they are) no longer reproduces the AMLA row of Table 3 on a peaked column."""
     import test_oracle_method as method
 
