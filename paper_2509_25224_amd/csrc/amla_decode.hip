@@ -34,322 +34,7 @@
 
 namespace {
 
-constexpr int kDqk = 576;
-constexpr int kDv = 512;
-constexpr int kBlock = 64;               // keys per cache block
-constexpr int kRowBytes = kDqk * 2;      // 1152 bytes of bf16 per cached row
-constexpr int kLdsRow = kRowBytes + 16;  // padded LDS row: 73 chunks of 16 B (odd -> no bank conflicts)
-constexpr int kChunksPerRow = kLdsRow / 16;           // 73
-constexpr int kTileBytes = kBlock * kLdsRow;          // 74752 = 73 * 1024
-constexpr int kTileLoads = kTileBytes / 1024;         // 73 wave-wide 1 KiB direct-to-LDS loads
-constexpr int kRowsPerWg = 128;
-constexpr int kThreads = 256;
-constexpr int kLdsBytes = 2 * kTileBytes;             // double buffer, 149504 B of the 160 KiB
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
-typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
-
-#define LDS_PTR(T) __attribute__((address_space(3))) T*
-#define GLB_PTR(T) __attribute__((address_space(1))) T*
-
-struct DecodeParams {
-  const uint16_t* q;        // [B, G, 576] bf16 bits (G = s_q * H rows per sequence)
-  const uint16_t* kv;       // [num_blocks, 64, 576]
-  const int32_t* table;     // [B, max_blocks]
-  const int32_t* seqlens;   // [B]
-  uint16_t* out;            // [B, G, 512] bf16 bits
-  float* lse;               // [B, G] or null
-  float* part_o;            // [n_splits, B, G, 512] f32 (n_splits > 1)
-  float* part_lse;          // [n_splits, B, G]
-  float scale_log2e;        // softmax_scale * log2(e)
-  int32_t batch;
-  int32_t rows;             // G
-  int32_t n_tiles;          // ceil(G / 128)
-  int32_t n_splits;
-  int32_t max_blocks;
-  int32_t n_streams;        // batch * n_splits; balanced decomposition: number of workers
-  int32_t flags;
-  int32_t num_blocks;       // physical blocks in the pool (the balanced kernel clamps table entries)
-};
-
-// Lemma 3.1 with a guard: x * 2^delta as an integer add of n23 = delta << 23 (delta <= 0) on the
-// bit pattern.  The saturating add pins a negative float whose exponent would go below zero at
-// 0x80000000 (-0.0); the max with the sign bit turns a wrapped positive float into +0.0.
-// n23 may also carry a small mantissa term of either sign (Algorithm 2's eps inside N): the guard
-// only concerns sums that leave the float's own sign range.
-__device__ __forceinline__ float exponent_add(float x, int n23) {
-  const int i = __float_as_int(x);
-  int r = __builtin_elementwise_add_sat(i, n23);
-  r = max(r, i & (int)0x80000000);
-  return __int_as_float(r);
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
-
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  f32x2 v = {lo, hi};
-  bf16x2 b = __builtin_convertvector(v, bf16x2);   // round to nearest even
-  return __builtin_bit_cast(unsigned, b);
-}
-
-// Issue this wave's share of the direct-to-LDS loads of one 64 x 576 bf16 block.
-// LDS destination of load i is the 1 KiB range [i * 1024, (i + 1) * 1024) of the tile buffer,
-// lane l landing at + 16 l; chunk c = 64 i + l of the padded tile is row c / 73, column chunk
-// c % 73, the 73rd chunk of a row being padding (it receives 16 harmless bytes).
-__device__ __forceinline__ void issue_tile_loads(const uint8_t* block_base, LDS_PTR(uint8_t) buf,
-                                                 int wave, int lane) {
-  // keep the per-lane offsets out of loop-invariant hoisting: 19 of them per lane would
-  // cost more registers than recomputing them costs VALU slots
-  asm volatile("" : "+v"(lane));
-#pragma unroll
-  for (int k = 0; k < (kTileLoads + 3) / 4; ++k) {
-    const int i = wave + 4 * k;
-    if (i < kTileLoads) {
-      const int c = i * 64 + lane;
-      const int row = (int)(((unsigned)c * 57457u) >> 22);      // c / 73 for c < 4672
-      const int cc = c - row * kChunksPerRow;
-      const int off = (cc < kChunksPerRow - 1) ? (c - row) * 16 : 0;
-      __builtin_amdgcn_global_load_lds((const GLB_PTR(void))(block_base + off),
-                                       (LDS_PTR(void))(buf + i * 1024), 16, 0, 0);
-    }
-  }
-}
-
-constexpr float kLazyThreshold = 8.f;   // base-2 units: the weights may grow to 2^8 before the reference moves
-
-template <int VARIANT, bool LAZY>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void amla_decode_kernel(const DecodeParams p) {
-  extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
-  LDS_PTR(uint8_t) smem = (LDS_PTR(uint8_t))smem_raw;
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int l32 = lane & 31;
-  const int h = lane >> 5;
-
-  // Workgroup -> (kv stream, row tile).  Consecutive workgroup ids go round-robin over the 8
-  // XCDs; the row tiles of one (sequence, split) get ids that differ by 8 so that they land on
-  // the same XCD next to each other and share the KV blocks in that XCD's L2.
-  const int xcd = blockIdx.x & 7;
-  const int slot = blockIdx.x >> 3;
-  const int stream = (slot / p.n_tiles) * 8 + xcd;
-  const int tile = slot % p.n_tiles;
-  if (stream >= p.n_streams) return;
-  const int b = stream / p.n_splits;
-  const int split = stream - b * p.n_splits;
-
-  const int kv_len = p.seqlens[b];
-  const int nb = (kv_len + kBlock - 1) / kBlock;
-  const int j0 = (int)(((long long)split * nb) / p.n_splits);
-  const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
-
-  const int row = tile * kRowsPerWg + wave * 32 + l32;       // row within the sequence
-  const bool row_ok = row < p.rows;
-  const size_t grow = (size_t)b * p.rows + (row_ok ? row : 0);
-
-#define AMLA_PIECE_BALANCED 0
-#define AMLA_PIECE_PHYS(j) __builtin_amdgcn_readfirstlane(tab[j])
-#include "amla_decode_piece.inc"
-#undef AMLA_PIECE_PHYS
-#undef AMLA_PIECE_BALANCED
-}
-
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int u = __shfl_up(v, o);
-    if (lane >= o) v += u;
-  }
-  return v;
-}
-
-// The same loop under the balanced decomposition: workgroup = (worker, row tile); the worker's share
-// of the batch's concatenated block list is walked piece by piece (amla_plan.h).  p.n_streams is the
-// number of workers.
-template <int VARIANT, bool LAZY>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void amla_decode_balanced_kernel(const DecodeParams p) {
-  extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
-  LDS_PTR(uint8_t) smem = (LDS_PTR(uint8_t))smem_raw;
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int l32 = lane & 31;
-  const int h = lane >> 5;
-
-  // workers go round-robin over the 8 XCDs; the row tiles of one worker sit next to each other on
-  // the same XCD and share the worker's KV blocks in that XCD's L2
-  const int xcd = blockIdx.x & 7;
-  const int slot = blockIdx.x >> 3;
-  const int stream = (slot / p.n_tiles) * 8 + xcd;
-  const int tile = slot % p.n_tiles;
-  if (stream >= p.n_streams) return;
-
-  const int row = tile * kRowsPerWg + wave * 32 + l32;       // row within the sequence
-  const bool row_ok = row < p.rows;
-
-  // total number of blocks of the batch, then this worker's range of the concatenated list
-  int total = 0;
-  for (int c = 0; c < p.batch; c += 64) {
-    const int i = c + lane;
-    total += wave_sum(i < p.batch ? plan_blocks_of(plan_len(p.seqlens[i], p.max_blocks, kBlock), kBlock) : 0);
-  }
-  total = __builtin_amdgcn_readfirstlane(total);
-  const long long g0 = plan_worker_begin(stream, total, p.n_streams);
-  const long long g1 = plan_worker_begin(stream + 1, total, p.n_streams);
-  if (g0 >= g1) return;
-  // the sequence that holds global block g0, and g0's position in it
-  int b0 = -1, jstart = 0, base = 0;
-  for (int c = 0; c < p.batch && b0 < 0; c += 64) {
-    const int i = c + lane;
-    const int nbi = i < p.batch ? plan_blocks_of(plan_len(p.seqlens[i], p.max_blocks, kBlock), kBlock) : 0;
-    const int incl = wave_inclusive_scan(nbi, lane);
-    const int excl = incl - nbi;
-    const bool hit = (long long)base + excl <= g0 && g0 < (long long)base + incl;
-    const unsigned long long mask = __builtin_amdgcn_ballot_w64(hit);
-    if (mask != 0) {
-      const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(mask));
-      b0 = c + l;
-      jstart = (int)(g0 - ((long long)base + __builtin_amdgcn_readlane(excl, l)));
-    }
-    base += __builtin_amdgcn_readlane(incl, 63);
-  }
-  if (b0 < 0) return;   // unreachable when g0 < total
-  PlanWalk walk = {b0, jstart, g1 - g0};
-  while (walk.left > 0 && walk.b < p.batch) {
-    const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[walk.b]), p.max_blocks, kBlock);
-    PlanPiece piece;
-    if (!plan_next(&walk, plan_blocks_of(kv_len, kBlock), &piece)) continue;
-    [&](const int b, const int j0, const int j1, const bool to_final) __attribute__((always_inline)) {
-    const size_t slot_row = ((size_t)stream + b) * p.rows;   // slot worker + sequence < n_streams + batch - 1
-    const size_t grow = (size_t)b * p.rows + (row_ok ? row : 0);
-#define AMLA_PIECE_BALANCED 1
-#define AMLA_PIECE_PHYS(j) min(max(__builtin_amdgcn_readfirstlane(tab[j]), 0), p.num_blocks - 1)
-#include "amla_decode_piece.inc"
-#undef AMLA_PIECE_PHYS
-#undef AMLA_PIECE_BALANCED
-    }(piece.b, piece.j0, piece.j1, piece.full != 0);
-  }
-}
-
-// Merge the per-split partial results of one row: weights exp(lse_s - lse) (the merge rule of
-// Algorithm 1's update applied across splits).  One 128-thread workgroup per row, 4 columns
-// per thread.
-__global__ __launch_bounds__(128) void amla_combine_kernel(const float* __restrict__ part_o,
-                                                          const float* __restrict__ part_lse,
-                                                          uint16_t* __restrict__ out, float* __restrict__ lse,
-                                                          int n_rows, int n_splits) {
-  const int row = blockIdx.x;
-  if (row >= n_rows) return;
-  float mx = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_lse[(size_t)s * n_rows + row]);
-  f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  float tot = 0.f;
-  if (mx > -INFINITY) {
-    for (int s = 0; s < n_splits; ++s) {
-      const float ls = part_lse[(size_t)s * n_rows + row];
-      if (ls == -INFINITY) continue;
-      const float w = __expf(ls - mx);
-      tot += w;
-      const f32x4 v = *reinterpret_cast<const f32x4*>(part_o + ((size_t)s * n_rows + row) * kDv + 4 * threadIdx.x);
-      o += v * w;
-    }
-  }
-  const float inv = tot > 0.f ? 1.f / tot : 0.f;
-  const i32x2 w = {(int)pack_bf16(o[0] * inv, o[1] * inv), (int)pack_bf16(o[2] * inv, o[3] * inv)};
-  *reinterpret_cast<i32x2*>(out + (size_t)row * kDv + 4 * threadIdx.x) = w;
-  if (lse != nullptr && threadIdx.x == 0) lse[row] = tot > 0.f ? mx + __logf(tot) : -INFINITY;
-}
-
-// The same merge for the balanced decomposition: the pieces of sequence b are those of the workers
-// whose ranges meet the sequence's span of the concatenated block list; piece (w, b) sits in slot
-// w + b.  A sequence with a single piece was written in final form by the decode kernel; a
-// sequence without blocks gets its zeros here.  One 128-thread workgroup per row.
-__global__ __launch_bounds__(128) void amla_combine_balanced_kernel(const float* __restrict__ part_o,
-                                                                   const float* __restrict__ part_lse,
-                                                                   const int32_t* __restrict__ seqlens,
-                                                                   uint16_t* __restrict__ out, float* __restrict__ lse,
-                                                                   int batch, int rows, int workers, int max_blocks) {
-  const int b = blockIdx.x / rows;
-  const int r = blockIdx.x - b * rows;
-  if (b >= batch) return;
-  const int lane = threadIdx.x & 63;
-  int total = 0, before = 0;
-  for (int c = 0; c < batch; c += 64) {
-    const int i = c + lane;
-    const int nbi = i < batch ? plan_blocks_of(plan_len(seqlens[i], max_blocks, kBlock), kBlock) : 0;
-    total += wave_sum(nbi);
-    before += wave_sum(i < b ? nbi : 0);
-  }
-  const int nb = plan_blocks_of(plan_len(seqlens[b], max_blocks, kBlock), kBlock);
-  const size_t grow = (size_t)b * rows + r;
-  f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  float tot = 0.f, mx = -INFINITY;
-  if (nb > 0) {
-    const int w_lo = (int)plan_worker_of_block(before, total, workers);
-    const int w_hi = (int)plan_worker_of_block((long long)before + nb - 1, total, workers);
-    if (w_lo == w_hi) return;   // a full piece: the decode kernel wrote out and lse itself
-    for (int w = w_lo; w <= w_hi; ++w) {
-      if (plan_worker_begin(w, total, workers) == plan_worker_begin(w + 1, total, workers)) continue;
-      mx = fmaxf(mx, part_lse[(size_t)(w + b) * rows + r]);
-    }
-    if (mx > -INFINITY) {
-      for (int w = w_lo; w <= w_hi; ++w) {
-        if (plan_worker_begin(w, total, workers) == plan_worker_begin(w + 1, total, workers)) continue;
-        const size_t prow = (size_t)(w + b) * rows + r;
-        const float ls = part_lse[prow];
-        if (ls == -INFINITY) continue;
-        const float wgt = __expf(ls - mx);
-        tot += wgt;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(part_o + prow * kDv + 4 * threadIdx.x);
-        o += v * wgt;
-      }
-    }
-  }
-  const float inv = tot > 0.f ? 1.f / tot : 0.f;
-  const i32x2 w2 = {(int)pack_bf16(o[0] * inv, o[1] * inv), (int)pack_bf16(o[2] * inv, o[3] * inv)};
-  *reinterpret_cast<i32x2*>(out + grow * kDv + 4 * threadIdx.x) = w2;
-  if (lse != nullptr && threadIdx.x == 0) lse[grow] = tot > 0.f ? mx + __logf(tot) : -INFINITY;
-}
-
-// Register-resident MFMA loop: the measured-peak denominator beside the datasheet peak (the
-// paper's footnote makes the same distinction between a theoretical and a throttled peak).
-__global__ __launch_bounds__(256) void amla_mfma_probe_kernel(float* out, int iters) {
-  bf16x8 a, b;
-  for (int e = 0; e < 8; ++e) {
-    a[e] = (__bf16)(float)(threadIdx.x % 3);
-    b[e] = (__bf16)(float)(threadIdx.x % 5);
-  }
-  f32x16 c[4];
-  for (int n = 0; n < 4; ++n) c[n] = f32x16{0};
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int n = 0; n < 4; ++n) c[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[n], 0, 0, 0);
-  }
-  float s = 0.f;
-  for (int n = 0; n < 4; ++n) s += c[n][0];
-  if (s == 12345.678f && out != nullptr) out[0] = s;   // keeps the loop alive; never true for these operands
-}
-
-__global__ void amla_exponent_add_kernel(const float* x, float* y, size_t n, int n23) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) y[i] = exponent_add(x[i], n23);
-}
+#include "amla_decode_kernels.inc"
 
 // ---- hand-scheduled kernels: code object assembled from the generated gfx950 assembly --------
 const unsigned char kDecodeCodeObject[] = {

@@ -1,0 +1,263 @@
+// CPU stand-in for <hip/hip_runtime.h> (tests only): the HIP / gfx950 constructs the decode library uses,
+// so that its source -- kernels and host code alike -- compiles for the host unmodified and runs under
+// AddressSanitizer.  One OS thread per work-item;
+// the 64 threads of a wave meet at a barrier for every wave-wide operation (shuffle, ballot, readlane,
+// MFMA, transposing LDS read), the threads of a workgroup at __syncthreads().
+//
+// Semantics of the two matrix-pipeline operations are the ones measured on the hardware:
+//   v_mfma_f32_32x32x16_bf16: A lane l holds row l%32, k = 8*(l/32)+0..7; B lane l holds column l%32,
+//       same k; C/D register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+//   ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives, for j = 0..3, element i%4 of
+//       the 4 x b16 that lane (i/4 + 4j) of the group addressed.
+// Direct-to-LDS loads are made deliberately strict: at issue the destination is filled with a NaN
+// pattern, the data lands when the issuing wave waits for its loads.  A kernel that reads a tile
+// before waiting, or refills a buffer another wave may still read, then produces NaNs.
+#ifndef AMLA_TESTS_HIP_RUNTIME_SHIM_H_
+#define AMLA_TESTS_HIP_RUNTIME_SHIM_H_
+
+#include <algorithm>
+#include <atomic>
+#include <sched.h>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <thread>
+#include <vector>
+
+struct dim3 {
+  unsigned x, y, z;
+  dim3(unsigned x_ = 1, unsigned y_ = 1, unsigned z_ = 1) : x(x_), y(y_), z(z_) {}
+};
+inline thread_local dim3 threadIdx, blockIdx, blockDim;
+
+#define __global__
+#define __device__
+#define __host__
+#define __forceinline__ inline __attribute__((always_inline))
+#define __launch_bounds__(...)
+#define __shared__
+using std::max;
+using std::min;
+
+namespace shim {
+
+// A yielding barrier: there are far more threads than cores, so a waiter gives up its time slice
+// instead of spinning or sleeping on a futex (waking 63 sleepers per wave-wide operation is what
+// costs the time otherwise).
+class Barrier {
+ public:
+  explicit Barrier(unsigned n) : n_(n) {}
+  void arrive_and_wait() {
+    const unsigned gen = gen_.load(std::memory_order_acquire);
+    if (count_.fetch_add(1, std::memory_order_acq_rel) + 1 == n_) {
+      count_.store(0, std::memory_order_relaxed);
+      gen_.store(gen + 1, std::memory_order_release);
+    } else {
+      while (gen_.load(std::memory_order_acquire) == gen) sched_yield();
+    }
+  }
+
+ private:
+  const unsigned n_;
+  std::atomic<unsigned> count_{0}, gen_{0};
+};
+
+struct WaveCtx {
+  Barrier bar{64};
+  alignas(64) unsigned char slot[2][64][64];
+};
+struct PendingLoad {
+  const void* src;
+  void* dst;
+};
+inline thread_local WaveCtx* wave = nullptr;
+inline thread_local Barrier* wg_bar = nullptr;
+inline thread_local int lane = 0;
+inline thread_local unsigned turn = 0;
+inline thread_local std::vector<PendingLoad>* pending = nullptr;
+
+// every lane contributes `mine`; returns a pointer to the 64 contributions (valid until the wave's
+// next collective but one)
+template <class T>
+inline const unsigned char (*exchange(const T& mine))[64] {
+  static_assert(sizeof(T) <= 64, "payload");
+  const unsigned t = turn++ & 1u;
+  std::memcpy(wave->slot[t][lane], &mine, sizeof(T));
+  wave->bar.arrive_and_wait();
+  return wave->slot[t];
+}
+template <class T>
+inline T peer(const unsigned char (*all)[64], int l) {
+  T v;
+  std::memcpy(&v, all[l], sizeof(T));
+  return v;
+}
+
+template <class T>
+inline T shfl_xor(T v, int m) {
+  return peer<T>(exchange(v), lane ^ m);
+}
+template <class T>
+inline T shfl_up(T v, int d) {
+  auto all = exchange(v);
+  return lane >= d ? peer<T>(all, lane - d) : v;
+}
+template <class T>
+inline T readfirstlane(T v) {
+  return peer<T>(exchange(v), 0);
+}
+inline int readlane(int v, int l) { return peer<int>(exchange(v), l & 63); }
+inline unsigned long long ballot(bool p) {
+  auto all = exchange((int)p);
+  unsigned long long m = 0;
+  for (int l = 0; l < 64; ++l) m |= (unsigned long long)(peer<int>(all, l) != 0) << l;
+  return m;
+}
+
+template <class AB, class C>
+inline C mfma_32x32x16_bf16(AB a, AB b, C c, int, int, int) {
+  struct Frag {
+    AB a, b;
+  } mine = {a, b};
+  auto all = exchange(mine);
+  const int col = lane & 31, half = lane >> 5;
+  Frag colf[2];   // the two lanes that hold column `col` of B (k 0..7 and 8..15)
+  colf[0] = peer<Frag>(all, col);
+  colf[1] = peer<Frag>(all, col + 32);
+  for (int r = 0; r < 16; ++r) {
+    const int row = 8 * (r / 4) + 4 * half + r % 4;
+    const Frag r0 = peer<Frag>(all, row), r1 = peer<Frag>(all, row + 32);
+    double acc = 0.0;
+    for (int e = 0; e < 8; ++e) {
+      acc += (double)(float)r0.a[e] * (double)(float)colf[0].b[e];
+      acc += (double)(float)r1.a[e] * (double)(float)colf[1].b[e];
+    }
+    c[r] = (float)((double)c[r] + acc);
+  }
+  return c;
+}
+
+template <class V4>
+inline V4 ds_read_tr16_b64(V4* p) {
+  V4 mine;
+  std::memcpy(&mine, p, sizeof(V4));
+  auto all = exchange(mine);
+  const int g = lane / 16, i = lane % 16;
+  V4 out;
+  for (int j = 0; j < 4; ++j) out[j] = peer<V4>(all, g * 16 + i / 4 + 4 * j)[i % 4];
+  return out;
+}
+
+inline void global_load_lds(const void* g, void* lds_base, int bytes, int, int) {
+  if (bytes != 16) std::abort();
+  unsigned char* dst = static_cast<unsigned char*>(lds_base) + 16 * lane;
+  volatile unsigned char probe = *static_cast<const unsigned char*>(g);          // the read is checked at issue
+  probe = static_cast<const unsigned char*>(g)[15];
+  (void)probe;
+  for (int i = 0; i < 8; ++i) reinterpret_cast<uint16_t*>(dst)[i] = 0x7FC0;      // bf16 NaN until it lands
+  pending->push_back({g, dst});
+}
+inline void wait_tile_loads() {
+  for (const PendingLoad& l : *pending) std::memcpy(l.dst, l.src, 16);
+  pending->clear();
+}
+inline void syncthreads() { wg_bar->arrive_and_wait(); }
+
+// Runs kernel(args) for every workgroup of a 1-D or 2-D grid with `threads` work-items each (a
+// multiple of 64).  Workgroups run one after another; the work-items of one run concurrently.
+template <class F>
+void launch(unsigned grid_x, unsigned grid_y, unsigned threads, F kernel) {
+  const unsigned n_waves = threads / 64;
+  std::vector<std::unique_ptr<WaveCtx>> waves;
+  for (unsigned w = 0; w < n_waves; ++w) waves.emplace_back(new WaveCtx);
+  Barrier wg(threads);
+  std::vector<std::thread> pool;
+  for (unsigned t = 0; t < threads; ++t) {
+    pool.emplace_back([&, t] {
+      std::vector<PendingLoad> my_pending;
+      pending = &my_pending;
+      wave = waves[t / 64].get();
+      wg_bar = &wg;
+      lane = (int)(t % 64);
+      turn = 0;
+      threadIdx.x = t;
+      blockDim.x = threads;
+      for (unsigned y = 0; y < grid_y; ++y)
+        for (unsigned x = 0; x < grid_x; ++x) {
+          blockIdx.x = x;
+          blockIdx.y = y;
+          kernel();
+          if (!my_pending.empty()) {
+            std::fprintf(stderr, "shim: a wave left the kernel with direct-to-LDS loads in flight\n");
+            std::abort();
+          }
+          wg.arrive_and_wait();   // the next workgroup reuses the LDS buffer
+        }
+    });
+  }
+  for (auto& th : pool) th.join();
+}
+
+}  // namespace shim
+
+// ---- the slice of the HIP runtime API the library's host code uses ---------------------------------
+typedef int hipError_t;
+typedef void* hipStream_t;
+typedef void* hipModule_t;
+typedef void* hipFunction_t;
+enum { hipSuccess = 0, hipErrorNotSupported = 801 };
+enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
+#define HIP_LAUNCH_PARAM_BUFFER_POINTER ((void*)1)
+#define HIP_LAUNCH_PARAM_BUFFER_SIZE ((void*)2)
+#define HIP_LAUNCH_PARAM_END ((void*)3)
+inline hipError_t hipGetLastError() { return hipSuccess; }
+inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
+inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
+// no code objects on the CPU: the hand-scheduled kernels are unavailable in this build
+inline hipError_t hipModuleLoadData(hipModule_t*, const void*) { return hipErrorNotSupported; }
+inline hipError_t hipModuleGetFunction(hipFunction_t*, hipModule_t, const char*) { return hipErrorNotSupported; }
+inline hipError_t hipModuleLaunchKernel(hipFunction_t, unsigned, unsigned, unsigned, unsigned, unsigned, unsigned,
+                                        unsigned, hipStream_t, void**, void**) { return hipErrorNotSupported; }
+#define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                              \
+  do {                                                                                             \
+    const dim3 shim_grid = (grid), shim_block = (block);                                           \
+    (void)(lds_bytes);                                                                             \
+    (void)(stream);                                                                                \
+    shim::launch(shim_grid.x, shim_grid.y, shim_block.x, [&] { kern(__VA_ARGS__); });              \
+  } while (0)
+
+#define __syncthreads() shim::syncthreads()
+#define __shfl_xor(v, m) shim::shfl_xor((v), (m))
+#define __shfl_up(v, d) shim::shfl_up((v), (d))
+#define __builtin_amdgcn_readfirstlane(v) shim::readfirstlane((v))
+#define __builtin_amdgcn_readlane(v, l) shim::readlane((v), (l))
+#define __builtin_amdgcn_ballot_w64(p) shim::ballot((p))
+#define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) shim::mfma_32x32x16_bf16((a), (b), (c), (x), (y), (z))
+#define __builtin_amdgcn_ds_read_tr16_b64_v4i16(p) shim::ds_read_tr16_b64((p))
+#define __builtin_amdgcn_global_load_lds(g, l, n, o, a) shim::global_load_lds((g), (l), (n), (o), (a))
+#define __builtin_amdgcn_sched_barrier(x) ((void)0)
+#define __builtin_amdgcn_exp2f(x) exp2f((x))
+#define __builtin_amdgcn_logf(x) log2f((x))
+#define __expf(x) expf((x))
+#define __logf(x) logf((x))
+
+inline int __float_as_int(float f) { return __builtin_bit_cast(int, f); }
+inline float __int_as_float(int i) { return __builtin_bit_cast(float, i); }
+inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); }
+
+// target hooks of amla_decode_kernels.inc
+#define AMLA_TARGET_HOOKS 1
+#define LDS_PTR(T) T*
+#define GLB_PTR(T) T*
+#ifdef SHIM_PLANT_NO_WAIT
+#define AMLA_WAIT_TILE_LOADS() ((void)0)   // planted mistake for the harness's own test: tiles are read before they land
+#else
+#define AMLA_WAIT_TILE_LOADS() shim::wait_tile_loads()
+#endif
+#define AMLA_OPAQUE(x) ((void)(x))
+#define AMLA_ONE_WAVE_PER_SIMD
+
+#endif  // AMLA_TESTS_HIP_RUNTIME_SHIM_H_
