@@ -74,7 +74,7 @@ enum {
 
 /* desc->flags, continued */
 enum {
-  AMLA_FLAG_BALANCED = 8        /* decomposition for ragged batches (compiler-built kernel only): the 64-key
+  AMLA_FLAG_BALANCED = 8,       /* decomposition for ragged batches (compiler-built kernel only): the 64-key
                                    blocks of all sequences are laid end to end and cut into equal
                                    ranges, one per worker workgroup; a worker walks its range sequence
                                    by sequence, and the pieces of a sequence are merged like split-KV
@@ -84,6 +84,13 @@ enum {
                                    rejected with AMLA_ERR_UNSUPPORTED unless the environment variable
                                    AMLA_ENABLE_BALANCED is "1", because this index arithmetic has not
                                    yet run on hardware. */
+  AMLA_FLAG_CAUSAL = 16         /* causal mask among the s_q query tokens of a sequence (multi-token
+                                   prediction: the s_q tokens are the last s_q positions of the cache):
+                                   token t attends to keys 0 .. kv_len - s_q + t, i.e. to
+                                   kv_len - (s_q - 1 - t) keys; a token whose limit is <= 0 gets
+                                   out = 0, lse = -inf.  Without the flag every token attends to all
+                                   kv_len keys.  Runs in the balanced kernels (implies
+                                   AMLA_FLAG_BALANCED, and is switched off with it). */
 };
 
 typedef struct amla_desc {

@@ -106,6 +106,9 @@ bool balanced_enabled() {
   return e != nullptr && std::strcmp(e, "1") == 0;
 }
 
+// The causal mask lives in the balanced kernels only, so it selects them.
+bool uses_balanced(const amla_desc* d) { return (d->flags & (AMLA_FLAG_BALANCED | AMLA_FLAG_CAUSAL)) != 0; }
+
 bool desc_supported(const amla_desc* d) {
   if (d == nullptr) return false;
   if (d->d_qk != kDqk || d->d_v != kDv || d->block_size != kBlock) return false;
@@ -114,10 +117,11 @@ bool desc_supported(const amla_desc* d) {
     return false;
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
-  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED)) != 0)
+  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
+                    AMLA_FLAG_CAUSAL)) != 0)
     return false;
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
-  if ((d->flags & AMLA_FLAG_BALANCED) && ((d->flags & AMLA_FLAG_ASM_KERNEL) || !balanced_enabled())) return false;
+  if (uses_balanced(d) && ((d->flags & AMLA_FLAG_ASM_KERNEL) || !balanced_enabled())) return false;
   if ((long long)d->batch * d->max_blocks_per_seq > (1ll << 31) - 1) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
@@ -128,7 +132,7 @@ int choose_splits(const amla_desc* d) {
   if (d->num_splits > 0) return d->num_splits;
   const long long rows = (long long)d->s_q * d->num_heads;
   const long long tiles = (rows + kRowsPerWg - 1) / kRowsPerWg;
-  if (d->flags & AMLA_FLAG_BALANCED) {
+  if (uses_balanced(d)) {
     // workers: one workgroup per CU over all row tiles, never more workers than blocks can exist
     long long w = 256 / tiles > 0 ? 256 / tiles : 1;
     const long long most = (long long)d->batch * d->max_blocks_per_seq;
@@ -157,7 +161,7 @@ int amla_effective_splits(const amla_desc* desc) {
 size_t amla_workspace_bytes(const amla_desc* desc) {
   if (!desc_supported(desc)) return 0;
   const int ns = choose_splits(desc);
-  if (desc->flags & AMLA_FLAG_BALANCED) {
+  if (uses_balanced(desc)) {
     // one slot of s_q * num_heads partial rows per (worker, sequence) piece: slot ids < workers + batch - 1
     const size_t slots = (size_t)ns + desc->batch - 1;
     return slots * desc->s_q * desc->num_heads * (kDv + 1) * sizeof(float);
@@ -179,7 +183,7 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
 
   const int ns = choose_splits(desc);
   const size_t need = amla_workspace_bytes(desc);
-  const bool balanced = (desc->flags & AMLA_FLAG_BALANCED) != 0;
+  const bool balanced = uses_balanced(desc);
   if (ns > 1 || balanced) {
     if (desc->workspace == nullptr || desc->workspace_bytes < need) return AMLA_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(desc->workspace) & 15) return AMLA_ERR_WORKSPACE;
@@ -200,6 +204,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
   p.n_streams = balanced ? ns : desc->batch * ns;
   p.flags = desc->flags;
   p.num_blocks = desc->num_blocks;
+  p.heads = desc->num_heads;
+  p.causal_span = (desc->flags & AMLA_FLAG_CAUSAL) ? desc->s_q - 1 : 0;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   const size_t n_rows = (size_t)desc->batch * p.rows;
   p.part_o = (ns > 1 || balanced) ? static_cast<float*>(desc->workspace) : nullptr;

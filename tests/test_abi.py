@@ -85,6 +85,10 @@ def test_balanced_decomposition_is_gated_off_and_sized(amla, monkeypatch):
     assert _call(amla, d) == amla.AMLA_ERR_WORKSPACE         # pieces always need their slots
     d.flags |= amla.AMLA_FLAG_ASM_KERNEL
     assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
+    c = amla.make_desc(32, 2, 128, 5000, 256, flags=amla.AMLA_FLAG_CAUSAL)    # the mask selects the balanced kernels
+    assert amla.amla_effective_splits(c) == 128 and amla.amla_workspace_bytes(c) == (128 + 31) * 256 * 513 * 4
+    monkeypatch.delenv("AMLA_ENABLE_BALANCED")
+    assert _call(amla, c) == amla.AMLA_ERR_UNSUPPORTED
 
 
 def test_workspace_and_split_queries(amla):

@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SHIM = os.path.join(ROOT, "tests", "cpu_build")
 CLANG = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang++")
 MUL, ADD, COMP = 0, 1, 2
-NO_SKIP, LAZY, ASM, BALANCED = 1, 2, 4, 8
+NO_SKIP, LAZY, ASM, BALANCED, CAUSAL = 1, 2, 4, 8, 16
 FLAGS = ["-std=c++20", "-O0", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
          "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi"]
 
@@ -66,12 +66,13 @@ def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0):
     return out, lse, splits
 
 
-def check(out, lse, case, peaked=False):
+def check(out, lse, case, peaked=False, causal=False):
     """The GPU tests' bounds: |out error| <= 1e-2 where |exact| < 4, else half a bf16 step + 6e-3 for the
     rounding of the softmax weights; with `peaked` (query scale > 1: few keys carry the weight and the
     outputs reach several units) the second form everywhere, as in the GPU tests' wide-logit cases.
     |lse error| <= 1e-3."""
-    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                                causal=causal)
     fin = np.isfinite(want_lse)
     assert np.array_equal(lse[~fin], want_lse[~fin])
     half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 2.0 ** -20))) - 9)
@@ -139,6 +140,23 @@ def test_no_skip_flag_keeps_the_result(exe, tmp_path):
     b = run_cpu(exe, tmp_path, case, ADD, flags=NO_SKIP)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
     check(b[0], b[1], case)
+
+
+@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, 0), 3), ((ADD, LAZY), 7), ((COMP, 0), 2),
+                                          ((MUL, LAZY), 11)])
+def test_causal_mask_among_the_query_tokens(exe, tmp_path, kind, workers):
+    """s_q = 4 tokens, lengths around block boundaries: tokens with no key at all (kv_len 1), limits that
+    end exactly at or fall into the previous block (kv_len 64, 65, 66, 130: whole blocks masked for the
+    early tokens, also as the first block of a piece), and 40 heads so that one wave holds rows of two
+    tokens.  (Rows that see two or three keys are left out: there the bf16 rounding of two comparable
+    weights times the spread of two value rows alone can exceed the bound, mask or no mask.)"""
+    case = wl.make_case("causal", 57, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
+    out, lse, _ = run_cpu(exe, tmp_path, case, kind[0], flags=kind[1] | CAUSAL, ns=workers)
+    check(out, lse, case, causal=True)
+    assert np.all(out[0, :3] == 0) and np.all(np.isneginf(lse[0, :3]))
+    # and the mask matters: the unmasked result differs
+    plain, _ = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    assert np.abs(out[4, 0] - plain[4, 0]).max() > 0.05
 
 
 def test_auto_split_of_a_long_single_sequence(exe, tmp_path):

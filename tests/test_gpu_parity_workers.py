@@ -15,6 +15,7 @@ pytestmark = [pytest.mark.gpu,
                                  reason="balanced decomposition switched off: not yet run on hardware")]
 
 BALANCED = 8
+CAUSAL = 16
 COMP = 2
 KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((ADD, LAZY), id="add_lazy"),
          pytest.param((COMP, 0), id="add_comp")]
@@ -70,3 +71,35 @@ def test_full_size_ragged_config_balanced(env):
         worst[1] = max(worst[1], float(np.abs(lse[b] - want_lse[b]).max()))
     print(f"config 3 balanced: max|out err| {worst[0]:.3e} max|lse err| {worst[1]:.3e}", flush=True)
     assert worst[1] <= LSE_TOL
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("workers", [0, 3, 11])
+def test_causal_mask_among_the_query_tokens(env, kind, workers):
+    """s_q = 4 under AMLA_FLAG_CAUSAL: tokens without any key (kv_len 1), limits at and just past block
+    boundaries (whole blocks masked for the early tokens), 40 heads (two tokens per wave)."""
+    torch, orc, amla, wl = env
+    case = wl.make_case("causal", 43, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                                causal=True)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=kind[0], flags=kind[1] | CAUSAL,
+                       num_splits=workers)
+    check(out, lse, want, want_lse, f"causal workers={workers} {kind}")
+    assert np.all(out[0, :3] == 0)
+
+
+def test_causal_headline_shape_rows_match_shorter_caches(env):
+    """At the headline shape (batch 128, s_q 2, 128 heads, kv 4096) the first token under the mask equals
+    the unmasked run on caches one key shorter, the second token is unchanged."""
+    torch, orc, amla, wl = env
+    case = wl.make_config(2)
+    dev = to_dev(torch, case)
+    masked, masked_lse = run_gpu(torch, amla, case, dev, variant=ADD, flags=CAUSAL)
+    plain, plain_lse = run_gpu(torch, amla, case, dev, variant=ADD, flags=BALANCED)
+    q, kv, tab, lens = dev
+    shorter, shorter_lse = amla.amla_decode(q, kv, tab, lens - 1, case.softmax_scale, variant=ADD, flags=BALANCED)
+    torch.cuda.synchronize()
+    shorter = shorter.float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(masked[:, 1], plain[:, 1]) and np.array_equal(masked_lse[:, 1], plain_lse[:, 1])
+    assert np.array_equal(masked[:, 0], shorter[:, 0])
+    assert np.abs(masked_lse[:, 0] - shorter_lse.cpu().numpy()[:, 0]).max() == 0

@@ -167,3 +167,43 @@ def test_bf16_rounding_of_generator_is_nearest_even():
     bits = wl.f32_to_bf16_bits(x)
     back = wl.bf16_bits_to_f32(bits)
     assert back.tolist() == [1.0, 1.0, 1.015625, -2.5, 3.140625]
+
+
+# ------------------------------------------------------------------ causal mask among the s_q tokens
+def test_causal_rows_equal_unmasked_rows_of_a_shorter_cache():
+    """Token t of s_q under the causal mask is, by definition, the unmasked single-token problem on the
+    first kv_len - (s_q - 1 - t) keys; the last token sees everything, and with s_q = 1 the mask
+    changes nothing.  A token with no key gets the empty-sequence convention."""
+    case = wl.make_case("causal", 61, batch=3, s_q=3, heads=4, seqlens=[1, 66, 130], spare_frac=0.3)
+    masked, masked_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                                    causal=True)
+    plain, plain_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    assert np.array_equal(masked[:, 2], plain[:, 2]) and np.array_equal(masked_lse[:, 2], plain_lse[:, 2])
+    for t in range(3):
+        shorter = np.maximum(case.seqlens - (2 - t), 0).astype(np.int32)
+        one, one_lse = orc.decode(case.q_bits[:, t:t + 1], case.kv_bits, case.block_table, shorter, case.softmax_scale)
+        assert np.array_equal(masked[:, t], one[:, 0]) and np.array_equal(masked_lse[:, t], one_lse[:, 0])
+    # kv_len 1: tokens 0 and 1 have no key at all
+    assert np.all(masked[0, :2] == 0) and np.all(np.isneginf(masked_lse[0, :2]))
+    single = wl.make_case("causal1", 62, batch=2, s_q=1, heads=4, seqlens=[5, 70])
+    a = orc.decode(single.q_bits, single.kv_bits, single.block_table, single.seqlens, single.softmax_scale, causal=True)
+    b = orc.decode(single.q_bits, single.kv_bits, single.block_table, single.seqlens, single.softmax_scale)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_causal_mask_against_brute_force():
+    """Pure-Python softmax with the mask written out key by key."""
+    import math
+    case = wl.make_case("causal_bf", 63, batch=1, s_q=2, heads=2, seqlens=[5], table="identity")
+    got, got_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale, causal=True)
+    q = wl.bf16_bits_to_f32(case.q_bits).astype(float)
+    kv = wl.bf16_bits_to_f32(case.kv_bits).astype(float)[0]
+    for t in range(2):
+        for h in range(2):
+            visible = [j for j in range(5) if j <= 5 - 2 + t]          # keys 0 .. kv_len - s_q + t
+            logits = [case.softmax_scale * sum(q[0, t, h, d] * kv[j, d] for d in range(576)) for j in visible]
+            z = sum(math.exp(x) for x in logits)
+            for d in (0, 17, 511):
+                want = sum(math.exp(x) / z * kv[j, d] for x, j in zip(logits, visible))
+                assert abs(got[0, t, h, d] - want) < 1e-12
+            assert abs(got_lse[0, t, h] - math.log(z)) < 1e-12
