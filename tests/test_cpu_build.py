@@ -215,3 +215,21 @@ def test_the_harness_notices_a_tile_read_before_it_landed(tmp_path):
     env.pop("LD_PRELOAD", None)
     r = subprocess.run([bad, inp, outp], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode != 0 and "loads in flight" in r.stderr
+
+
+def test_thread_sanitizer_sees_no_race_between_waves(tmp_path):
+    """The same program under ThreadSanitizer: the waves of a workgroup share the LDS tile buffers (every
+    wave writes its share of a tile, all read all of it), and a buffer refilled or read on the wrong side
+    of a barrier is a data race between the threads that stand in for the waves."""
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ to build the CPU harness with")
+    (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
+    exe = str(tmp_path / "decode_tsan")
+    subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=thread", "-pthread",
+                    "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi", "-I" + SHIM,
+                    "-I" + os.path.join(ROOT, "include"), "-I" + str(tmp_path), os.path.join(SHIM, "decode_cpu.cpp"),
+                    "-o", exe], check=True)
+    case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
+    for flags, ns in ((BALANCED, 3), (0, 2)):
+        out, lse, _ = run_cpu(exe, tmp_path, case, ADD, flags=flags, ns=ns)      # a report makes the exit code non-zero
+        check(out, lse, case)
