@@ -220,16 +220,20 @@ def _round_bf16(x32: np.ndarray) -> np.ndarray:
     return r.view(np.float32)
 
 
-def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None):
+def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None, normalise="f32"):
     """Q, K, V are float32 arrays holding bf16-exact values.  Uses base-2 exponentials
     (t = s * scale * log2 e), mu_i = rint(max t) (= -n_i), P = 2^(t - mu_i) rounded to BF16
     for the PV product, FP32 row sum for l, exponent add for the rescale.  With
     `lazy_threshold` the reference mu is only moved when the row max exceeds it by more than
-    that many base-2 units (the weights may then grow up to 2^threshold)."""
+    that many base-2 units (the weights may then grow up to 2^threshold).  `normalise` chooses
+    what divides the accumulator at the end: "f32", the FP32 sum of the unrounded weights (as
+    Algorithm 2 sums them), or "b16", a second row sum over the BF16-rounded weights that
+    entered the product (lse always comes from the FP32 sum)."""
     f32 = np.float32
     G, L = Q.shape[0], K.shape[0]
     O = np.zeros((G, V.shape[1]), dtype=f32)
     l = np.zeros(G, dtype=f32)
+    l16 = np.zeros(G, dtype=f32)
     m = np.full(G, -np.inf, dtype=f32)
     mu = None
     c = f32(scale * math.log2(math.e))
@@ -241,14 +245,17 @@ def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None
         if lazy_threshold is not None and mu is not None:
             mu_new = np.where(m > mu + lazy_threshold, mu_new, mu)
         P = np.exp2((t - mu_new[:, None]).astype(f32)).astype(f32)
+        Pb = _round_bf16(P)
         if mu is not None:
             d = np.maximum(mu - mu_new, clamp).astype(np.int64)      # <= 0
             O = exponent_add_guarded(O, d[:, None])
             l = exponent_add_guarded(l, d)
+            l16 = exponent_add_guarded(l16, d)
         l = (l + P.sum(axis=1, dtype=f32)).astype(f32)
-        O = (O + (_round_bf16(P) @ Vb).astype(f32)).astype(f32)
+        l16 = (l16 + Pb.sum(axis=1, dtype=f32)).astype(f32)
+        O = (O + (Pb @ Vb).astype(f32)).astype(f32)
         mu = mu_new
-    out = O / l[:, None]
+    out = O / (l16 if normalise == "b16" else l)[:, None]
     lse = (mu.astype(np.float64) + np.log2(l.astype(np.float64))) * LN2
     return out, lse
 

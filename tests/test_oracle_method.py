@@ -223,11 +223,11 @@ def test_algorithm2_compensation_and_the_two_readings_of_c():
     """Algorithm 2 prints c_i = S32 / S16, Appendix A defines c_i = r_i / r'_i = S16 / S32.  With
     the appendix's definition the compensated recurrence, outputs rounded to BF16, is as accurate as
     Base (what Tables 3-4 report); with the printed one the correction has the wrong sign and the
-    error before output rounding is more than twice as large.  The recurrence the kernels run (power-
-    of-two reference, two row sums, no scale compensation) sits in between: its largest weight is not
-    BF16-exact, which costs up to ~1.7x Base's error on peaked rows -- inside the stated tolerance,
-    and the price of not touching the accumulator on every new row max.  Value rows are nonzero here
-    (the raw INT32 add of Algorithm 2 has no guard for zeros)."""
+    error before output rounding is more than twice as large.  Without any compensation (power-of-two
+    reference, largest weight not BF16-exact) the error on peaked rows is 25-40 % above Base when one
+    FP32 row sum normalises the output; the kernels' ADD and lazy variants keep a second sum over the
+    rounded weights, which takes most of that back (3-12 % above Base on 32-row means; 25 % is this 16-row sample's bound).  Value rows are
+    nonzero here (the raw INT32 add of Algorithm 2 has no guard for zeros)."""
     rng = np.random.default_rng(11)
     def bf(x):
         return orc._round_bf16(x.astype(np.float32))
@@ -239,10 +239,16 @@ def test_algorithm2_compensation_and_the_two_readings_of_c():
         app = orc.amla_alg2_emulation(Q, K, K[:, :512], 192 ** -0.5, c_reading="appendix")
         alg = orc.amla_alg2_emulation(Q, K, K[:, :512], 192 ** -0.5, c_reading="algorithm")
         base, _ = orc.flash_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5)
-        ours, _ = orc.amla_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5)
+        one_sum, _ = orc.amla_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5)
+        two_sums, _ = orc.amla_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5, normalise="b16")
+        lazy, _ = orc.amla_fp32_emulation(Q, K, K[:, :512], 192 ** -0.5, normalise="b16", lazy_threshold=8)
         assert e(alg) > 1.9 * e(app), (sigma, e(alg), e(app))
         assert abs(e(bf(app)) - e(bf(base))) < 0.1 * e(bf(base)), (sigma, e(bf(app)), e(bf(base)))
-        assert e(bf(base)) <= e(bf(ours)) < 1.8 * e(bf(base)), (sigma, e(bf(ours)), e(bf(base)))
+        assert e(bf(base)) <= e(bf(one_sum)) < 1.8 * e(bf(base)), (sigma, e(bf(one_sum)), e(bf(base)))
+        assert e(bf(two_sums)) < 1.25 * e(bf(base)), (sigma, e(bf(two_sums)), e(bf(base)))
+        assert e(bf(lazy)) < 1.25 * e(bf(base)), (sigma, e(bf(lazy)), e(bf(base)))
+        if sigma > 1.0:
+            assert e(bf(two_sums)) < 0.95 * e(bf(one_sum)), (sigma, e(bf(two_sums)), e(bf(one_sum)))
 
 
 def test_compensation_restated_in_base_two_matches_algorithm2():
