@@ -105,7 +105,8 @@ typedef struct amla_desc {
   int32_t variant;             /* AMLA_RESCALE_MUL, AMLA_RESCALE_ADD or AMLA_RESCALE_ADD_COMP */
   int32_t num_splits;          /* split-KV factor: each sequence's blocks are cut into this many
                                   contiguous ranges processed by separate workgroups and merged
-                                  by a combine kernel.  0 = library chooses from the shape. */
+                                  by a combine kernel.  0 = library chooses from the shape; at
+                                  most 256. */
   int32_t flags;               /* AMLA_FLAG_* */
   int32_t reserved;            /* must be 0 */
   void* workspace;             /* device scratch for split-KV partials; may be NULL when the

@@ -1,4 +1,7 @@
 // Absorbed-MLA decode attention for gfx950 (MI355X): kernels and the C-ABI entry points.
+// Device code: amla_decode_kernels.inc (kernels, included below) and amla_decode_piece.inc (the body
+// of the decode loop, shared by the equal-share and the balanced kernel); amla_plan.h holds the
+// balanced decomposition's integer arithmetic; this file holds the host side.
 //
 // One workgroup (4 waves, one per SIMD, up to 512 VGPRs each) owns 128 query rows of one
 // sequence and a contiguous range of that sequence's 64-key cache blocks.  Wave w owns
