@@ -48,11 +48,59 @@ def out_tolerance(want):
     return np.where(np.abs(want) < 4.0, OUT_TOL, half_ulp + 6e-3)
 
 
+def describe_mismatch(out, lse, want, want_lse, what):
+    """Where the wrong elements sit, printed once when a case fails: by sequence, by row within a 128-row
+    workgroup tile (wave = row // 32, MFMA column = row % 32), by output column (32-column accumulator
+    tile = col // 32, position in it = col % 32), and how wrong they are.  One failing run should be
+    enough to tell an addressing mistake from a synchronisation or an arithmetic one."""
+    B = out.shape[0]
+    o = out.reshape(B, -1, 512)
+    w = want.reshape(B, -1, 512)
+    bad = ~(np.abs(o - w) <= out_tolerance(w))            # NaNs count as bad
+    lines = [f"--- mismatch report: {what}: {int(bad.sum())} of {bad.size} elements outside the bound, "
+             f"{int(np.isnan(o).sum())} NaN, {int(np.isinf(o).sum())} inf"]
+    if bad.any():
+        b_idx, r_idx, c_idx = np.nonzero(bad)
+        def hist(name, v, n):
+            h = np.bincount(v, minlength=n)
+            lines.append(f"{name}: " + " ".join(f"{i}:{c}" for i, c in enumerate(h) if c))
+        hist("by sequence", b_idx, B)
+        hist("by wave (row // 32 % 4)", (r_idx // 32) % 4, 4)
+        hist("by row tile (row // 128)", r_idx // 128, int(r_idx.max()) // 128 + 1)
+        hist("by row % 32", r_idx % 32, 32)
+        hist("by column tile (col // 32)", c_idx // 32, 16)
+        hist("by col % 32", c_idx % 32, 32)
+        with np.errstate(all="ignore"):
+            ratio = o[bad] / w[bad]
+        fin = np.isfinite(ratio)
+        if fin.any():
+            q = np.percentile(ratio[fin], [5, 50, 95])
+            lines.append(f"out / want over the bad elements: 5 % {q[0]:.4g}  median {q[1]:.4g}  95 % {q[2]:.4g}")
+        lines.append(f"first bad: seq {b_idx[0]} row {r_idx[0]} col {c_idx[0]}: got {o[b_idx[0], r_idx[0], c_idx[0]]!r} "
+                     f"want {w[b_idx[0], r_idx[0], c_idx[0]]!r}")
+    fin = np.isfinite(want_lse)
+    if fin.any():
+        le = np.abs(lse[fin] - want_lse[fin])
+        lines.append(f"lse: {int((~(le <= LSE_TOL)).sum())} of {le.size} rows outside the bound, max {np.nanmax(le):.3e}, "
+                     f"{int(np.isnan(lse).sum())} NaN")
+    text = "\n".join(lines)
+    print(text, flush=True)
+    try:
+        os.makedirs("gpurun_out", exist_ok=True)
+        with open(os.path.join("gpurun_out", "mismatch_report.txt"), "a") as f:
+            f.write(text + "\n")
+    except OSError:
+        pass
+
+
 def check(out, lse, want, want_lse, what):
     fin = np.isfinite(want_lse)
     eo = np.abs(out - want).max()
     el = np.abs(lse[fin] - want_lse[fin]).max() if fin.any() else 0.0
     print(f"{what}: max|out err| {eo:.3e}  max|lse err| {el:.3e}  max|out| {np.abs(want).max():.3f}", flush=True)
+    if not (np.array_equal(lse[~fin], want_lse[~fin]) and np.all(np.abs(out - want) <= out_tolerance(want))
+            and el <= LSE_TOL):
+        describe_mismatch(out, lse, want, want_lse, what)
     assert np.array_equal(lse[~fin], want_lse[~fin]), what
     assert np.all(np.abs(out - want) <= out_tolerance(want)), (what, eo)
     assert el <= LSE_TOL, (what, el)
