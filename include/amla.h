@@ -126,8 +126,9 @@ typedef struct amla_desc {
  *                still poison the value product).
  *   block_table  int32 [batch, max_blocks_per_seq]; entry j of row b is the physical block of
  *                keys 64j .. 64j+63 of sequence b.  Entries j >= ceil(kv_len[b]/64) are never
- *                read.  Entries that are read must lie in [0, num_blocks); this is not checked
- *                on the device.
+ *                read.  Entries that are read must lie in [0, num_blocks).  The balanced and the
+ *                hand-scheduled kernels clamp them into that range (a wrong entry then gives a
+ *                wrong result, not a wild access); the default kernels read them as they are.
  *   seqlens      int32 [batch], 0 <= kv_len[b] <= 64 * max_blocks_per_seq
  *   softmax_scale  multiplies q.k before the softmax (the paper's 1/sqrt(D_k) generalised);
  *                finite and > 0

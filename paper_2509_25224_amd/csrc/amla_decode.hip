@@ -91,8 +91,10 @@ struct AsmArgs {
   int32_t n_streams;
   int32_t flags;
   uint32_t split_magic;   // floor(2^32 / n_splits) + 1: x / n_splits == mulhi(x, magic) for x * n_splits < 2^32
+  int32_t num_blocks;     // physical blocks in the pool: table entries are clamped into it
+  int32_t pad;
 };
-static_assert(sizeof(AsmArgs) == 0x60, "kernel argument block layout");
+static_assert(sizeof(AsmArgs) == 0x68, "kernel argument block layout");
 
 // The hand-scheduled kernels are switched off unless the process opts in: their first run on
 // the GPU faulted (a missing wait state before v_readfirstlane, since fixed in the generator)
@@ -247,7 +249,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     const unsigned long long ns2 = (unsigned long long)ns * ns;
     if (ns2 * (unsigned long long)desc->max_blocks_per_seq >= (1ull << 32) ||
         ns2 * (unsigned long long)desc->batch >= (1ull << 32) ||
-        (unsigned long long)ns * n_rows >= (1ull << 31) || p.n_tiles * 8ll > 65535 || streams_pad / 8 > 65535)
+        (unsigned long long)ns * n_rows >= (1ull << 31) || p.n_tiles * 8ll > 65535 || streams_pad / 8 > 65535 ||
+        desc->max_blocks_per_seq > (1 << 24))
       return AMLA_ERR_UNSUPPORTED;
     const DeviceKernels* dk = device_kernels();
     if (dk == nullptr) return AMLA_ERR_LAUNCH;
@@ -268,6 +271,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     a.n_streams = p.n_streams;
     a.flags = p.flags;
     a.split_magic = ns > 1 ? (uint32_t)((1ull << 32) / (unsigned)ns) + 1u : 0u;
+    a.num_blocks = desc->num_blocks;
+    a.pad = 0;
     size_t arg_size = sizeof(a);
     void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &a, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
     const int which = (desc->variant == AMLA_RESCALE_ADD ? 1 : 0) + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 2 : 0);

@@ -87,9 +87,10 @@ S_ULD2 = 60      # the sub-tile index it belongs to
 S_DOIT = 61      # accumulator rescale wanted in this pass
 S_GB2 = 62       # 2: global base of the next sub-tile to load
 S_UPART = 64     # index of the sub-tile with fewer than 32 keys in range, or -1
-S_NEXT_FREE = 66
+S_NBLKM1 = 66    # num_blocks - 1: every block-table entry is clamped into [0, num_blocks - 1]
+S_NEXT_FREE = 67
 
-KARG_SIZE = 0x60
+KARG_SIZE = 0x68
 
 
 class Gen:
@@ -187,12 +188,14 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     # ------------------------------------------------------------------ prologue: arguments
     g(f"s_load_dwordx16 {sr(S_QP, 16)}, {sr(S_KARG, 2)}, 0x0")
     g(f"s_load_dwordx8 {sr(S_C, 8)}, {sr(S_KARG, 2)}, 0x40")
+    g(f"s_load_dword {sr(S_NBLKM1)}, {sr(S_KARG, 2)}, 0x60")
     g(f"v_and_b32 v{T0}, 0x3ff, v0")                            # workitem id x (v0 packs x, y, z)
     g(f"s_and_b32 {sr(S_T0)}, {sr(S_WGX)}, 7")                  # xcd
     g(f"s_lshr_b32 {sr(S_TILE)}, {sr(S_WGX)}, 3")
     g(f"s_lshl_b32 {sr(S_STREAM)}, {sr(S_WGY)}, 3")
     g(f"s_or_b32 {sr(S_STREAM)}, {sr(S_STREAM)}, {sr(S_T0)}")
     g("s_waitcnt lgkmcnt(0)")
+    g(f"s_sub_u32 {sr(S_NBLKM1)}, {sr(S_NBLKM1)}, 1")
     if os.environ.get("AMLA_ASM_DEBUG") == "1":
         g("v_mov_b32 v2, 0")
         for i, reg in enumerate((S_WGX, S_WGY, S_STREAM, S_NSTREAMS, S_ROWS, S_NS)):
@@ -288,6 +291,9 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
 
     # sub-tile range of this split
     g("s_waitcnt lgkmcnt(0)")
+    g(f"s_max_i32 {sr(S_LEN)}, {sr(S_LEN)}, 0")                 # a length outside [0, 64 * max_blocks] must not
+    g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_MAXB)}, 6")                # reach past the sequence's block-table row
+    g(f"s_min_i32 {sr(S_LEN)}, {sr(S_LEN)}, {sr(S_T0)}")
     g(f"s_add_u32 {sr(S_T0)}, {sr(S_LEN)}, 63")
     g(f"s_lshr_b32 {sr(S_T0)}, {sr(S_T0)}, 6")                  # nb
     g(f"s_add_u32 {sr(S_T1)}, {sr(S_LEN)}, 31")
@@ -328,7 +334,9 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     # ---- direct-to-LDS load of one sub-tile ---------------------------------------------------
     def tile_base_code(dst=S_GB, phys=S_PHYS, uld=S_ULD):
         """dst = kv + phys * 73728 + (uld & 1) * 36864."""
-        return [f"s_mul_i32 {sr(S_T2)}, {sr(phys)}, 73728",
+        return [f"s_max_i32 {sr(phys)}, {sr(phys)}, 0",                 # a table entry outside the pool must not
+                f"s_min_i32 {sr(phys)}, {sr(phys)}, {sr(S_NBLKM1)}",    # become a wild address
+                f"s_mul_i32 {sr(S_T2)}, {sr(phys)}, 73728",
                 f"s_mul_hi_u32 {sr(S_T3)}, {sr(phys)}, 73728",
                 f"s_and_b32 {sr(S_T1)}, {sr(uld)}, 1",
                 f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, 36864",

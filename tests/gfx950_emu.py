@@ -434,6 +434,14 @@ class Wave:
         if mnem == "s_mul_hi_u32":
             self.sdst(ops[0], (S(ops[1]) * S(ops[2])) >> 32)
             return nxt
+        if mnem in ("s_min_i32", "s_max_i32"):
+            a, b = S(ops[1]), S(ops[2])
+            sa = a - (1 << 32) if a >> 31 else a
+            sb = b - (1 << 32) if b >> 31 else b
+            first = sa < sb if mnem == "s_min_i32" else sa > sb
+            self.sdst(ops[0], a if first else b)
+            self.scc = int(first)
+            return nxt
         if mnem == "s_min_u32":
             a, b = S(ops[1]), S(ops[2])
             self.sdst(ops[0], min(a, b))

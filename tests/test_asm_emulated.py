@@ -45,8 +45,9 @@ def run_case(asm_text, kernel, case, n_splits, flags=0, dma_late=False, smem_fir
     magic = ((1 << 32) // n_splits + 1) & 0xFFFFFFFF if n_splits > 1 else 0
     scale_log2e = np.float32(case.softmax_scale) * np.float32(1.4426950408889634)
     karg = struct.pack("<8Q", q, kv, tab, lens, out, lse, po, pl) + struct.pack(
-        "<f6iI", float(scale_log2e), B, rows, n_splits, case.max_blocks_per_seq, n_streams, flags, magic)
-    assert len(karg) == 0x60
+        "<f6iIii", float(scale_log2e), B, rows, n_splits, case.max_blocks_per_seq, n_streams, flags, magic,
+        case.num_blocks, 0)
+    assert len(karg) == 0x68
     ka = mem.add("kernarg", np.frombuffer(karg, dtype=np.uint8))
     n_tiles = (rows + 127) // 128
     gy = (n_streams + 7) // 8
@@ -211,3 +212,16 @@ def test_modelled_pass_time_of_the_lazy_kernel(asm_text):
     per_pass, stall = timing.cycles_per_pass(ins, labels, trace, f".L_{kernel}_loop")
     print(f"modelled cycles per pass: {per_pass:.0f}, stalls {dict(stall)}")
     assert 2176 <= per_pass <= 2176 * 1.10
+
+
+def test_bad_table_entries_and_lengths_stay_inside_the_buffers(asm_text):
+    """A block-table entry outside the pool and a length past the table row are caller mistakes; the
+    kernels clamp both, so the result is unspecified but every access stays inside the buffers (the
+    emulator's memory raises on any access outside them)."""
+    case = wl.make_case("bad", 36, batch=2, s_q=1, heads=4, seqlens=[200, 130], table="identity")
+    case.block_table[0, 1] = 1 << 20
+    case.block_table[0, 2] = -5
+    case.seqlens[1] = 10 ** 6
+    for kernel in ("amla_decode_asm_add", "amla_decode_asm_mul_lazy"):
+        o, l, _ = run_case(asm_text, kernel, case, 1)
+        assert np.all(np.isfinite(o[0]))          # clamped entries point at real blocks
