@@ -210,6 +210,8 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"s_mul_hi_u32 {sr(S_T1)}, {sr(S_STREAM)}, {sr(S_MAGIC)}")
     g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
     g(f"s_cselect_b32 {sr(S_B)}, {sr(S_STREAM)}, {sr(S_T1)}")
+    g(f"s_sub_u32 {sr(S_T1)}, {sr(S_BATCH)}, 1")
+    g(f"s_min_u32 {sr(S_B)}, {sr(S_B)}, {sr(S_T1)}")              # b < batch whatever the launch arguments say
     g(f"s_mul_i32 {sr(S_T1)}, {sr(S_B)}, {sr(S_NS)}")
     g(f"s_sub_u32 {sr(S_SPLIT)}, {sr(S_STREAM)}, {sr(S_T1)}")
     g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_B)}, 2")
