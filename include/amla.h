@@ -74,7 +74,7 @@ enum {
 
 /* desc->flags, continued */
 enum {
-  AMLA_FLAG_BALANCED = 8,       /* decomposition for ragged batches (compiler-built kernel only): the 64-key
+  AMLA_FLAG_BALANCED = 8,       /* decomposition for ragged batches: the 64-key
                                    blocks of all sequences are laid end to end and cut into equal
                                    ranges, one per worker workgroup; a worker walks its range sequence
                                    by sequence, and the pieces of a sequence are merged like split-KV
@@ -89,8 +89,9 @@ enum {
                                    token t attends to keys 0 .. kv_len - s_q + t, i.e. to
                                    kv_len - (s_q - 1 - t) keys; a token whose limit is <= 0 gets
                                    out = 0, lse = -inf.  Without the flag every token attends to all
-                                   kv_len keys.  Runs in the balanced kernels (implies
-                                   AMLA_FLAG_BALANCED, and is switched off with it). */
+                                   kv_len keys.  Runs in the compiler-built balanced kernels (implies
+                                   AMLA_FLAG_BALANCED, is switched off with it, and cannot be
+                                   combined with AMLA_FLAG_ASM_KERNEL). */
 };
 
 typedef struct amla_desc {

@@ -45,9 +45,11 @@ const unsigned char kDecodeCodeObject[] = {
 };
 
 constexpr int kMaxDevices = 64;
-constexpr int kAsmKernels = 4;   // index = variant + 2 * lazy
-const char* const kAsmNames[kAsmKernels] = {"amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_mul_lazy",
-                                            "amla_decode_asm_add_lazy"};
+constexpr int kAsmKernels = 8;   // index = variant + 2 * lazy + 4 * balanced
+const char* const kAsmNames[kAsmKernels] = {"amla_decode_asm_mul",          "amla_decode_asm_add",
+                                            "amla_decode_asm_mul_lazy",     "amla_decode_asm_add_lazy",
+                                            "amla_decode_asm_mul_bal",      "amla_decode_asm_add_bal",
+                                            "amla_decode_asm_mul_lazy_bal", "amla_decode_asm_add_lazy_bal"};
 struct DeviceKernels {
   bool tried = false;
   bool ok = false;
@@ -93,8 +95,10 @@ struct AsmArgs {
   uint32_t split_magic;   // floor(2^32 / n_splits) + 1: x / n_splits == mulhi(x, magic) for x * n_splits < 2^32
   int32_t num_blocks;     // physical blocks in the pool: table entries are clamped into it
   int32_t pad;
+  int32_t workers;        // balanced kernels: number of workers W (= n_streams)
+  uint32_t worker_magic;  // floor(2^32 / W) + 1: x / W == mulhi(x, magic) for x * W < 2^32 (W == 1 is special-cased)
 };
-static_assert(sizeof(AsmArgs) == 0x68, "kernel argument block layout");
+static_assert(sizeof(AsmArgs) == 0x70, "kernel argument block layout");
 
 // The hand-scheduled kernels are switched off unless the process opts in: their first run on
 // the GPU faulted (a missing wait state before v_readfirstlane, since fixed in the generator)
@@ -126,7 +130,8 @@ bool desc_supported(const amla_desc* d) {
                     AMLA_FLAG_CAUSAL)) != 0)
     return false;
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
-  if (uses_balanced(d) && ((d->flags & AMLA_FLAG_ASM_KERNEL) || !balanced_enabled())) return false;
+  if (uses_balanced(d) && !balanced_enabled()) return false;
+  if ((d->flags & AMLA_FLAG_CAUSAL) && (d->flags & AMLA_FLAG_ASM_KERNEL)) return false;   // the mask is in the compiler-built kernels only
   if ((long long)d->batch * d->max_blocks_per_seq > (1ll << 31) - 1) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
@@ -252,6 +257,9 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
         (unsigned long long)ns * n_rows >= (1ull << 31) || p.n_tiles * 8ll > 65535 || streams_pad / 8 > 65535 ||
         desc->max_blocks_per_seq > (1 << 24))
       return AMLA_ERR_UNSUPPORTED;
+    // balanced: worker ranges w T / W by the same kind of division, T <= batch * max_blocks_per_seq
+    if (balanced && (unsigned long long)ns * ns * (unsigned long long)desc->batch * desc->max_blocks_per_seq >= (1ull << 32))
+      return AMLA_ERR_UNSUPPORTED;
     const DeviceKernels* dk = device_kernels();
     if (dk == nullptr) return AMLA_ERR_LAUNCH;
     AsmArgs a;
@@ -273,9 +281,16 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     a.split_magic = ns > 1 ? (uint32_t)((1ull << 32) / (unsigned)ns) + 1u : 0u;
     a.num_blocks = desc->num_blocks;
     a.pad = 0;
+    a.workers = balanced ? ns : 0;
+    a.worker_magic = balanced ? (uint32_t)((1ull << 32) / (unsigned)ns) + 1u : 0u;
+    if (balanced) {
+      a.n_splits = 1;
+      a.split_magic = 0;
+    }
     size_t arg_size = sizeof(a);
     void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &a, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
-    const int which = (desc->variant == AMLA_RESCALE_ADD ? 1 : 0) + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 2 : 0);
+    const int which = (desc->variant == AMLA_RESCALE_ADD ? 1 : 0) + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 2 : 0) +
+                      (balanced ? 4 : 0);
     if (hipModuleLaunchKernel(dk->fn[which], (unsigned)(8 * p.n_tiles), (unsigned)(streams_pad / 8), 1, kThreads, 1, 1,
                               0, stream, nullptr, config) != hipSuccess) {
       (void)hipGetLastError();

@@ -88,9 +88,19 @@ S_DOIT = 61      # accumulator rescale wanted in this pass
 S_GB2 = 62       # 2: global base of the next sub-tile to load
 S_UPART = 64     # index of the sub-tile with fewer than 32 keys in range, or -1
 S_NBLKM1 = 66    # num_blocks - 1: every block-table entry is clamped into [0, num_blocks - 1]
-S_NEXT_FREE = 67
+# balanced decomposition (worker walk over the batch's concatenated block list)
+S_WORKERS, S_WMAGIC = 68, 69   # number of workers W, floor(2^32 / W) + 1 (an even-aligned pair: one load)
+S_LEFT = 70      # blocks of this worker's range still to process
+S_J = 71         # next block of the current sequence
+S_J0, S_J1 = 72, 73            # the piece: blocks [j0, j1) of sequence S_B
+S_FULL = 74      # the piece covers its whole sequence: write out / lse directly
+S_I = 75         # scan index
+S_ACC = 76       # scan: blocks before sequence S_I
+S_G0 = 77
+S_LB = 80        # 16: lengths of one scan chunk (s[80:95])
+S_NEXT_FREE = 96
 
-KARG_SIZE = 0x68
+KARG_SIZE = 0x70
 
 
 class Gen:
@@ -180,7 +190,7 @@ def interleave(g, groups, valu, first_group=0):
     assert vi == len(valu)
 
 
-def kernel(g: Gen, name: str, rescale: str, lazy: bool):
+def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
     L = lambda s: f".L_{name}_{s}"
     g.lines.append(f"\t.globl {name}\n\t.p2align 8\n\t.type {name},@function")
     g.label(name)
@@ -189,6 +199,8 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"s_load_dwordx16 {sr(S_QP, 16)}, {sr(S_KARG, 2)}, 0x0")
     g(f"s_load_dwordx8 {sr(S_C, 8)}, {sr(S_KARG, 2)}, 0x40")
     g(f"s_load_dword {sr(S_NBLKM1)}, {sr(S_KARG, 2)}, 0x60")
+    if balanced:
+        g(f"s_load_dwordx2 {sr(S_WORKERS, 2)}, {sr(S_KARG, 2)}, 0x68")
     g(f"v_and_b32 v{T0}, 0x3ff, v0")                            # workitem id x (v0 packs x, y, z)
     g(f"s_and_b32 {sr(S_T0)}, {sr(S_WGX)}, 7")                  # xcd
     g(f"s_lshr_b32 {sr(S_TILE)}, {sr(S_WGX)}, 3")
@@ -206,29 +218,145 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
         g("s_endpgm")
     g(f"s_cmp_ge_i32 {sr(S_STREAM)}, {sr(S_NSTREAMS)}")
     g(f"s_cbranch_scc1 {L('end')}")
-    # b = stream / n_splits, split = stream % n_splits
-    g(f"s_mul_hi_u32 {sr(S_T1)}, {sr(S_STREAM)}, {sr(S_MAGIC)}")
-    g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
-    g(f"s_cselect_b32 {sr(S_B)}, {sr(S_STREAM)}, {sr(S_T1)}")
-    g(f"s_sub_u32 {sr(S_T1)}, {sr(S_BATCH)}, 1")
-    g(f"s_min_u32 {sr(S_B)}, {sr(S_B)}, {sr(S_T1)}")              # b < batch whatever the launch arguments say
-    g(f"s_mul_i32 {sr(S_T1)}, {sr(S_B)}, {sr(S_NS)}")
-    g(f"s_sub_u32 {sr(S_SPLIT)}, {sr(S_STREAM)}, {sr(S_T1)}")
-    g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_B)}, 2")
-    g(f"s_load_dword {sr(S_LEN)}, {sr(S_LENP, 2)}, {sr(S_T1)}")
-    # block table row: table + b * max_blocks * 4
-    g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_MAXB)}")
-    g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_B)}, {sr(S_MAXB)}")
-    g(f"s_lshl_b64 {sr(S_T2, 2)}, {sr(S_T2, 2)}, 2")
-    g(f"s_add_u32 {sr(S_TABB)}, {sr(S_TABP)}, {sr(S_T2)}")
-    g(f"s_addc_u32 {sr(S_TABB + 1)}, {sr(S_TABP + 1)}, {sr(S_T3)}")
-    # lane decomposition
-    g(f"v_lshrrev_b32 v{T1}, 6, v{T0}")
-    g("s_nop 3")                                                # VALU write -> v_readfirstlane of the same VGPR needs a wait state
-    g(f"v_readfirstlane_b32 {sr(S_WAVE)}, v{T1}")
-    g("s_nop 3")
-    g(f"s_and_b32 {sr(S_WAVE)}, {sr(S_WAVE)}, 3")               # 4 waves; keeps every derived LDS / global offset in range
-    g(f"v_and_b32 v{T0}, 63, v{T0}")                            # lane
+
+    def table_row_of_b():
+        # block table row: table + b * max_blocks * 4
+        g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_MAXB)}")
+        g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_B)}, {sr(S_MAXB)}")
+        g(f"s_lshl_b64 {sr(S_T2, 2)}, {sr(S_T2, 2)}, 2")
+        g(f"s_add_u32 {sr(S_TABB)}, {sr(S_TABP)}, {sr(S_T2)}")
+        g(f"s_addc_u32 {sr(S_TABB + 1)}, {sr(S_TABP + 1)}, {sr(S_T3)}")
+
+    def wave_id_from_v0():
+        g(f"v_lshrrev_b32 v{T1}, 6, v{T0}")
+        g("s_nop 3")                                                # VALU write -> v_readfirstlane of the same VGPR needs a wait state
+        g(f"v_readfirstlane_b32 {sr(S_WAVE)}, v{T1}")
+        g("s_nop 3")
+        g(f"s_and_b32 {sr(S_WAVE)}, {sr(S_WAVE)}, 3")               # 4 waves; keeps every derived LDS / global offset in range
+
+    if not balanced:
+        # b = stream / n_splits, split = stream % n_splits
+        g(f"s_mul_hi_u32 {sr(S_T1)}, {sr(S_STREAM)}, {sr(S_MAGIC)}")
+        g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
+        g(f"s_cselect_b32 {sr(S_B)}, {sr(S_STREAM)}, {sr(S_T1)}")
+        g(f"s_sub_u32 {sr(S_T1)}, {sr(S_BATCH)}, 1")
+        g(f"s_min_u32 {sr(S_B)}, {sr(S_B)}, {sr(S_T1)}")              # b < batch whatever the launch arguments say
+        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_B)}, {sr(S_NS)}")
+        g(f"s_sub_u32 {sr(S_SPLIT)}, {sr(S_STREAM)}, {sr(S_T1)}")
+        g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_B)}, 2")
+        g(f"s_load_dword {sr(S_LEN)}, {sr(S_LENP, 2)}, {sr(S_T1)}")
+        table_row_of_b()
+        # lane decomposition
+        wave_id_from_v0()
+        g(f"v_and_b32 v{T0}, 63, v{T0}")                            # lane
+    else:
+        # ---- balanced decomposition: this workgroup is worker S_STREAM of S_WORKERS.  The blocks of all
+        # sequences laid end to end are cut into equal worker ranges [w T / W, (w + 1) T / W); the
+        # worker walks its range sequence by sequence, one piece (= one turn of the loop below) per
+        # sequence it meets.  Divisions by W are mulhi by floor(2^32 / W) + 1, exact while
+        # (w + 1) T W < 2^32 (checked by the host).
+        wave_id_from_v0()                                           # v0 is overwritten by the first piece's Q loads
+
+        def scan_chunk(per_length):
+            """Loads lengths S_I .. S_I + 15 (indices past the end re-read the last one) and hands each,
+            as a block count in S_T2 (0 past the end), to per_length(k)."""
+            g(f"s_sub_u32 {sr(S_T3)}, {sr(S_BATCH)}, 1")
+            for k in range(16):
+                g(f"s_add_u32 {sr(S_T1)}, {sr(S_I)}, {k}")
+                g(f"s_min_u32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_T3)}")
+                g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_T1)}, 2")
+                g(f"s_load_dword {sr(S_LB + k)}, {sr(S_LENP, 2)}, {sr(S_T1)}")
+            g("s_waitcnt lgkmcnt(0)")
+            g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_MAXB)}, 6")                # longest length the table row allows
+            for k in range(16):
+                g(f"s_max_i32 {sr(S_T2)}, {sr(S_LB + k)}, 0")
+                g(f"s_min_i32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_T0)}")
+                g(f"s_add_u32 {sr(S_T2)}, {sr(S_T2)}, 63")
+                g(f"s_lshr_b32 {sr(S_T2)}, {sr(S_T2)}, 6")              # blocks of sequence S_I + k
+                g(f"s_add_u32 {sr(S_T1)}, {sr(S_I)}, {k}")
+                g(f"s_cmp_ge_u32 {sr(S_T1)}, {sr(S_BATCH)}")
+                g(f"s_cselect_b32 {sr(S_T2)}, 0, {sr(S_T2)}")
+                per_length(k)
+
+        # pass 1: T = blocks of the whole batch (in S_ACC)
+        g(f"s_mov_b32 {sr(S_I)}, 0")
+        g(f"s_mov_b32 {sr(S_ACC)}, 0")
+        g.label(L("scan_total"))
+        scan_chunk(lambda k: g(f"s_add_u32 {sr(S_ACC)}, {sr(S_ACC)}, {sr(S_T2)}"))
+        g(f"s_add_u32 {sr(S_I)}, {sr(S_I)}, 16")
+        g(f"s_cmp_lt_u32 {sr(S_I)}, {sr(S_BATCH)}")
+        g(f"s_cbranch_scc1 {L('scan_total')}")
+        # this worker's range
+        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_STREAM)}, {sr(S_ACC)}")         # w T
+        g(f"s_add_u32 {sr(S_T2)}, {sr(S_T1)}, {sr(S_ACC)}")              # (w + 1) T
+        g(f"s_mul_hi_u32 {sr(S_G0)}, {sr(S_T1)}, {sr(S_WMAGIC)}")
+        g(f"s_mul_hi_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_WMAGIC)}")
+        g(f"s_cmp_eq_u32 {sr(S_WORKERS)}, 1")                            # floor(2^32 / 1) + 1 does not fit 32 bits
+        g(f"s_cselect_b32 {sr(S_G0)}, 0, {sr(S_G0)}")
+        g(f"s_cselect_b32 {sr(S_T2)}, {sr(S_ACC)}, {sr(S_T2)}")
+        g(f"s_sub_u32 {sr(S_LEFT)}, {sr(S_T2)}, {sr(S_G0)}")
+        g(f"s_cmp_eq_u32 {sr(S_LEFT)}, 0")
+        g(f"s_cbranch_scc1 {L('end')}")
+        # pass 2: the sequence that holds block g0: the first i with (blocks before i) + nb_i > g0
+        g(f"s_mov_b32 {sr(S_I)}, 0")
+        g(f"s_mov_b32 {sr(S_ACC)}, 0")
+        g(f"s_mov_b32 {sr(S_B)}, -1")
+
+        def locate(k):
+            g(f"s_add_u32 {sr(S_T1)}, {sr(S_ACC)}, {sr(S_T2)}")          # blocks up to and including this sequence
+            g(f"s_add_u32 {sr(S_NEED)}, {sr(S_I)}, {k}")                 # candidate sequence
+            g(f"s_sub_u32 {sr(S_NEED + 1)}, {sr(S_G0)}, {sr(S_ACC)}")    # and g0's position in it
+            g(f"s_cmp_gt_u32 {sr(S_T1)}, {sr(S_G0)}")
+            g(f"s_cselect_b32 {sr(S_T3)}, 1, 0")
+            g(f"s_cmp_eq_u32 {sr(S_B)}, -1")
+            g(f"s_cselect_b32 {sr(S_T3)}, {sr(S_T3)}, 0")                # found here and not found before
+            g(f"s_cmp_eq_u32 {sr(S_T3)}, 1")
+            g(f"s_cselect_b32 {sr(S_B)}, {sr(S_NEED)}, {sr(S_B)}")
+            g(f"s_cselect_b32 {sr(S_J)}, {sr(S_NEED + 1)}, {sr(S_J)}")
+            g(f"s_mov_b32 {sr(S_ACC)}, {sr(S_T1)}")
+        g(f"s_mov_b32 {sr(S_J)}, 0")
+        g.label(L("scan_locate"))
+        scan_chunk(locate)
+        g(f"s_add_u32 {sr(S_I)}, {sr(S_I)}, 16")
+        g(f"s_cmp_lg_u32 {sr(S_B)}, -1")
+        g(f"s_cbranch_scc1 {L('located')}")
+        g(f"s_cmp_lt_u32 {sr(S_I)}, {sr(S_BATCH)}")
+        g(f"s_cbranch_scc1 {L('scan_locate')}")
+        g(f"s_branch {L('end')}")                                       # unreachable while g0 < T
+        g.label(L("located"))
+
+        # ---- next piece of the walk
+        g.label(L("piece_begin"))
+        g(f"s_cmp_ge_u32 {sr(S_B)}, {sr(S_BATCH)}")
+        g(f"s_cbranch_scc1 {L('end')}")                                 # unreachable while left <= blocks remaining
+        g(f"s_lshl_b32 {sr(S_T1)}, {sr(S_B)}, 2")
+        g(f"s_load_dword {sr(S_LEN)}, {sr(S_LENP, 2)}, {sr(S_T1)}")
+        g("s_waitcnt lgkmcnt(0)")
+        g(f"s_max_i32 {sr(S_LEN)}, {sr(S_LEN)}, 0")
+        g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_MAXB)}, 6")
+        g(f"s_min_i32 {sr(S_LEN)}, {sr(S_LEN)}, {sr(S_T0)}")
+        g(f"s_add_u32 {sr(S_T0)}, {sr(S_LEN)}, 63")
+        g(f"s_lshr_b32 {sr(S_T0)}, {sr(S_T0)}, 6")                      # nb
+        g(f"s_cmp_lt_u32 {sr(S_J)}, {sr(S_T0)}")
+        g(f"s_cbranch_scc1 {L('piece_take')}")
+        g(f"s_add_u32 {sr(S_B)}, {sr(S_B)}, 1")                         # sequence exhausted or empty: next one
+        g(f"s_mov_b32 {sr(S_J)}, 0")
+        g(f"s_branch {L('piece_begin')}")
+        g.label(L("piece_take"))
+        g(f"s_sub_u32 {sr(S_T1)}, {sr(S_T0)}, {sr(S_J)}")               # blocks the sequence still has
+        g(f"s_min_u32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_LEFT)}")            # take
+        g(f"s_mov_b32 {sr(S_J0)}, {sr(S_J)}")
+        g(f"s_add_u32 {sr(S_J1)}, {sr(S_J)}, {sr(S_T1)}")
+        g(f"s_sub_u32 {sr(S_LEFT)}, {sr(S_LEFT)}, {sr(S_T1)}")
+        g(f"s_mov_b32 {sr(S_J)}, {sr(S_J1)}")
+        g(f"s_cmp_eq_u32 {sr(S_J1)}, {sr(S_T0)}")
+        g(f"s_cselect_b32 {sr(S_FULL)}, 1, 0")
+        g(f"s_cmp_eq_u32 {sr(S_J0)}, 0")
+        g(f"s_cselect_b32 {sr(S_FULL)}, {sr(S_FULL)}, 0")
+        table_row_of_b()
+        # lane decomposition (v0 no longer holds the workitem id)
+        g(f"v_mbcnt_lo_u32_b32 v{T0}, -1, 0")
+        g(f"v_mbcnt_hi_u32_b32 v{T0}, -1, v{T0}")                    # lane
     g(f"s_lshl_b32 {sr(S_WAVELDS)}, {sr(S_WAVE)}, 10")
     g(f"s_mov_b32 {sr(S_ONES)}, 0x3f803f80")
     g(f"s_mov_b32 {sr(S_FIRST)}, 1")
@@ -291,7 +419,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     for i in range(256):
         g(f"v_accvgpr_write_b32 a{i}, 0")
 
-    # sub-tile range of this split
+    # sub-tile range of this split / piece
     g("s_waitcnt lgkmcnt(0)")
     g(f"s_max_i32 {sr(S_LEN)}, {sr(S_LEN)}, 0")                 # a length outside [0, 64 * max_blocks] must not
     g(f"s_lshl_b32 {sr(S_T0)}, {sr(S_MAXB)}, 6")                # reach past the sequence's block-table row
@@ -300,13 +428,17 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"s_lshr_b32 {sr(S_T0)}, {sr(S_T0)}, 6")                  # nb
     g(f"s_add_u32 {sr(S_T1)}, {sr(S_LEN)}, 31")
     g(f"s_lshr_b32 {sr(S_T1)}, {sr(S_T1)}, 5")                  # n32
-    g(f"s_mul_i32 {sr(S_T2)}, {sr(S_SPLIT)}, {sr(S_T0)}")       # x0 = split * nb
-    g(f"s_add_u32 {sr(S_T3)}, {sr(S_T2)}, {sr(S_T0)}")          # x1
-    g(f"s_mul_hi_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_MAGIC)}")    # j0
-    g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_T3)}, {sr(S_MAGIC)}")    # j1
-    g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
-    g(f"s_cselect_b32 {sr(S_T2)}, 0, {sr(S_T2)}")
-    g(f"s_cselect_b32 {sr(S_T3)}, {sr(S_T0)}, {sr(S_T3)}")
+    if not balanced:
+        g(f"s_mul_i32 {sr(S_T2)}, {sr(S_SPLIT)}, {sr(S_T0)}")       # x0 = split * nb
+        g(f"s_add_u32 {sr(S_T3)}, {sr(S_T2)}, {sr(S_T0)}")          # x1
+        g(f"s_mul_hi_u32 {sr(S_T2)}, {sr(S_T2)}, {sr(S_MAGIC)}")    # j0
+        g(f"s_mul_hi_u32 {sr(S_T3)}, {sr(S_T3)}, {sr(S_MAGIC)}")    # j1
+        g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
+        g(f"s_cselect_b32 {sr(S_T2)}, 0, {sr(S_T2)}")
+        g(f"s_cselect_b32 {sr(S_T3)}, {sr(S_T0)}, {sr(S_T3)}")
+    else:
+        g(f"s_mov_b32 {sr(S_T2)}, {sr(S_J0)}")
+        g(f"s_mov_b32 {sr(S_T3)}, {sr(S_J1)}")
     g(f"s_lshl_b32 {sr(S_U)}, {sr(S_T2)}, 1")                   # u0
     g(f"s_lshl_b32 {sr(S_UEND)}, {sr(S_T3)}, 1")
     g(f"s_min_u32 {sr(S_UEND)}, {sr(S_UEND)}, {sr(S_T1)}")
@@ -714,6 +846,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"s_branch {L('loop')}")
 
     # --------------------------------------------------------------------------------- epilogue
+    DONE = L('piece_done') if balanced else L('end')      # where a wave goes when it has nothing (more) to store
     g.label(L("epilogue"))
     g("s_waitcnt vmcnt(0) lgkmcnt(0)")
     if os.environ.get("AMLA_ASM_DEBUG") == "2":
@@ -757,10 +890,10 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
     g(f"v_add_u32 v{T0}, {sr(S_T1)}, v{T0}")                     # row
     g(f"v_cmp_gt_i32 vcc, {sr(S_ROWS)}, v{T0}")
     g(f"s_and_saveexec_b64 {sr(S_SAVE, 2)}, vcc")
-    g(f"s_cbranch_execz {L('end')}")
+    g(f"s_cbranch_execz {DONE}")
     g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_ROWS)}")
     g(f"v_add_u32 v{T0}, {sr(S_T2)}, v{T0}")                     # global row  b * rows + row
-    g(f"s_cmp_eq_u32 {sr(S_NS)}, 1")
+    g(f"s_cmp_eq_u32 {sr(S_FULL if balanced else S_NS)}, 1")     # whole sequence in one piece / no split: final form
     g(f"s_cbranch_scc0 {L('store_partial')}")
 
     # direct: bf16 out + lse
@@ -801,19 +934,23 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             g(f"v_cvt_pk_bf16_f32 v{t + 5}, v{t + 2}, v{t + 3}")
             g(f"global_store_dwordx2 {vr(V_L32, 2)}, {vr(t + 4, 2)}, off offset:{64 * dt + 16 * rg}")
     g(f"s_cmp_eq_u64 {sr(S_LSEP, 2)}, 0")
-    g(f"s_cbranch_scc1 {L('end')}")
+    g(f"s_cbranch_scc1 {DONE}")
     g(f"v_cmp_eq_u32 vcc, 0, v{V_KOFF}")                         # h == 0 writes the row's lse
     g(f"s_and_b64 exec, exec, vcc")
-    g(f"s_cbranch_execz {L('end')}")
+    g(f"s_cbranch_execz {DONE}")
     g(f"v_mov_b32 v{T4}, 4")
     g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_LSEP, 2)}")
     g(f"global_store_dword {vr(V_L32, 2)}, v{T3}, off")
-    g(f"s_branch {L('end')}")
+    g(f"s_branch {DONE}")
 
     # split: f32 partial out + partial lse at [(split * batch * rows) + global row]
     g.label(L("store_partial"))
-    g(f"s_mul_i32 {sr(S_T1)}, {sr(S_BATCH)}, {sr(S_ROWS)}")
-    g(f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_SPLIT)}")
+    if not balanced:
+        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_BATCH)}, {sr(S_ROWS)}")
+        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_T1)}, {sr(S_SPLIT)}")
+    else:
+        # slot worker + sequence: partial row (w + b) * rows + row = w * rows + global row
+        g(f"s_mul_i32 {sr(S_T1)}, {sr(S_STREAM)}, {sr(S_ROWS)}")
     g(f"v_add_u32 v{T0}, {sr(S_T1)}, v{T0}")
     g(f"v_mov_b32 v{T4}, 2048")
     g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_POP, 2)}")
@@ -830,11 +967,19 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool):
             g(f"global_store_dwordx4 {vr(V_L32, 2)}, {vr(t, 4)}, off offset:{128 * dt + 32 * rg}")
     g(f"v_cmp_eq_u32 vcc, 0, v{V_KOFF}")
     g(f"s_and_b64 exec, exec, vcc")
-    g(f"s_cbranch_execz {L('end')}")
+    g(f"s_cbranch_execz {DONE}")
     g(f"v_mov_b32 v{T4}, 4")
     g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_PLP, 2)}")
     g(f"global_store_dword {vr(V_L32, 2)}, v{T3}, off")
 
+    if balanced:
+        # the piece is done; the next one refills the LDS ring, which a slower wave may still be reading
+        g.label(L("piece_done"))
+        g("s_mov_b64 exec, -1")
+        g("s_waitcnt vmcnt(0) lgkmcnt(0)")
+        g("s_barrier")
+        g(f"s_cmp_lg_u32 {sr(S_LEFT)}, 0")
+        g(f"s_cbranch_scc1 {L('piece_begin')}")
     g.label(L("end"))
     g("s_endpgm")
     g.lines.append(f".Lfunc_end_{name}:\n\t.size {name}, .Lfunc_end_{name}-{name}")
@@ -895,8 +1040,10 @@ def metadata(names):
     return "\n".join(out)
 
 
-KERNELS = [("amla_decode_asm_mul", "mul", False), ("amla_decode_asm_add", "add", False),
-           ("amla_decode_asm_mul_lazy", "mul", True), ("amla_decode_asm_add_lazy", "add", True)]
+KERNELS = [("amla_decode_asm_mul", "mul", False, False), ("amla_decode_asm_add", "add", False, False),
+           ("amla_decode_asm_mul_lazy", "mul", True, False), ("amla_decode_asm_add_lazy", "add", True, False),
+           ("amla_decode_asm_mul_bal", "mul", False, True), ("amla_decode_asm_add_bal", "add", False, True),
+           ("amla_decode_asm_mul_lazy_bal", "mul", True, True), ("amla_decode_asm_add_lazy_bal", "add", True, True)]
 
 
 def main():
@@ -904,8 +1051,8 @@ def main():
     g = Gen()
     g.lines.append('\t.amdgcn_target "amdgcn-amd-amdhsa--gfx950"')
     g.lines.append("\t.text")
-    for name, rescale, lazy in KERNELS:
-        kernel(g, name, rescale, lazy)
+    for name, rescale, lazy, balanced in KERNELS:
+        kernel(g, name, rescale, lazy, balanced)
     if os.environ.get("AMLA_ASM_SAFE") == "1":
         # Diagnostic build: every wait is a full drain and every instruction is followed by idle
         # issue slots, so that a wrong result that disappears here points at a timing hazard.

@@ -382,7 +382,10 @@ class Wave:
 
         # ---------------- SALU
         if mnem in ("s_mov_b32", "s_mov_b64"):
-            self.sdst(ops[0], S(ops[1]))
+            val = S(ops[1])
+            if mnem == "s_mov_b64" and re.fullmatch(r"-\d+", ops[1]):
+                val = int(ops[1]) & ((1 << 64) - 1)          # a negative inline constant is sign-extended to 64 bits
+            self.sdst(ops[0], val)
             return nxt
         if mnem in ("s_and_b32", "s_or_b32", "s_andn2_b32", "s_and_b64", "s_or_b64"):
             a, b = S(ops[1]), S(ops[2])

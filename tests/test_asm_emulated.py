@@ -27,11 +27,15 @@ def asm_text(tmp_path_factory):
     return out.read_text()
 
 
-def run_case(asm_text, kernel, case, n_splits, flags=0, dma_late=False, smem_first=False):
+def run_case(asm_text, kernel, case, n_splits, flags=0, dma_late=False, smem_first=False, workers=0):
+    """`workers` > 0 runs a balanced kernel (name ending in _bal) with that many workers; `n_splits` is
+    then ignored."""
     ins, labels = emu.parse_kernel(asm_text, kernel)
     B, T, H = case.batch, case.s_q, case.heads
     rows = T * H
     n_rows = B * rows
+    if workers:
+        return run_balanced(ins, labels, case, workers, flags, dma_late, smem_first)
     mem = emu.Memory()
     q = mem.add("q", case.q_bits)
     kv = mem.add("kv", case.kv_bits)
@@ -77,6 +81,62 @@ def run_case(asm_text, kernel, case, n_splits, flags=0, dma_late=False, smem_fir
     return o, l, steps
 
 
+def run_balanced(ins, labels, case, workers, flags, dma_late, smem_first):
+    from paper_2509_25224_amd import amla
+    B, T, H = case.batch, case.s_q, case.heads
+    rows = T * H
+    n_rows = B * rows
+    slots = workers + B - 1
+    mem = emu.Memory()
+    q = mem.add("q", case.q_bits)
+    kv = mem.add("kv", case.kv_bits)
+    tab = mem.add("table", case.block_table)
+    lens = mem.add("seqlens", case.seqlens)
+    out = mem.add("out", np.full(n_rows * 512, 0x7F7F, np.uint16), writable=True)
+    lse = mem.add("lse", np.full(n_rows, np.nan, np.float32), writable=True)
+    po = mem.add("part_o", np.full(slots * rows * 512, np.nan, np.float32), writable=True)
+    pl = mem.add("part_lse", np.full(slots * rows, np.nan, np.float32), writable=True)
+    scale_log2e = np.float32(case.softmax_scale) * np.float32(1.4426950408889634)
+    wmagic = ((1 << 32) // workers + 1) & 0xFFFFFFFF
+    karg = struct.pack("<8Q", q, kv, tab, lens, out, lse, po, pl) + struct.pack(
+        "<f6iIiiiI", float(scale_log2e), B, rows, 1, case.max_blocks_per_seq, workers, flags, 0,
+        case.num_blocks, 0, workers, wmagic)
+    assert len(karg) == 0x70
+    ka = mem.add("kernarg", np.frombuffer(karg, dtype=np.uint8))
+    n_tiles = (rows + 127) // 128
+    gy = (workers + 7) // 8
+    steps = 0
+    for y in range(gy):
+        for x in range(8 * n_tiles):
+            if y * 8 + (x & 7) >= workers and (x, y) != (8 * n_tiles - 1, gy - 1):
+                continue
+            wg = emu.Workgroup(ins, labels, mem, ka, x, y, LDS_BYTES, dma_late=dma_late, smem_first=smem_first)
+            steps += wg.run()
+    o = mem.get("out").view(np.uint16).astype(np.uint32)
+    o = (o << 16).view(np.float32).astype(np.float64).reshape(B, rows, 512)
+    l = mem.get("lse").view(np.float32).astype(np.float64).reshape(B, rows)
+    P = mem.get("part_o").view(np.float32).astype(np.float64).reshape(slots, rows, 512)
+    PL = mem.get("part_lse").view(np.float32).astype(np.float64).reshape(slots, rows)
+    # what the combine kernel does, from the same plan
+    lens_c = np.clip(case.seqlens, 0, 64 * case.max_blocks_per_seq)
+    pieces, _ = amla.amla_plan_segments(lens_c, workers)
+    for b in range(B):
+        mine = [p for p in pieces if p[1] == b]
+        if not mine:
+            o[b], l[b] = 0.0, -np.inf
+        elif len(mine) > 1:
+            pls = np.stack([PL[p[4]] for p in mine])
+            mx = pls.max(axis=0)
+            with np.errstate(invalid="ignore"):
+                w = np.where(np.isneginf(pls), 0.0, np.exp(pls - np.where(np.isneginf(mx), 0.0, mx)))
+            tot = w.sum(axis=0)
+            acc = sum(w[i][:, None] * np.nan_to_num(P[p[4]]) for i, p in enumerate(mine))
+            with np.errstate(invalid="ignore", divide="ignore"):
+                o[b] = np.where(tot[:, None] > 0, acc / tot[:, None], 0.0)
+                l[b] = np.where(tot > 0, mx + np.log(tot), -np.inf)
+    return o.reshape(B, T, H, 512), l.reshape(B, T, H), steps
+
+
 def check(o, l, case, bf16_out=True):
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
     fin = np.isfinite(want_lse)
@@ -89,6 +149,18 @@ def check(o, l, case, bf16_out=True):
 
 
 KERNELS = ["amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_mul_lazy", "amla_decode_asm_add_lazy"]
+
+
+def test_generated_assembly_assembles(asm_text, tmp_path):
+    """The emulator parses text; the assembler also checks what the text cannot say on this target
+    (register-pair alignment, operand kinds, literal counts)."""
+    clang = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang")
+    if not os.path.exists(clang):
+        pytest.skip("no assembler")
+    src = tmp_path / "k.s"
+    src.write_text(asm_text)
+    subprocess.run([clang, "-x", "assembler", "-target", "amdgcn-amd-amdhsa", "-mcpu=gfx950", "-c", str(src), "-o",
+                    str(tmp_path / "k.o")], check=True)
 
 
 def test_hazard_rules_hold(asm_text):
@@ -225,3 +297,15 @@ def test_bad_table_entries_and_lengths_stay_inside_the_buffers(asm_text):
     for kernel in ("amla_decode_asm_add", "amla_decode_asm_mul_lazy"):
         o, l, _ = run_case(asm_text, kernel, case, 1)
         assert np.all(np.isfinite(o[0]))          # clamped entries point at real blocks
+
+
+@pytest.mark.parametrize("kernel,workers", [("amla_decode_asm_add_bal", 1), ("amla_decode_asm_mul_bal", 3),
+                                            ("amla_decode_asm_add_lazy_bal", 8), ("amla_decode_asm_mul_lazy_bal", 20)])
+def test_balanced_walk_on_the_emulator(asm_text, kernel, workers):
+    """Worker ranges that start mid-sequence, cross several sequences (with an empty one between) and, with
+    20 workers for 12 blocks, are partly empty; pieces written in final form and as partial rows; loads
+    that land late, so that a ring refilled too early for the next piece would show."""
+    case = wl.make_case("bal", 37, batch=5, s_q=1, heads=4, seqlens=[70, 0, 1, 200, 300], spare_frac=0.5, q_sigma=2.0)
+    o, l, _ = run_case(asm_text, kernel, case, 1, dma_late=True, workers=workers)
+    check(o, l, case)
+    assert np.all(o[1] == 0)

@@ -17,8 +17,13 @@ pytestmark = [pytest.mark.gpu,
 BALANCED = 8
 CAUSAL = 16
 COMP = 2
+ASM = 4
+asm_off = pytest.mark.skipif(os.environ.get("AMLA_ENABLE_ASM_KERNELS") != "1",
+                             reason="assembly kernels switched off: not yet run on hardware since the hazard fix")
 KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((ADD, LAZY), id="add_lazy"),
-         pytest.param((COMP, 0), id="add_comp")]
+         pytest.param((COMP, 0), id="add_comp"),
+         pytest.param((MUL, ASM), id="mul_asm", marks=asm_off), pytest.param((ADD, ASM | LAZY), id="add_lazy_asm", marks=asm_off)]
+NO_ASM = [k for k in KINDS if not (k.values[0][1] & ASM)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -73,7 +78,7 @@ def test_full_size_ragged_config_balanced(env):
     assert worst[1] <= LSE_TOL
 
 
-@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("kind", NO_ASM)
 @pytest.mark.parametrize("workers", [0, 3, 11])
 def test_causal_mask_among_the_query_tokens(env, kind, workers):
     """s_q = 4 under AMLA_FLAG_CAUSAL: tokens without any key (kv_len 1), limits at and just past block
