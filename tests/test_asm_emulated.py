@@ -309,3 +309,19 @@ def test_balanced_walk_on_the_emulator(asm_text, kernel, workers):
     o, l, _ = run_case(asm_text, kernel, case, 1, dma_late=True, workers=workers)
     check(o, l, case)
     assert np.all(o[1] == 0)
+
+
+@pytest.mark.parametrize("kernel", ["amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_add_lazy"])
+def test_extreme_inputs_on_the_emulator(asm_text, kernel):
+    """Logits hundreds of base-2 units apart (the -30 clamp, underflow of the multiply, saturation of the
+    guarded add) and an all-zero cache (out = 0 exactly, lse = ln L)."""
+    steep = wl.make_case("steep", 38, batch=1, s_q=1, heads=4, seqlens=[150], q_sigma=30.0)
+    want, want_lse = orc.decode(steep.q_bits, steep.kv_bits, steep.block_table, steep.seqlens, steep.softmax_scale)
+    o, l, _ = run_case(asm_text, kernel, steep, 1)
+    half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 2.0 ** -20))) - 9)
+    assert np.all(np.abs(o - want) <= half_ulp + 6e-3)
+    assert np.abs(l - want_lse).max() <= 1e-3
+    flat = wl.make_case("flat", 39, batch=1, s_q=1, heads=4, seqlens=[100])
+    flat.kv_bits[...] = 0
+    o, l, _ = run_case(asm_text, kernel, flat, 1)
+    assert np.all(o == 0) and np.abs(l - np.log(100.0)).max() < 1e-5

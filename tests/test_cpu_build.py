@@ -233,3 +233,22 @@ def test_thread_sanitizer_sees_no_race_between_waves(tmp_path):
     for flags, ns in ((BALANCED, 3), (0, 2)):
         out, lse, _ = run_cpu(exe, tmp_path, case, ADD, flags=flags, ns=ns)      # a report makes the exit code non-zero
         check(out, lse, case)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_extreme_inputs(exe, tmp_path, kind):
+    """Logits hundreds of base-2 units apart (rescale factors far below 2^-30: the clamp, underflow of the
+    multiply, saturation of the guarded add), an all-zero cache (every weight equal, out = 0, lse = ln L,
+    zeros that must stay zeros under the exponent add) and a zero query."""
+    steep = wl.make_case("steep", 59, batch=1, s_q=1, heads=8, seqlens=[300], q_sigma=30.0)
+    out, lse, _ = run_cpu(exe, tmp_path, steep, kind[0], flags=kind[1])
+    check(out, lse, steep, peaked=True)
+    flat = wl.make_case("flat", 60, batch=2, s_q=1, heads=8, seqlens=[130, 64])
+    flat.kv_bits[...] = 0
+    out, lse, _ = run_cpu(exe, tmp_path, flat, kind[0], flags=kind[1])
+    assert np.all(out == 0)
+    assert np.abs(lse - np.log(np.array([130.0, 64.0]))[:, None, None]).max() < 1e-5
+    zero_q = wl.make_case("zero_q", 61, batch=1, s_q=1, heads=8, seqlens=[200])
+    zero_q.q_bits[...] = 0
+    out, lse, _ = run_cpu(exe, tmp_path, zero_q, kind[0], flags=kind[1])
+    check(out, lse, zero_q)
