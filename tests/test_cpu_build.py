@@ -252,3 +252,35 @@ def test_extreme_inputs(exe, tmp_path, kind):
     zero_q.q_bits[...] = 0
     out, lse, _ = run_cpu(exe, tmp_path, zero_q, kind[0], flags=kind[1])
     check(out, lse, zero_q)
+
+
+def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
+    """A copy of the source with the barrier at the start of a piece taken out (a wave may then refill
+    an LDS buffer that a slower wave still reads from the previous piece): the strict direct-to-LDS
+    semantics turn that into wrong results, ThreadSanitizer into a reported race.  Planted in a copy,
+    on the CPU."""
+    import shutil
+    if not os.path.exists(CLANG):
+        pytest.skip("no clang++ to build the CPU harness with")
+    csrc = tmp_path / "paper_2509_25224_amd" / "csrc"
+    csrc.mkdir(parents=True)
+    for name in ("amla_decode.hip", "amla_decode_kernels.inc", "amla_decode_piece.inc", "amla_plan.h"):
+        shutil.copy(os.path.join(ROOT, "paper_2509_25224_amd", "csrc", name), csrc / name)
+    piece = (csrc / "amla_decode_piece.inc").read_text()
+    barrier = "  // the previous piece's last tile may still be read by a slower wave\n  __syncthreads();\n"
+    assert barrier in piece
+    (csrc / "amla_decode_piece.inc").write_text(piece.replace(barrier, ""))
+    shim = tmp_path / "tests" / "cpu_build"
+    shutil.copytree(os.path.join(SHIM, "hip"), shim / "hip")
+    shutil.copy(os.path.join(SHIM, "decode_cpu.cpp"), shim / "decode_cpu.cpp")
+    (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
+    case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
+    for sanitizer in ("address", "thread"):
+        exe = str(tmp_path / ("decode_" + sanitizer))
+        subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=" + sanitizer, "-pthread",
+                        "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi", "-I" + str(shim),
+                        "-I" + os.path.join(ROOT, "include"), "-I" + str(tmp_path), str(shim / "decode_cpu.cpp"),
+                        "-o", exe], check=True)
+        with pytest.raises(AssertionError):
+            out, lse, _ = run_cpu(exe, tmp_path, case, ADD, flags=BALANCED, ns=2)
+            check(out, lse, case)
