@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
     ap.add_argument("--balanced", action="store_true",
                     help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
@@ -182,8 +182,8 @@ def main():
             del o2, l2
             quick = {}
             for name in passed * 2:
-                t, _ = time_steps(torch, lambda: step(name), 5, 2)
-                quick[name] = min(quick.get(name, float("inf")), t / 5)
+                t, _ = time_steps(torch, lambda: step(name), 20, 3)
+                quick[name] = min(quick.get(name, float("inf")), t / 20)
             chosen = min(quick, key=quick.get)
             self_check["quick_ms"] = quick
         except Exception as e:  # noqa: BLE001  (fall back to the variant every GPU test covers)
