@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--balanced", action="store_true",
                     help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
                          "means workers)")
-    ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy", "add_comp"], default="auto",
+    ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy", "add_comp", "add_ldexp", "add_ldexp_lazy"], default="auto",
                     help="auto = the fastest exponent-add variant whose output agrees with the strict add variant on this input")
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
                     help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
@@ -143,7 +143,9 @@ def main():
     VARIANTS = {"mul": (amla.AMLA_RESCALE_MUL, 0), "add": (amla.AMLA_RESCALE_ADD, 0),
                 "mul_lazy": (amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE),
                 "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE),
-                "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0)}
+                "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0),
+                "add_ldexp": (amla.AMLA_RESCALE_ADD_LDEXP, 0),
+                "add_ldexp_lazy": (amla.AMLA_RESCALE_ADD_LDEXP, amla.AMLA_FLAG_LAZY_RESCALE)}
 
     def step(name, o=out, l=lse):
         v, f = VARIANTS[name]
@@ -165,7 +167,9 @@ def main():
             step("add")
             torch.cuda.synchronize()
             passed = ["add"]
-            for name in ("add_lazy", "add_comp") if args.impl == "compiler" else ("add_lazy",):
+            others = ("add_lazy", "add_comp", "add_ldexp", "add_ldexp_lazy") if args.impl == "compiler" and not args.balanced \
+                else ("add_lazy", "add_comp") if args.impl == "compiler" else ("add_lazy",)
+            for name in others:
                 try:
                     step(name, o2, l2)
                     torch.cuda.synchronize()
@@ -224,7 +228,8 @@ def main():
     if not args.no_ab:
         try:
             ab = {}
-            names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ())
+            names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
+                (("add_ldexp", "add_ldexp_lazy") if args.impl == "compiler" and not args.balanced else ())
             for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)
@@ -236,7 +241,8 @@ def main():
                                  "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in best.items()},
                                  "note": "interleaved runs, best of 2 per variant, same binary; strict = "
                                          "reference moves with every new row max, lazy = only past 2^8, "
-                                         "add_comp = Algorithm 2 with its BF16 scale compensation"}
+                                         "add_comp = Algorithm 2 with its BF16 scale compensation, add_ldexp = the exponent add "
+                                         "done by v_ldexp_f32"}
         except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
             notes.append(f"rescale side-by-side failed: {e!r}")
 

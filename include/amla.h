@@ -20,6 +20,11 @@
  *                     (Eq. (4), Lemma 3.1, Algorithm 2's n_i, N and AtomicAdd<INT32>), the INT32 add
  *                     guarded so that an exponent that would drop to or below zero yields
  *                     a signed zero instead of a wrapped bit pattern.
+ *   AMLA_RESCALE_ADD_LDEXP  the ADD variant with the exponent add done by the FP32 ldexp
+ *                     instruction (v_ldexp_f32) instead of an INT32 add on the bit pattern: the
+ *                     same product x * 2^n wherever Lemma 3.1 applies, one instruction per
+ *                     register instead of three, and zeros, signs and underflow handled by the
+ *                     instruction itself.
  *   AMLA_RESCALE_ADD_COMP  the ADD variant with the BF16 scale compensation of Algorithm 2
  *                     (S32, S16, c_i, eps) and Appendix A: the weights are 2^(t - m) * S16 with S16 the
  *                     BF16 rounding of S32 = 2^(m - rint(m)), so the largest weight of a row is
@@ -51,7 +56,7 @@ enum {
   AMLA_ERR_LAUNCH = -4        /* the HIP runtime refused a launch */
 };
 
-enum { AMLA_RESCALE_MUL = 0, AMLA_RESCALE_ADD = 1, AMLA_RESCALE_ADD_COMP = 2 };
+enum { AMLA_RESCALE_MUL = 0, AMLA_RESCALE_ADD = 1, AMLA_RESCALE_ADD_COMP = 2, AMLA_RESCALE_ADD_LDEXP = 3 };
 
 /* desc->flags */
 enum {
@@ -103,7 +108,7 @@ typedef struct amla_desc {
   int32_t block_size;          /* keys per cache block, must be 64 */
   int32_t num_blocks;          /* physical blocks in kv_cache */
   int32_t max_blocks_per_seq;  /* row stride of block_table */
-  int32_t variant;             /* AMLA_RESCALE_MUL, AMLA_RESCALE_ADD or AMLA_RESCALE_ADD_COMP */
+  int32_t variant;             /* one of AMLA_RESCALE_* */
   int32_t num_splits;          /* split-KV factor: each sequence's blocks are cut into this many
                                   contiguous ranges processed by separate workgroups and merged
                                   by a combine kernel.  0 = library chooses from the shape; at

@@ -19,6 +19,7 @@ AMLA_ERR_LAUNCH = -4
 AMLA_RESCALE_MUL = 0
 AMLA_RESCALE_ADD = 1
 AMLA_RESCALE_ADD_COMP = 2
+AMLA_RESCALE_ADD_LDEXP = 3
 AMLA_FLAG_NO_SKIP = 1
 AMLA_FLAG_LAZY_RESCALE = 2
 AMLA_FLAG_ASM_KERNEL = 4

@@ -122,8 +122,12 @@ bool desc_supported(const amla_desc* d) {
   if (d == nullptr) return false;
   if (d->d_qk != kDqk || d->d_v != kDv || d->block_size != kBlock) return false;
   if (d->batch < 1 || d->s_q < 1 || d->num_heads < 1 || d->num_blocks < 1 || d->max_blocks_per_seq < 1) return false;
-  if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD && d->variant != AMLA_RESCALE_ADD_COMP)
+  if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD && d->variant != AMLA_RESCALE_ADD_COMP &&
+      d->variant != AMLA_RESCALE_ADD_LDEXP)
     return false;
+  // ldexp rescale: equal-share compiler-built kernels only (this compiler's AGPR-copy rewrite pass crashes on
+  // the balanced instantiation)
+  if (d->variant == AMLA_RESCALE_ADD_LDEXP && ((d->flags & AMLA_FLAG_ASM_KERNEL) || uses_balanced(d))) return false;
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
@@ -232,15 +236,17 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     void (*kern)(const DecodeParams) = nullptr;
     if (!balanced) {
       kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
+             : desc->variant == AMLA_RESCALE_ADD_LDEXP
+                 ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
              : desc->variant == AMLA_RESCALE_ADD
                  ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
                  : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
     } else {
       kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
-             : desc->variant == AMLA_RESCALE_ADD ? (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD, true>
-                                                         : amla_decode_balanced_kernel<AMLA_RESCALE_ADD, false>)
-                                                 : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
-                                                         : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
+             : desc->variant == AMLA_RESCALE_ADD     ? (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD, true>
+                                                               : amla_decode_balanced_kernel<AMLA_RESCALE_ADD, false>)
+                                                     : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
+                                                             : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
     }
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kLdsBytes) != hipSuccess) {

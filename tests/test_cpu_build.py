@@ -18,7 +18,7 @@ from paper_2509_25224_amd import workloads as wl
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SHIM = os.path.join(ROOT, "tests", "cpu_build")
 CLANG = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang++")
-MUL, ADD, COMP = 0, 1, 2
+MUL, ADD, COMP, LDEXP = 0, 1, 2, 3
 NO_SKIP, LAZY, ASM, BALANCED, CAUSAL = 1, 2, 4, 8, 16
 FLAGS = ["-std=c++20", "-O0", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
          "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi"]
@@ -84,7 +84,8 @@ def check(out, lse, case, peaked=False, causal=False):
 
 KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"),
          pytest.param((MUL, LAZY), id="mul_lazy"), pytest.param((ADD, LAZY), id="add_lazy"),
-         pytest.param((COMP, 0), id="add_comp")]
+         pytest.param((COMP, 0), id="add_comp"), pytest.param((LDEXP, 0), id="add_ldexp"),
+         pytest.param((LDEXP, LAZY), id="add_ldexp_lazy")]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -101,7 +102,7 @@ def _ragged(seed, heads=80):
     return wl.make_case("edges", seed, batch=7, s_q=2, heads=heads, seqlens=[1, 63, 0, 64, 65, 200, 330], spare_frac=0.25)
 
 
-@pytest.mark.parametrize("kind,ns", [((MUL, 0), 1), ((ADD, 0), 3), ((ADD, LAZY), 0)])
+@pytest.mark.parametrize("kind,ns", [((MUL, 0), 1), ((ADD, 0), 3), ((ADD, LAZY), 0), ((LDEXP, 0), 2)])
 def test_ragged_equal_share_splits(exe, tmp_path, kind, ns):
     case = _ragged(51)
     out, lse, splits = run_cpu(exe, tmp_path, case, kind[0], flags=kind[1], ns=ns)
@@ -125,7 +126,7 @@ def test_ragged_balanced_decomposition(exe, tmp_path, kind, workers):
 
 
 @pytest.mark.parametrize("kind", [pytest.param((ADD, LAZY), id="add_lazy"), pytest.param((MUL, LAZY), id="mul_lazy"),
-                                  pytest.param((COMP, 0), id="add_comp")])
+                                  pytest.param((COMP, 0), id="add_comp"), pytest.param((LDEXP, 0), id="add_ldexp")])
 def test_wide_logits_move_the_reference(exe, tmp_path, kind):
     """Logit spread of tens of base-2 units over 11 blocks: the lazy kernels take the deferred update
     several times, the compensated one rescales with mantissa terms of both signs."""
@@ -172,6 +173,7 @@ def test_entry_point_rejects_what_it_documents(exe, tmp_path):
     run_cpu(exe, tmp_path, case, 7, expect_status=-2)
     run_cpu(exe, tmp_path, case, ADD, flags=ASM, expect_status=-2)            # gate closed
     run_cpu(exe, tmp_path, case, ADD, flags=ASM | BALANCED, expect_status=-2)
+    run_cpu(exe, tmp_path, case, LDEXP, flags=BALANCED, expect_status=-2)     # equal-share kernels only
 
 
 def test_random_shapes_lengths_and_decompositions(exe, tmp_path):

@@ -84,3 +84,46 @@ def test_full_size_headline_comp(env):
         worst[1] = max(worst[1], float(np.abs(lse[b] - want_lse[b]).max()))
     print(f"config 2 comp: max|out err| {worst[0]:.3e} max|lse err| {worst[1]:.3e}", flush=True)
     assert worst[1] <= LSE_TOL
+
+
+# ---- the ADD variant with the exponent add done by v_ldexp_f32 (AMLA_RESCALE_ADD_LDEXP) ----------------
+LDEXP = 3
+LAZY_FLAG = 2
+
+
+@pytest.mark.parametrize("flags", [0, LAZY_FLAG])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_ldexp_variant_small_cases(env, flags, splits):
+    torch, orc, amla, wl = env
+    assert amla.AMLA_RESCALE_ADD_LDEXP == LDEXP
+    case = wl.make_case("edges", 35, batch=6, s_q=2, heads=80, seqlens=[1, 63, 64, 65, 300, 1000], spare_frac=0.25)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=LDEXP, flags=flags, num_splits=splits)
+    check(out, lse, want, want_lse, f"edges ldexp flags={flags} splits={splits}")
+
+
+def test_ldexp_variant_headline_shape(env):
+    torch, orc, amla, wl = env
+    case = wl.make_config(2)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=LDEXP)
+    worst = [0.0, 0.0]
+    for b in range(0, case.batch, 8):
+        want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens,
+                                    case.softmax_scale, seq_ids=[b])
+        assert np.all(np.abs(out[b] - want[b]) <= out_tolerance(want[b])), b
+        worst[0] = max(worst[0], float(np.abs(out[b] - want[b]).max()))
+        worst[1] = max(worst[1], float(np.abs(lse[b] - want_lse[b]).max()))
+    print(f"config 2 ldexp: max|out err| {worst[0]:.3e} max|lse err| {worst[1]:.3e}", flush=True)
+    assert worst[1] <= LSE_TOL
+
+
+def test_ldexp_variant_equals_the_integer_add(env):
+    """Inside Lemma 3.1's range the two forms of the exponent add are the same operation: same reference,
+    same weights, same products, so the strict ADD and ADD_LDEXP outputs agree bit for bit on inputs whose
+    accumulators stay normal (N(0,1) data; kv 4096)."""
+    torch, orc, amla, wl = env
+    case = wl.make_case("same", 36, batch=2, s_q=1, heads=128, seqlens=[4096, 4096])
+    dev = to_dev(torch, case)
+    a, la = run_gpu(torch, amla, case, dev, variant=ADD)
+    b, lb = run_gpu(torch, amla, case, dev, variant=LDEXP)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
