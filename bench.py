@@ -167,8 +167,13 @@ def main():
             step("add")
             torch.cuda.synchronize()
             passed = ["add"]
-            others = ("add_lazy", "add_comp", "add_ldexp", "add_ldexp_lazy") if args.impl == "compiler" and not args.balanced \
-                else ("add_lazy", "add_comp") if args.impl == "compiler" else ("add_lazy",)
+            # what each build of the kernels offers: the compensated form only compiler-built, the ldexp
+            # form compiler-built without the balanced decomposition and hand-scheduled with or without it
+            others = ["add_lazy"]
+            if args.impl == "compiler":
+                others.append("add_comp")
+            if args.impl == "asm" or not args.balanced:
+                others += ["add_ldexp", "add_ldexp_lazy"]
             for name in others:
                 try:
                     step(name, o2, l2)
@@ -229,7 +234,7 @@ def main():
         try:
             ab = {}
             names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
-                (("add_ldexp", "add_ldexp_lazy") if args.impl == "compiler" and not args.balanced else ())
+                (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ())
             for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)

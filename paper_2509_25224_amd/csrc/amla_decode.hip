@@ -45,11 +45,12 @@ const unsigned char kDecodeCodeObject[] = {
 };
 
 constexpr int kMaxDevices = 64;
-constexpr int kAsmKernels = 8;   // index = variant + 2 * lazy + 4 * balanced
-const char* const kAsmNames[kAsmKernels] = {"amla_decode_asm_mul",          "amla_decode_asm_add",
-                                            "amla_decode_asm_mul_lazy",     "amla_decode_asm_add_lazy",
-                                            "amla_decode_asm_mul_bal",      "amla_decode_asm_add_bal",
-                                            "amla_decode_asm_mul_lazy_bal", "amla_decode_asm_add_lazy_bal"};
+constexpr int kAsmKernels = 12;   // index = kind (mul, add, ldexp) + 3 * lazy + 6 * balanced
+const char* const kAsmNames[kAsmKernels] = {
+    "amla_decode_asm_mul",          "amla_decode_asm_add",          "amla_decode_asm_ldexp",
+    "amla_decode_asm_mul_lazy",     "amla_decode_asm_add_lazy",     "amla_decode_asm_ldexp_lazy",
+    "amla_decode_asm_mul_bal",      "amla_decode_asm_add_bal",      "amla_decode_asm_ldexp_bal",
+    "amla_decode_asm_mul_lazy_bal", "amla_decode_asm_add_lazy_bal", "amla_decode_asm_ldexp_lazy_bal"};
 struct DeviceKernels {
   bool tried = false;
   bool ok = false;
@@ -125,9 +126,9 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD && d->variant != AMLA_RESCALE_ADD_COMP &&
       d->variant != AMLA_RESCALE_ADD_LDEXP)
     return false;
-  // ldexp rescale: equal-share compiler-built kernels only (this compiler's AGPR-copy rewrite pass crashes on
-  // the balanced instantiation)
-  if (d->variant == AMLA_RESCALE_ADD_LDEXP && ((d->flags & AMLA_FLAG_ASM_KERNEL) || uses_balanced(d))) return false;
+  // ldexp rescale with the balanced decomposition: hand-scheduled kernels only (this compiler's AGPR-copy
+  // rewrite pass crashes on the balanced compiler-built instantiation)
+  if (d->variant == AMLA_RESCALE_ADD_LDEXP && uses_balanced(d) && !(d->flags & AMLA_FLAG_ASM_KERNEL)) return false;
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
@@ -295,8 +296,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     }
     size_t arg_size = sizeof(a);
     void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &a, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
-    const int which = (desc->variant == AMLA_RESCALE_ADD ? 1 : 0) + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 2 : 0) +
-                      (balanced ? 4 : 0);
+    const int kind = desc->variant == AMLA_RESCALE_ADD ? 1 : desc->variant == AMLA_RESCALE_ADD_LDEXP ? 2 : 0;
+    const int which = kind + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 3 : 0) + (balanced ? 6 : 0);
     if (hipModuleLaunchKernel(dk->fn[which], (unsigned)(8 * p.n_tiles), (unsigned)(streams_pad / 8), 1, kThreads, 1, 1,
                               0, stream, nullptr, config) != hipSuccess) {
       (void)hipGetLastError();

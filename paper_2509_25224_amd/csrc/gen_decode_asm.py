@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Generator of the hand-scheduled gfx950 decode kernels (CDNA4 assembly).
 
-Writes one assembly file holding four kernels, `amla_decode_asm_{mul,add}{,_lazy}`, that the
-build assembles into a code object and embeds into libamla.so.  All four run the same loop
+Writes one assembly file holding twelve kernels, `amla_decode_asm_{mul,add,ldexp}{,_lazy}{,_bal}`, that
+the build assembles into a code object and embeds into libamla.so.  All run the same loop
 (Algorithm 1 / Algorithm 2 of the AMLA paper per 32-key sub-tile of a 64-key cache block);
 they differ only in how the reference of the exponent is moved and how the accumulator is
 rescaled:
@@ -11,6 +11,9 @@ rescaled:
   add        reference = rint(running row max), an integer power of two; O's bit patterns get
              (n_new - n_old) << 23 added as INT32, guarded against exponent underflow
              (Eq. (4), Lemma 3.1, Algorithm 2's n_i, N and AtomicAdd<INT32> steps)
+  ldexp      the add variant with the exponent add done by v_ldexp_f32 (one instruction per register)
+  *_bal      balanced decomposition: the workgroup is a worker that walks its share of the batch's
+             concatenated block list, one pass through the pipeline per (worker, sequence) piece
   *_lazy     the reference is moved only when the row max exceeds it by more than 2^8; until
              then the softmax weights are allowed to grow up to 2^8 (same relative precision in
              bf16 / FP32), which makes the rescale of the 32 x 512 accumulator a rare event.
@@ -603,7 +606,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
         v.append(f"v_max_f32 v{T0}, v{V_M}, v{T0}")                      # m_new
         v.append(f"v_mov_b32 v{V_M}, v{T0}")
         # candidate reference
-        if rescale == "add":
+        if rescale in ("add", "ldexp"):
             v.append(f"v_rndne_f32 v{T1}, v{T0}")
         else:
             v.append(f"v_mov_b32 v{T1}, v{T0}")
@@ -619,8 +622,11 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
         else:
             v.append(f"v_sub_f32 v{T4}, v{V_REF}, v{T1}")                # <= 0, integer valued (or -inf)
             v.append(f"v_max_f32 v{T4}, 0xc1f00000, v{T4}")             # clamp at -30 (Algorithm 2's max(n_i - n_{i-1}, -30))
-            v.append(f"v_cvt_i32_f32 v{T4}, v{T4}")
-            v.append(f"v_lshlrev_b32 v{V_FAC}, 23, v{T4}")
+            if rescale == "add":
+                v.append(f"v_cvt_i32_f32 v{T4}, v{T4}")
+                v.append(f"v_lshlrev_b32 v{V_FAC}, 23, v{T4}")              # n * 2^23 for the integer add
+            else:
+                v.append(f"v_cvt_i32_f32 v{V_FAC}, v{T4}")                  # n itself for v_ldexp_f32
             v.append(f"v_cmp_ne_u32 {sr(S_NEED, 2)}, 0, v{V_FAC}")
         v.append(f"v_mov_b32 v{V_REF}, v{T1}")
         # weights 2^(s * c - ref), their FP32 sum, the bf16 pack and the sum of the rounded weights.
@@ -649,6 +655,10 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
         if rescale == "mul":
             v.append(f"v_fma_f32 v{V_L32}, v{V_L32}, v{V_FAC}, v{T2}")
             v.append(f"v_fma_f32 v{V_L16}, v{V_L16}, v{V_FAC}, v{T3}")
+        elif rescale == "ldexp":
+            for reg, add in ((V_L32, T2), (V_L16, T3)):
+                v.append(f"v_ldexp_f32 v{reg}, v{reg}, v{V_FAC}")
+                v.append(f"v_add_f32 v{reg}, v{reg}, v{add}")
         else:
             for reg, add in ((V_L32, T2), (V_L16, T3)):
                 v.append(f"v_and_b32 v{T4}, 0x80000000, v{reg}")
@@ -708,6 +718,9 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
             if rescale == "mul":
                 for r in range(8):
                     g(f"v_mul_f32 v{SC + r}, v{SC + r}, v{V_FAC}")
+            elif rescale == "ldexp":
+                for r in range(8):
+                    g(f"v_ldexp_f32 v{SC + r}, v{SC + r}, v{V_FAC}")
             else:
                 for r in range(8):
                     g(f"v_and_b32 v{SC + 8 + r}, 0x80000000, v{SC + r}")
@@ -1040,10 +1053,8 @@ def metadata(names):
     return "\n".join(out)
 
 
-KERNELS = [("amla_decode_asm_mul", "mul", False, False), ("amla_decode_asm_add", "add", False, False),
-           ("amla_decode_asm_mul_lazy", "mul", True, False), ("amla_decode_asm_add_lazy", "add", True, False),
-           ("amla_decode_asm_mul_bal", "mul", False, True), ("amla_decode_asm_add_bal", "add", False, True),
-           ("amla_decode_asm_mul_lazy_bal", "mul", True, True), ("amla_decode_asm_add_lazy_bal", "add", True, True)]
+KERNELS = [(f"amla_decode_asm_{kind}{'_lazy' if lazy else ''}{'_bal' if bal else ''}", kind, lazy, bal)
+           for bal in (False, True) for lazy in (False, True) for kind in ("mul", "add", "ldexp")]
 
 
 def main():

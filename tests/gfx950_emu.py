@@ -578,6 +578,12 @@ class Wave:
         if mnem in ("v_accvgpr_write_b32", "v_accvgpr_read_b32", "v_mov_b32"):
             self.vdst(ops[0], V(ops[1]))
             return nxt
+        if mnem == "v_ldexp_f32":
+            x = f32(V(ops[1])).astype(np.float64)
+            n = V(ops[2]).astype(np.int32).astype(np.int64)
+            with np.errstate(over="ignore", under="ignore"):
+                self.vdst(ops[0], bits(np.ldexp(x, np.clip(n, -300, 300)).astype(np.float32)))
+            return nxt
         if mnem == "v_readfirstlane_b32":
             x = V(ops[1])
             lane = next((i for i in range(LANES) if (self.exec >> i) & 1), 0)

@@ -148,7 +148,8 @@ def check(o, l, case, bf16_out=True):
     return eo, el
 
 
-KERNELS = ["amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_mul_lazy", "amla_decode_asm_add_lazy"]
+KERNELS = ["amla_decode_asm_mul", "amla_decode_asm_add", "amla_decode_asm_mul_lazy", "amla_decode_asm_add_lazy",
+           "amla_decode_asm_ldexp", "amla_decode_asm_ldexp_lazy"]
 
 
 def test_generated_assembly_assembles(asm_text, tmp_path):
@@ -325,3 +326,19 @@ def test_extreme_inputs_on_the_emulator(asm_text, kernel):
     flat.kv_bits[...] = 0
     o, l, _ = run_case(asm_text, kernel, flat, 1)
     assert np.all(o == 0) and np.abs(l - np.log(100.0)).max() < 1e-5
+
+
+def test_ldexp_kernel_equals_the_integer_add_kernel(asm_text):
+    """Same reference, same weights, same products; inside Lemma 3.1's range v_ldexp_f32 and the guarded
+    INT32 add are the same operation, so the two kernels' results agree bit for bit.  Wide logits so
+    that the rescale path runs, a split so that partial rows are written, a balanced run as well."""
+    case = wl.make_case("ldexp", 40, batch=2, s_q=1, heads=8, seqlens=[160, 97], q_sigma=5.0)
+    a = run_case(asm_text, "amla_decode_asm_add", case, 2)
+    b = run_case(asm_text, "amla_decode_asm_ldexp", case, 2)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    c = run_case(asm_text, "amla_decode_asm_ldexp_bal", case, 1, workers=3)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 2.0 ** -20))) - 9)
+    for o, l, _ in (b, c):
+        assert np.all(np.abs(o - want) <= half_ulp + 6e-3)
+        assert np.abs(l - want_lse).max() <= 1e-3

@@ -120,8 +120,11 @@ VARIANTS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"),
             pytest.param((MUL, ASM), id="mul_asm", marks=asm_off),
             pytest.param((ADD, ASM), id="add_asm", marks=asm_off),
             pytest.param((MUL, ASM | LAZY), id="mul_asm_lazy", marks=asm_off),
-            pytest.param((ADD, ASM | LAZY), id="add_asm_lazy", marks=asm_off)]
-ALL = [(MUL, 0), (ADD, 0)] + ([(MUL, ASM), (ADD, ASM), (MUL, ASM | LAZY), (ADD, ASM | LAZY)] if ASM_ON else [])
+            pytest.param((ADD, ASM | LAZY), id="add_asm_lazy", marks=asm_off),
+            pytest.param((3, ASM), id="ldexp_asm", marks=asm_off),
+            pytest.param((3, ASM | LAZY), id="ldexp_asm_lazy", marks=asm_off)]
+ALL = [(MUL, 0), (ADD, 0)] + ([(MUL, ASM), (ADD, ASM), (MUL, ASM | LAZY), (ADD, ASM | LAZY), (3, ASM), (3, ASM | LAZY)]
+                              if ASM_ON else [])
 
 
 def kw_of(v):
