@@ -70,7 +70,7 @@ enum {
                                    reference follows the row max by construction. */
   AMLA_FLAG_ASM_KERNEL = 4      /* run the hand-scheduled assembly kernels (32-key steps, explicit
                                    MFMA / VALU / LDS interleave) instead of the compiler-built HIP
-                                   kernel (64-key steps); MUL and ADD variants only.  SWITCHED OFF:
+                                   kernel (64-key steps); MUL, ADD and ADD_LDEXP variants.  SWITCHED OFF:
                                    rejected with
                                    AMLA_ERR_UNSUPPORTED unless the environment variable
                                    AMLA_ENABLE_ASM_KERNELS is "1", because these kernels have not
