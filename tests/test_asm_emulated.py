@@ -342,3 +342,33 @@ def test_ldexp_kernel_equals_the_integer_add_kernel(asm_text):
     for o, l, _ in (b, c):
         assert np.all(np.abs(o - want) <= half_ulp + 6e-3)
         assert np.abs(l - want_lse).max() <= 1e-3
+
+
+def test_random_shapes_on_the_emulator(asm_text):
+    """Seeded sweep: batch, heads (one or two row tiles), s_q, lengths with empty sequences and ragged last
+    sub-tiles, kernel kind, split factor or worker count, early or late loads."""
+    rng = np.random.default_rng(42)
+    kinds = ["mul", "add", "ldexp", "mul_lazy", "add_lazy", "ldexp_lazy"]
+    for trial in range(6):
+        batch = int(rng.integers(1, 5))
+        s_q = int(rng.integers(1, 3))
+        heads = int(rng.choice([1, 5, 70]))
+        lens = rng.integers(0, 230, batch)
+        if trial % 2:
+            lens[rng.integers(0, batch)] = 0
+        kind = kinds[trial % len(kinds)]
+        balanced = bool(trial % 2)
+        q_sigma = float(rng.choice([1.0, 4.0]))
+        case = wl.make_case(f"sweep{trial}", 420 + trial, batch=batch, s_q=s_q, heads=heads, seqlens=lens.tolist(),
+                            spare_frac=0.4, q_sigma=q_sigma,
+                            max_blocks_per_seq=int(lens.max() + 63) // 64 + int(rng.integers(0, 2)) or 1)
+        name = "amla_decode_asm_" + kind + ("_bal" if balanced else "")
+        n = int(rng.integers(1, 7))
+        o, l, _ = run_case(asm_text, name, case, n, dma_late=bool(rng.integers(0, 2)), workers=n if balanced else 0)
+        want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+        fin = np.isfinite(want_lse)
+        half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 2.0 ** -20))) - 9)
+        assert np.array_equal(l[~fin], want_lse[~fin]), (trial, name)
+        assert np.all(np.abs(o - want) <= half_ulp + 6e-3), (trial, name, np.abs(o - want).max())
+        if fin.any():
+            assert np.abs(l[fin] - want_lse[fin]).max() <= 1e-3, (trial, name)
