@@ -35,8 +35,10 @@
  *
  * Every pointer below is a DEVICE pointer unless it says host.  The library allocates
  * no device memory, never synchronises the device, and enqueues all work on desc->stream.  The
- * caller owns every buffer.  The only state kept between calls is the code object of the
- * hand-scheduled kernels, loaded once per device on the first call that asks for them.
+ * caller owns every buffer.  The only state kept between calls is per device and set up by the
+ * first call that needs it: the code object of the hand-scheduled kernels, and the record of which
+ * kernels have been allowed their dynamic LDS size.  After that first call a call consists of kernel
+ * launches only, so it may be recorded under stream capture (make the first call of a kind outside it).
  */
 #ifndef AMLA_H_
 #define AMLA_H_

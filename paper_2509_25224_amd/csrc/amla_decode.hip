@@ -76,6 +76,28 @@ const DeviceKernels* device_kernels() {
   return k.ok ? &k : nullptr;
 }
 
+// The decode kernels use more dynamic LDS than a launch may ask for by default; the attribute that
+// allows it is set once per kernel and device, on the first call, so that later calls (for instance
+// under stream capture) consist of launches only.
+constexpr int kMaxDecodeKernels = 32;
+const void* g_lds_ok[kMaxDevices][kMaxDecodeKernels];
+std::mutex g_lds_ok_mutex;
+
+bool allow_large_lds(const void* kernel) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+  std::lock_guard<std::mutex> lock(g_lds_ok_mutex);
+  int n = 0;
+  for (; n < kMaxDecodeKernels && g_lds_ok[dev][n] != nullptr; ++n)
+    if (g_lds_ok[dev][n] == kernel) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  if (n < kMaxDecodeKernels) g_lds_ok[dev][n] = kernel;
+  return true;
+}
+
 // Kernel argument block of the assembly kernels (offsets are fixed in the generator).
 struct AsmArgs {
   const void* q;
@@ -249,11 +271,7 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
                                                      : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
                                                              : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
     }
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kLdsBytes) != hipSuccess) {
-      (void)hipGetLastError();
-      return AMLA_ERR_LAUNCH;
-    }
+    if (!allow_large_lds(reinterpret_cast<const void*>(kern))) return AMLA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, stream, p);
     if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   } else {
