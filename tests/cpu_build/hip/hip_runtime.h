@@ -24,6 +24,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <string>
 #include <thread>
 #include <vector>
 
@@ -223,11 +224,44 @@ inline hipError_t hipGetSymbolAddress(void** ptr, const void* symbol) {
   *ptr = const_cast<void*>(symbol);
   return hipSuccess;
 }
-// no code objects on the CPU: the hand-scheduled kernels are unavailable in this build
-inline hipError_t hipModuleLoadData(hipModule_t*, const void*) { return hipErrorNotSupported; }
-inline hipError_t hipModuleGetFunction(hipFunction_t*, hipModule_t, const char*) { return hipErrorNotSupported; }
-inline hipError_t hipModuleLaunchKernel(hipFunction_t, unsigned, unsigned, unsigned, unsigned, unsigned, unsigned,
-                                        unsigned, hipStream_t, void**, void**) { return hipErrorNotSupported; }
+// Code objects cannot run on the CPU.  By default loading one fails (the hand-scheduled kernels are then
+// unavailable in this build).  With the environment variable AMLA_SHIM_RECORD naming a file, loading
+// succeeds and every launch of a code-object kernel is appended to that file instead of run: the kernel's
+// name, grid, block and argument block, so that a test can check what the host code would hand to the
+// kernel (and run the kernel on the assembly emulator with exactly those arguments).
+namespace shim {
+inline std::vector<std::string>& module_names() {
+  static std::vector<std::string> names;
+  return names;
+}
+}  // namespace shim
+inline hipError_t hipModuleLoadData(hipModule_t* m, const void*) {
+  if (std::getenv("AMLA_SHIM_RECORD") == nullptr) return hipErrorNotSupported;
+  *m = reinterpret_cast<hipModule_t>(1);
+  return hipSuccess;
+}
+inline hipError_t hipModuleGetFunction(hipFunction_t* f, hipModule_t, const char* name) {
+  shim::module_names().push_back(name);
+  *f = reinterpret_cast<hipFunction_t>(shim::module_names().size());     // 1-based index into the names
+  return hipSuccess;
+}
+inline hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned gx, unsigned gy, unsigned gz, unsigned bx, unsigned by,
+                                        unsigned bz, unsigned, hipStream_t, void**, void** extra) {
+  const char* path = std::getenv("AMLA_SHIM_RECORD");
+  if (path == nullptr || extra == nullptr || extra[0] != HIP_LAUNCH_PARAM_BUFFER_POINTER ||
+      extra[2] != HIP_LAUNCH_PARAM_BUFFER_SIZE)
+    return hipErrorNotSupported;
+  const size_t bytes = *static_cast<const size_t*>(extra[3]);
+  FILE* out = std::fopen(path, "ab");
+  if (out == nullptr) return hipErrorNotSupported;
+  const std::string& name = shim::module_names()[reinterpret_cast<size_t>(f) - 1];
+  const uint32_t head[8] = {(uint32_t)name.size(), gx, gy, gz, bx, by, bz, (uint32_t)bytes};
+  std::fwrite(head, 4, 8, out);
+  std::fwrite(name.data(), 1, name.size(), out);
+  std::fwrite(extra[1], 1, bytes, out);
+  std::fclose(out);
+  return hipSuccess;
+}
 #define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                              \
   do {                                                                                             \
     const dim3 shim_grid = (grid), shim_block = (block);                                           \

@@ -372,3 +372,85 @@ def test_random_shapes_on_the_emulator(asm_text):
         assert np.all(np.abs(o - want) <= half_ulp + 6e-3), (trial, name, np.abs(o - want).max())
         if fin.any():
             assert np.abs(l[fin] - want_lse[fin]).max() <= 1e-3, (trial, name)
+
+
+# ---- the host code's view: arguments recorded from amla_decode in the CPU build, kernel run on the emulator ----
+def _host_launch_record(tmp_path, case, variant, flags, num_splits):
+    """Builds the library's source for the host (tests/cpu_build), lets amla_decode dispatch a
+    hand-scheduled kernel, and returns what it handed to hipModuleLaunchKernel."""
+    import test_cpu_build as cpu
+    if not os.path.exists(cpu.CLANG):
+        pytest.skip("no clang++ to build the CPU harness with")
+    exe = cpu.build(tmp_path)
+    rec = tmp_path / "launches.bin"
+    inp, outp = str(tmp_path / "in.bin"), str(tmp_path / "out.bin")
+    with open(inp, "wb") as f:
+        f.write(struct.pack("<12i", case.batch, case.s_q, case.heads, case.num_blocks, case.max_blocks_per_seq,
+                            variant, num_splits, flags, 0, 0, 0, 0))
+        f.write(struct.pack("<f", case.softmax_scale))
+        for a in (case.q_bits, case.kv_bits, case.block_table, case.seqlens):
+            f.write(np.ascontiguousarray(a).tobytes())
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", AMLA_ENABLE_BALANCED="1", AMLA_ENABLE_ASM_KERNELS="1",
+               AMLA_SHIM_RECORD=str(rec))
+    env.pop("LD_PRELOAD", None)
+    r = subprocess.run([exe, inp, outp], capture_output=True, text=True, env=env, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    status, splits = (int(x) for x in np.fromfile(outp, dtype=np.int32, count=2))
+    assert status == 0, status
+    raw = rec.read_bytes()
+    n, gx, gy, gz, bx, by, bz, nbytes = struct.unpack_from("<8I", raw, 0)
+    name = raw[32:32 + n].decode()
+    karg = raw[32 + n:32 + n + nbytes]
+    assert len(raw) == 32 + n + nbytes and (gz, bx, by, bz) == (1, 256, 1, 1)
+    return name, (gx, gy), karg, splits
+
+
+@pytest.mark.parametrize("variant,flags,num_splits", [(1, 4, 3), (0, 4 | 2, 0), (3, 4 | 8, 5), (1, 4 | 8 | 2, 0)])
+def test_arguments_from_the_host_code_drive_the_kernel(asm_text, tmp_path, variant, flags, num_splits):
+    """What amla_decode passes to the hand-scheduled kernels (grid, split factor or worker count, the two
+    division constants, pool size), taken from the host code itself, must be what the kernels expect:
+    the recorded argument block, with only the eight pointers replaced, runs on the emulator and gives
+    the oracle's result.  Flags: 4 = assembly kernels, 2 = lazy, 8 = balanced."""
+    from paper_2509_25224_amd import amla
+    case = wl.make_case("host", 43, batch=3, s_q=1, heads=6, seqlens=[150, 40, 260], spare_frac=0.3, q_sigma=2.0)
+    name, (gx, gy), karg, splits = _host_launch_record(tmp_path, case, variant, flags, num_splits)
+    balanced = bool(flags & 8)
+    kind = {0: "mul", 1: "add", 3: "ldexp"}[variant]
+    assert name == "amla_decode_asm_" + kind + ("_lazy" if flags & 2 else "") + ("_bal" if balanced else "")
+    ins, labels = emu.parse_kernel(asm_text, name)
+    B, rows = case.batch, case.s_q * case.heads
+    n_rows = B * rows
+    slots = (splits + B - 1) if balanced else splits * B
+    mem = emu.Memory()
+    ptrs = [mem.add("q", case.q_bits), mem.add("kv", case.kv_bits), mem.add("table", case.block_table),
+            mem.add("seqlens", case.seqlens),
+            mem.add("out", np.full(n_rows * 512, 0x7F7F, np.uint16), writable=True),
+            mem.add("lse", np.full(n_rows, np.nan, np.float32), writable=True),
+            mem.add("part_o", np.full(max(1, slots * rows * 512), np.nan, np.float32), writable=True),
+            mem.add("part_lse", np.full(max(1, slots * rows), np.nan, np.float32), writable=True)]
+    ka = mem.add("kernarg", np.frombuffer(struct.pack("<8Q", *ptrs) + karg[64:], dtype=np.uint8))
+    n_streams = splits if balanced else B * splits
+    assert (gx, gy) == (8 * ((rows + 127) // 128), (n_streams + 7) // 8)
+    for y in range(gy):
+        for x in range(gx):
+            if y * 8 + (x & 7) >= n_streams and (x, y) != (gx - 1, gy - 1):
+                continue
+            emu.Workgroup(ins, labels, mem, ka, x, y, LDS_BYTES, dma_late=True).run()
+    o = (mem.get("out").view(np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64).reshape(B, rows, 512)
+    l = mem.get("lse").view(np.float32).astype(np.float64).reshape(B, rows)
+    P = mem.get("part_o").view(np.float32).astype(np.float64).reshape(-1, rows, 512)
+    PL = mem.get("part_lse").view(np.float32).astype(np.float64).reshape(-1, rows)
+    if balanced:
+        pieces, _ = amla.amla_plan_segments(case.seqlens, splits)
+        groups = {b: [p[4] for p in pieces if p[1] == b] for b in range(B)}
+    else:
+        groups = {b: [s * B + b for s in range(splits)] for b in range(B)} if splits > 1 else {}
+    for b, slot_ids in groups.items():
+        if len(slot_ids) < 2:
+            continue
+        pls = np.stack([PL[i] for i in slot_ids])
+        mx = pls.max(axis=0)
+        w = np.where(np.isneginf(pls), 0.0, np.exp(pls - mx))
+        o[b] = sum(w[i][:, None] * np.nan_to_num(P[sid]) for i, sid in enumerate(slot_ids)) / w.sum(axis=0)[:, None]
+        l[b] = mx + np.log(w.sum(axis=0))
+    check(o.reshape(B, case.s_q, case.heads, 512), l.reshape(B, case.s_q, case.heads), case)
