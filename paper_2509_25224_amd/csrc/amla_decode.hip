@@ -43,6 +43,12 @@ namespace {
 const unsigned char kDecodeCodeObject[] = {
 #include "amla_decode_gfx950.hsaco.inc"
 };
+// The same kernels in their diagnostic form (every wait a full drain, idle issue slots after every
+// instruction): loaded instead when AMLA_ASM_SAFE_BUILD=1.  A wrong result that disappears with it
+// points at a timing hazard, one that stays at a semantic mistake.
+const unsigned char kDecodeCodeObjectSafe[] = {
+#include "amla_decode_gfx950_safe.hsaco.inc"
+};
 
 constexpr int kMaxDevices = 64;
 constexpr int kAsmKernels = 12;   // index = kind (mul, add, ldexp) + 3 * lazy + 6 * balanced
@@ -68,7 +74,9 @@ const DeviceKernels* device_kernels() {
   DeviceKernels& k = g_kernels[dev];
   if (!k.tried) {
     k.tried = true;
-    bool ok = hipModuleLoadData(&k.module, kDecodeCodeObject) == hipSuccess;
+    const char* safe = std::getenv("AMLA_ASM_SAFE_BUILD");
+    const bool use_safe = safe != nullptr && std::strcmp(safe, "1") == 0;
+    bool ok = hipModuleLoadData(&k.module, use_safe ? kDecodeCodeObjectSafe : kDecodeCodeObject) == hipSuccess;
     for (int i = 0; ok && i < kAsmKernels; ++i) ok = hipModuleGetFunction(&k.fn[i], k.module, kAsmNames[i]) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     k.ok = ok;

@@ -454,3 +454,24 @@ def test_arguments_from_the_host_code_drive_the_kernel(asm_text, tmp_path, varia
         o[b] = sum(w[i][:, None] * np.nan_to_num(P[sid]) for i, sid in enumerate(slot_ids)) / w.sum(axis=0)[:, None]
         l[b] = mx + np.log(w.sum(axis=0))
     check(o.reshape(B, case.s_q, case.heads, 512), l.reshape(B, case.s_q, case.heads), case)
+
+
+def test_the_diagnostic_build_is_the_same_program(tmp_path):
+    """The padded form of the kernels (AMLA_ASM_SAFE=1: every wait a full drain, idle slots after every
+    instruction; the library loads it when AMLA_ASM_SAFE_BUILD=1) assembles, keeps the hazard rules
+    and computes the same result."""
+    out = tmp_path / "safe.s"
+    env = dict(os.environ, AMLA_ASM_SAFE="1")
+    env.pop("AMLA_ASM_DEBUG", None)
+    subprocess.run([sys.executable, GEN, str(out)], check=True, env=env)
+    text = out.read_text()
+    for kernel in ("amla_decode_asm_add_lazy", "amla_decode_asm_mul_bal"):
+        ins, labels = emu.parse_kernel(text, kernel)
+        assert emu.check_hazards(ins, labels) == []
+    case = wl.make_config(0)
+    o, l, _ = run_case(text, "amla_decode_asm_add_lazy", case, 1)
+    check(o, l, case)
+    clang = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang")
+    if os.path.exists(clang):
+        subprocess.run([clang, "-x", "assembler", "-target", "amdgcn-amd-amdhsa", "-mcpu=gfx950", "-c", str(out), "-o",
+                        str(tmp_path / "safe.o")], check=True)

@@ -28,6 +28,7 @@ def build(tmp, extra=()):
     out = str(tmp / "decode_cpu")
     # the code object of the hand-scheduled kernels cannot be loaded on the CPU: one byte stands in
     (tmp / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
+    (tmp / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     subprocess.run([CLANG, "-x", "c++", *FLAGS, *extra, "-I" + SHIM, "-I" + os.path.join(ROOT, "include"),
                     "-I" + str(tmp), os.path.join(SHIM, "decode_cpu.cpp"), "-o", out], check=True)
     return out
@@ -226,6 +227,7 @@ def test_thread_sanitizer_sees_no_race_between_waves(tmp_path):
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ to build the CPU harness with")
     (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
+    (tmp_path / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     exe = str(tmp_path / "decode_tsan")
     subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=thread", "-pthread",
                     "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi", "-I" + SHIM,
@@ -276,6 +278,7 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
     shutil.copytree(os.path.join(SHIM, "hip"), shim / "hip")
     shutil.copy(os.path.join(SHIM, "decode_cpu.cpp"), shim / "decode_cpu.cpp")
     (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
+    (tmp_path / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
     for sanitizer in ("address", "thread"):
         exe = str(tmp_path / ("decode_" + sanitizer))

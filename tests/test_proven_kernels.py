@@ -23,10 +23,11 @@ def kernel_hashes(tmp):
     sys.path.insert(0, ROOT)
     import __graft_entry__ as entry
     gen = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "_build")
-    if not os.path.exists(os.path.join(gen, "amla_decode_gfx950.hsaco.inc")):
-        os.makedirs(gen, exist_ok=True)
-        with open(os.path.join(gen, "amla_decode_gfx950.hsaco.inc"), "w") as f:
-            f.write("0,\n")
+    for inc in ("amla_decode_gfx950.hsaco.inc", "amla_decode_gfx950_safe.hsaco.inc"):
+        if not os.path.exists(os.path.join(gen, inc)):
+            os.makedirs(gen, exist_ok=True)
+            with open(os.path.join(gen, inc), "w") as f:
+                f.write("0,\n")
     flags = [f for f in entry.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
     out = os.path.join(tmp, "device.s")
     subprocess.run([HIPCC, *flags, "-I" + gen, "--cuda-device-only", "-S", "-o", out, SRC], check=True,
