@@ -148,6 +148,11 @@ typedef struct amla_desc {
  *
  * Returns AMLA_OK or a negative AMLA_ERR_*; never throws, never aborts.  On error nothing
  * has been enqueued.
+ *
+ * Concurrency: the function may be called from several host threads; calls whose work may run at
+ * the same time (different streams) need different `out`, `lse` and `desc->workspace` buffers.
+ * The workspace need not be cleared between calls: every partial row that is read has been
+ * written by the same call.
  */
 int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
                 const int32_t* seqlens, float softmax_scale, void* out, float* lse,
