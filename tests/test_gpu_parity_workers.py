@@ -84,7 +84,7 @@ def test_causal_mask_among_the_query_tokens(env, kind, workers):
     """s_q = 4 under AMLA_FLAG_CAUSAL: tokens without any key (kv_len 1), limits at and just past block
     boundaries (whole blocks masked for the early tokens), 40 heads (two tokens per wave)."""
     torch, orc, amla, wl = env
-    case = wl.make_case("causal", 43, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
+    case = wl.make_case("causal", 44, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
                                 causal=True)
     out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=kind[0], flags=kind[1] | CAUSAL,
