@@ -654,7 +654,8 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
         v.extend(work)
         if rescale == "mul":
             v.append(f"v_fma_f32 v{V_L32}, v{V_L32}, v{V_FAC}, v{T2}")
-            v.append(f"v_fma_f32 v{V_L16}, v{V_L16}, v{V_FAC}, v{T3}")
+            v.append("s_nop 1")                                  # a dot result needs three wait states before another
+            v.append(f"v_fma_f32 v{V_L16}, v{V_L16}, v{V_FAC}, v{T3}")    # instruction may read it
         elif rescale == "ldexp":
             for reg, add in ((V_L32, T2), (V_L16, T3)):
                 v.append(f"v_ldexp_f32 v{reg}, v{reg}, v{V_FAC}")

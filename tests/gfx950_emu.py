@@ -873,6 +873,9 @@ def check_hazards(ins, labels):
                     problems.append(f"{i}:{m} -> {j}:{m2}: needs a wait state")
                 if _is_valu(m) and m2 == "v_permlane32_swap_b32" and gap < 2:
                     problems.append(f"{i}:{m} -> {j}:{m2}: needs two wait states")
+                if m == "v_dot2c_f32_bf16" and gap < 3 and not (m2 == m and hit <= _regs_of(ops2[0])
+                                                                and not hit & (_regs_of(ops2[1]) | _regs_of(ops2[2]))):
+                    problems.append(f"{i}:{m} -> {j}:{m2}: dot result read after {gap} wait states")
                 if m in TRANS and _is_valu(m2) and gap < 1:
                     problems.append(f"{i}:{m} -> {j}:{m2}: trans result used by the next VALU op")
                 if m.startswith("v_mfma") and not m2.startswith("v_mfma") and gap < 18:
@@ -888,6 +891,10 @@ def check_hazards(ins, labels):
                     problems.append(f"{i}:{m} -> {j}:{m2}: VALU-written SGPR used by VMEM")
             if ops and ops[0] == "m0" and m.startswith("s_") and m2 == "global_load_lds_dwordx4" and gap < 1:
                 problems.append(f"{i}:{m} -> {j}:{m2}: M0 write directly before LDS DMA")
+            if m.startswith("v_mfma") and not m2.startswith("v_mfma") and wr & wr2 and not hit and gap < 18:
+                problems.append(f"{i}:{m} -> {j}:{m2}: MFMA result overwritten after {gap} wait states")
+            if m == "v_dot2c_f32_bf16" and wr & wr2 and not hit and gap < 3:
+                problems.append(f"{i}:{m} -> {j}:{m2}: dot result overwritten after {gap} wait states")
             wr = wr - wr2 if not hit else wr                       # a later overwrite ends the window
             if m2 == "s_endpgm":
                 return
@@ -902,6 +909,10 @@ def check_hazards(ins, labels):
 
     for i, (m, ops, mods) in enumerate(ins):
         wr, _ = _dst_src(m, ops)
+        if m in ("global_store_dwordx3", "global_store_dwordx4") and i + 1 < len(ins):
+            m2, ops2, _ = ins[i + 1]                               # wide store data must survive one more slot
+            if _is_valu(m2) and _dst_src(m2, ops2)[0] & _regs_of(ops[1]):
+                problems.append(f"{i}:{m} -> {i + 1}:{m2}: store data overwritten in the next slot")
         if ops and ops[0] == "m0":
             wr = wr | {("m", 0)}
         if wr:

@@ -193,6 +193,19 @@ def test_hazard_checker_follows_branches_and_counts_nops():
     assert not _problems("\ts_add_u32 m0, s59, 0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v241, s[46:47]\n")
     assert _problems("\tv_exp_f32 v176, v176\n\tv_add_f32 v253, v176, v177\n")
     assert _problems("\tv_mov_b32 v252, v251\n\ts_nop 0\n\tv_permlane32_swap_b32 v251, v252\n")
+    # a dot result: free for the same instruction accumulating into it, three wait states for any other use
+    dot = "\tv_dot2c_f32_bf16 v254, s41, v192\n"
+    assert not _problems(dot + "\tv_dot2c_f32_bf16 v254, s41, v193\n")
+    assert _problems(dot + "\ts_nop 1\n\tv_fma_f32 v240, v240, v250, v254\n")
+    assert not _problems(dot + "\ts_nop 2\n\tv_fma_f32 v240, v240, v250, v254\n")
+    assert _problems(dot + "\ts_nop 1\n\tv_dot2c_f32_bf16 v253, s41, v254\n")
+    assert _problems(dot + "\ts_nop 1\n\tv_mov_b32 v254, 0\n")
+    acc = "\tv_mfma_f32_32x32x16_bf16 a[0:15], v[200:203], v[0:3], a[0:15]\n"
+    assert _problems(acc + "\ts_nop 7\n\tv_accvgpr_read_b32 v5, a3\n")
+    assert _problems(acc + "\ts_nop 7\n\tv_accvgpr_write_b32 a3, 0\n")            # overwritten while in flight
+    assert not _problems(acc + "\ts_nop 15\n\ts_nop 1\n\tv_accvgpr_write_b32 a3, 0\n")
+    assert _problems("\tglobal_store_dwordx4 v[10:11], v[20:23], off\n\tv_mov_b32 v21, 0\n")
+    assert not _problems("\tglobal_store_dwordx4 v[10:11], v[20:23], off\n\ts_nop 0\n\tv_mov_b32 v21, 0\n")
 
 
 def test_emulator_reports_a_missing_wait():
