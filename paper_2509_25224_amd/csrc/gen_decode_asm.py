@@ -1065,16 +1065,20 @@ def main():
     g.lines.append("\t.text")
     for name, rescale, lazy, balanced in KERNELS:
         kernel(g, name, rescale, lazy, balanced)
-    if os.environ.get("AMLA_ASM_SAFE") == "1":
-        # Diagnostic build: every wait is a full drain and every instruction is followed by idle
-        # issue slots, so that a wrong result that disappears here points at a timing hazard.
+    level = os.environ.get("AMLA_ASM_SAFE", "")
+    if level in ("1", "waits", "slots"):
+        # Diagnostic build: every wait is a full drain ("waits"), every instruction is followed by idle
+        # issue slots ("slots"), or both ("1"), so that a wrong result that disappears here points at a
+        # counted wait or at a wait-state rule respectively.
         safe = []
         for ln in g.lines:
             t = ln.strip()
-            if t.startswith("s_waitcnt"):
+            if t.startswith("s_waitcnt") and level != "slots":
                 safe.append("\ts_waitcnt vmcnt(0) lgkmcnt(0)")
                 continue
             safe.append(ln)
+            if level == "waits":
+                continue
             if t.startswith("v_mfma"):
                 safe.append("\ts_nop 15")
                 safe.append("\ts_nop 3")

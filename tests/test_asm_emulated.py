@@ -469,12 +469,14 @@ def test_arguments_from_the_host_code_drive_the_kernel(asm_text, tmp_path, varia
     check(o.reshape(B, case.s_q, case.heads, 512), l.reshape(B, case.s_q, case.heads), case)
 
 
-def test_the_diagnostic_build_is_the_same_program(tmp_path):
-    """The padded form of the kernels (AMLA_ASM_SAFE=1: every wait a full drain, idle slots after every
-    instruction; the library loads it when AMLA_ASM_SAFE_BUILD=1) assembles, keeps the hazard rules
-    and computes the same result."""
+@pytest.mark.parametrize("level", ["1", "waits", "slots"])
+def test_the_diagnostic_build_is_the_same_program(tmp_path, level):
+    """The padded forms of the kernels (AMLA_ASM_SAFE=1: every wait a full drain and idle slots after
+    every instruction, "waits" / "slots": one of the two; the library loads the form built as the
+    diagnostic one when AMLA_ASM_SAFE_BUILD=1) assemble, keep the hazard rules and compute the same
+    result."""
     out = tmp_path / "safe.s"
-    env = dict(os.environ, AMLA_ASM_SAFE="1")
+    env = dict(os.environ, AMLA_ASM_SAFE=level)
     env.pop("AMLA_ASM_DEBUG", None)
     subprocess.run([sys.executable, GEN, str(out)], check=True, env=env)
     text = out.read_text()
