@@ -204,6 +204,26 @@ int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stre
 int amla_plan_segments(const int32_t* seqlens, int32_t batch, int32_t workers, int32_t* pieces, int32_t capacity,
                        int32_t* n_pieces, int32_t* seq_workers);
 
+/*
+ * amla_preload_rotation -- the Cycle of the Preload Pipeline (Section 4.1, Theorem 4.1; Appendix B,
+ * Theorem B.3), host only.  For the dependency chain C_1 -> V_1 -> C_2 -> ... -> C_n -> V_n of n
+ * matrix ("Cube") and n vector stages with durations cube[i-1], vec[i-1] >= 0 (HOST arrays, any one
+ * unit, e.g. cycles; sums below 2^62), finds the cyclic order of the matrix stages in one Cycle of
+ * the steady loop under which n - 1 of the C_i -> V_i dependencies stay inside the Cycle and their
+ * vector stages still end with it, so that only n stages have to be preloaded.  The rule is the
+ * one of the proof: with a_i = V_i - C_{i+1} (C_{n+1} = C_1) and F(l) = a_1 + ... + a_l, take the
+ * first l in 1..n that minimises F; the Cycle ends with C_{l+1} and starts with C_{l+2} (cyclic).
+ * Writes the 1-based number of the Cycle's first matrix stage to *first_stage, the pair whose
+ * C -> V dependency crosses Cycles (the last matrix stage) to *external_pair and the Preload count
+ * (= n) to *preload_count.  Requires sum(vec) <= sum(cube) -- the matrix-bound case the theorem is
+ * proved for -- and 1 <= n <= 4096; otherwise AMLA_ERR_UNSUPPORTED.  For the chain of this library
+ * (n = 2, V_2 = 0) the answer is first_stage 2, external_pair 1, count 2 for any durations: the Cycle
+ * [C1, C2, V1] of Section 4.1 in which V1 consumes the previous Cycle's C1, which is the pass order
+ * the hand-scheduled kernels hard-code.
+ */
+int amla_preload_rotation(const int64_t* cube, const int64_t* vec, int32_t n, int32_t* first_stage,
+                          int32_t* external_pair, int32_t* preload_count);
+
 /* amla_status_string -- static, NUL-terminated description of a status code (host). */
 const char* amla_status_string(int status);
 

@@ -27,7 +27,7 @@ AMLA_FLAG_BALANCED = 8
 AMLA_FLAG_CAUSAL = 16
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
-           "amla_mfma_probe", "amla_plan_segments", "amla_status_string")
+           "amla_mfma_probe", "amla_plan_segments", "amla_preload_rotation", "amla_status_string")
 
 
 class AmlaDesc(ctypes.Structure):
@@ -62,6 +62,8 @@ lib.amla_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(c
 lib.amla_plan_segments.restype = ctypes.c_int
 lib.amla_plan_segments.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
                                    ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
+lib.amla_preload_rotation.restype = ctypes.c_int
+lib.amla_preload_rotation.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32] + [ctypes.POINTER(ctypes.c_int32)] * 3
 lib.amla_status_string.restype = ctypes.c_char_p
 lib.amla_status_string.argtypes = [ctypes.c_int]
 
@@ -180,3 +182,20 @@ def amla_plan_segments(seqlens, workers: int):
     if st != AMLA_OK:
         raise AmlaError(st)
     return pieces[:n.value].copy(), seq_workers
+
+
+def amla_preload_rotation(cube, vec):
+    """Cycle rotation of the Preload Pipeline for stage durations `cube`, `vec` (int sequences of equal
+    length): returns (first matrix stage of the Cycle, pair whose C -> V edge crosses Cycles, Preload
+    count), stage numbers 1-based."""
+    import numpy as np
+
+    c = np.ascontiguousarray(np.asarray(cube, dtype=np.int64))
+    v = np.ascontiguousarray(np.asarray(vec, dtype=np.int64))
+    if c.ndim != 1 or c.shape != v.shape:
+        raise ValueError("cube and vec must be one-dimensional and of equal length")
+    out = [ctypes.c_int32(0) for _ in range(3)]
+    st = lib.amla_preload_rotation(c.ctypes.data, v.ctypes.data, int(c.shape[0]), *[ctypes.byref(o) for o in out])
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return tuple(o.value for o in out)

@@ -405,6 +405,38 @@ int amla_plan_segments(const int32_t* seqlens, int32_t batch, int32_t workers, i
   return n <= capacity ? AMLA_OK : AMLA_ERR_WORKSPACE;
 }
 
+// Theorem B.3's construction: the rotation sits at the minimum of the partial sums of
+// a_i = V_i - C_{i+1}.
+int amla_preload_rotation(const int64_t* cube, const int64_t* vec, int32_t n, int32_t* first_stage,
+                          int32_t* external_pair, int32_t* preload_count) {
+  if (cube == nullptr || vec == nullptr || first_stage == nullptr || external_pair == nullptr ||
+      preload_count == nullptr)
+    return AMLA_ERR_NULL_ARG;
+  if (n < 1 || n > 4096) return AMLA_ERR_UNSUPPORTED;
+  const int64_t limit = (int64_t)1 << 62;
+  int64_t sum_c = 0, sum_v = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (cube[i] < 0 || vec[i] < 0 || cube[i] >= limit - sum_c || vec[i] >= limit - sum_v) return AMLA_ERR_UNSUPPORTED;
+    sum_c += cube[i];
+    sum_v += vec[i];
+  }
+  if (sum_v > sum_c) return AMLA_ERR_UNSUPPORTED;
+  int64_t f = 0, best = 0;
+  int32_t arg = 0;
+  for (int32_t l = 1; l <= n; ++l) {
+    f += vec[l - 1] - cube[l % n];  // a_l
+    if (arg == 0 || f < best) {
+      best = f;
+      arg = l;
+    }
+  }
+  const int32_t last = arg % n + 1;  // C_{l+1}
+  *external_pair = last;
+  *first_stage = last % n + 1;
+  *preload_count = n;
+  return AMLA_OK;
+}
+
 const char* amla_status_string(int status) {
   switch (status) {
     case AMLA_OK: return "ok";
