@@ -91,13 +91,16 @@ def attention_rows(Q: np.ndarray, K: np.ndarray, scale: float):
     return out, lse
 
 
-def decode(q_bits, kv_bits, block_table, seqlens, softmax_scale, seq_ids=None, causal=False):
+def decode(q_bits, kv_bits, block_table, seqlens, softmax_scale, seq_ids=None, causal=False, q_lens=None):
     """Decode attention for every row (b, t, h).  Without `causal` all s_q query tokens of a
     sequence see all kv_len cached keys (no mask among them).  With `causal` the s_q tokens are the
     last s_q positions of the cache and token t sees keys 0 .. kv_len - s_q + t, that is the first
     kv_len - (s_q - 1 - t) keys (none if that is <= 0: out = 0, lse = -inf).  The paper has no mask
     (its kernel is quoted for s_q in {1, 2} without one); this is the usual multi-token-prediction
-    convention.
+    convention.  `q_lens` (int [B], 0 <= q_lens[b] <= s_q) gives every sequence its own number of query
+    tokens in the padded q array: sequence b is the problem with s_q = q_lens[b] on its first q_lens[b]
+    tokens, and the rows of the padding tokens are out = 0, lse = -inf (a convention of this library;
+    the paper's kernel has one s_q for the batch).
 
     q_bits uint16 [B,T,H,576]; kv_bits uint16 [nblk,64,576]; block_table int32 [B,maxb];
     seqlens int32 [B].  Returns out float64 [B,T,H,512] (not rounded), lse float64 [B,T,H].
@@ -110,14 +113,18 @@ def decode(q_bits, kv_bits, block_table, seqlens, softmax_scale, seq_ids=None, c
     for b in (range(B) if seq_ids is None else seq_ids):
         L = int(seqlens[b])
         K = gather_kv(kv_bits, block_table[b], L)
+        Tb = T if q_lens is None else int(q_lens[b])
+        assert 0 <= Tb <= T
+        out[b, Tb:] = 0.0
+        lse[b, Tb:] = -np.inf
         if not causal:
-            Q = bf16_bits_to_f64(q_bits[b]).reshape(T * H, D_QK)
+            Q = bf16_bits_to_f64(q_bits[b, :Tb]).reshape(Tb * H, D_QK)
             o, l = attention_rows(Q, K, float(softmax_scale))
-            out[b] = o.reshape(T, H, D_V)
-            lse[b] = l.reshape(T, H)
+            out[b, :Tb] = o.reshape(Tb, H, D_V)
+            lse[b, :Tb] = l.reshape(Tb, H)
         else:
-            for t in range(T):
-                limit = max(L - (T - 1 - t), 0)
+            for t in range(Tb):
+                limit = max(L - (Tb - 1 - t), 0)
                 out[b, t], lse[b, t] = attention_rows(bf16_bits_to_f64(q_bits[b, t]), K[:limit], float(softmax_scale))
     return out, lse
 

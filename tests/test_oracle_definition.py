@@ -207,3 +207,44 @@ def test_causal_mask_against_brute_force():
                 want = sum(math.exp(x) / z * kv[j, d] for x, j in zip(logits, visible))
                 assert abs(got[0, t, h, d] - want) < 1e-12
             assert abs(got_lse[0, t, h] - math.log(z)) < 1e-12
+
+
+# ------------------------------------------------------------------ per-sequence number of query tokens
+@pytest.mark.parametrize("causal", [False, True])
+def test_q_lens_is_the_smaller_problem_on_the_first_tokens(causal):
+    """A sequence with q_lens[b] = k is, by definition, the s_q = k problem on its first k tokens; the
+    padding tokens get the empty convention; q_lens = s_q everywhere is the plain problem."""
+    case = wl.make_case("qlens", 64, batch=4, s_q=3, heads=4, seqlens=[130, 66, 5, 70], spare_frac=0.3)
+    q_lens = np.array([3, 1, 2, 0], np.int32)
+    got, got_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                              causal=causal, q_lens=q_lens)
+    for b, k in enumerate(q_lens):
+        assert np.all(got[b, k:] == 0) and np.all(np.isneginf(got_lse[b, k:]))
+        if k:
+            want, want_lse = orc.decode(case.q_bits[:, :k], case.kv_bits, case.block_table, case.seqlens,
+                                        case.softmax_scale, seq_ids=[b], causal=causal)
+            assert np.array_equal(got[b, :k], want[b]) and np.array_equal(got_lse[b, :k], want_lse[b])
+    full = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale, causal=causal,
+                      q_lens=np.full(4, 3, np.int32))
+    plain = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale, causal=causal)
+    assert np.array_equal(full[0], plain[0]) and np.array_equal(full[1], plain[1])
+
+
+def test_q_lens_with_the_mask_against_brute_force():
+    """Two of three tokens present, mask written out key by key: token t of k sees keys 0 .. kv_len - k + t."""
+    import math
+    case = wl.make_case("qlens_bf", 65, batch=1, s_q=3, heads=2, seqlens=[6], table="identity")
+    got, got_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                              causal=True, q_lens=[2])
+    q = wl.bf16_bits_to_f32(case.q_bits).astype(float)
+    kv = wl.bf16_bits_to_f32(case.kv_bits).astype(float)[0]
+    for t in range(2):
+        for h in range(2):
+            visible = [j for j in range(6) if j <= 6 - 2 + t]
+            logits = [case.softmax_scale * sum(q[0, t, h, d] * kv[j, d] for d in range(576)) for j in visible]
+            z = sum(math.exp(x) for x in logits)
+            for d in (0, 300, 511):
+                want = sum(math.exp(x) / z * kv[j, d] for x, j in zip(logits, visible))
+                assert abs(got[0, t, h, d] - want) < 1e-12
+            assert abs(got_lse[0, t, h] - math.log(z)) < 1e-12
+    assert np.all(got[0, 2] == 0) and np.all(np.isneginf(got_lse[0, 2]))
