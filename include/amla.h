@@ -121,6 +121,15 @@ typedef struct amla_desc {
                                   effective split factor is 1 */
   size_t workspace_bytes;      /* size of workspace */
   void* stream;                /* hipStream_t; NULL = the default stream */
+  const int32_t* q_lens;       /* device int32 [batch] or NULL.  Not NULL: sequence b has only its first
+                                  q_lens[b] (0 .. s_q, clamped into that range) of the s_q query tokens
+                                  of the padded q array -- a batch whose sequences carry different
+                                  numbers of new tokens.  Sequence b is then the problem with
+                                  s_q = q_lens[b] (also for AMLA_FLAG_CAUSAL: token t attends to
+                                  kv_len - (q_lens[b] - 1 - t) keys); the rows of its padding tokens are
+                                  written as out = 0, lse = -inf.  Runs in the compiler-built balanced
+                                  kernels: needs AMLA_FLAG_BALANCED or AMLA_FLAG_CAUSAL, is switched off
+                                  with them, and cannot be combined with AMLA_FLAG_ASM_KERNEL. */
 } amla_desc;
 
 /*

@@ -39,6 +39,7 @@ class AmlaDesc(ctypes.Structure):
         ("reserved", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
+        ("q_lens", ctypes.c_void_p),
     ]
 
 
@@ -85,7 +86,7 @@ def make_desc(batch, s_q, num_heads, num_blocks, max_blocks_per_seq, variant=AML
     d.d_qk, d.d_v, d.block_size = int(d_qk), int(d_v), int(block_size)
     d.num_blocks, d.max_blocks_per_seq = int(num_blocks), int(max_blocks_per_seq)
     d.variant, d.num_splits, d.flags, d.reserved = int(variant), int(num_splits), int(flags), 0
-    d.workspace, d.workspace_bytes, d.stream = None, 0, None
+    d.workspace, d.workspace_bytes, d.stream, d.q_lens = None, 0, None, None
     return d
 
 
@@ -98,12 +99,13 @@ def amla_effective_splits(desc: AmlaDesc) -> int:
 
 
 def amla_decode(q, kv_cache, block_table, seqlens, softmax_scale, out=None, lse=None, *,
-                variant=AMLA_RESCALE_ADD, num_splits=0, flags=0, workspace=None, want_lse=True):
+                variant=AMLA_RESCALE_ADD, num_splits=0, flags=0, workspace=None, want_lse=True, q_lens=None):
     """Decode attention on torch CUDA tensors.
 
     q bf16 [B, s_q, H, 576]; kv_cache bf16 [num_blocks, 64, 576]; block_table int32
     [B, max_blocks]; seqlens int32 [B].  Returns (out bf16 [B, s_q, H, 512], lse f32 [B, s_q, H]).
     `out`, `lse` and `workspace` (a uint8 tensor) are allocated with torch when not given.
+    `q_lens` (int32 CUDA tensor [B], optional): query tokens each sequence really has.
     The call is enqueued on torch's current stream.
     """
     import torch
@@ -119,6 +121,10 @@ def amla_decode(q, kv_cache, block_table, seqlens, softmax_scale, out=None, lse=
     if D2 != D:
         raise ValueError("q and kv_cache row widths differ")
     desc = make_desc(B, T, H, nblk, block_table.shape[1], variant, num_splits, flags, D, 512, bs)
+    if q_lens is not None:
+        if not (q_lens.is_cuda and q_lens.is_contiguous() and q_lens.dtype == torch.int32 and q_lens.shape == (B,)):
+            raise ValueError("q_lens must be a contiguous int32 CUDA tensor of shape [batch]")
+        desc.q_lens = q_lens.data_ptr()
     if out is None:
         out = torch.empty((B, T, H, 512), dtype=torch.bfloat16, device=q.device)
     if lse is None and want_lse:

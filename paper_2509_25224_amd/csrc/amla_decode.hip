@@ -167,6 +167,8 @@ bool desc_supported(const amla_desc* d) {
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
   if (uses_balanced(d) && !balanced_enabled()) return false;
   if ((d->flags & AMLA_FLAG_CAUSAL) && (d->flags & AMLA_FLAG_ASM_KERNEL)) return false;   // the mask is in the compiler-built kernels only
+  // per-sequence query counts are a per-row key limit like the mask: same kernels
+  if (d->q_lens != nullptr && (!uses_balanced(d) || (d->flags & AMLA_FLAG_ASM_KERNEL))) return false;
   if ((long long)d->batch * d->max_blocks_per_seq > (1ll << 31) - 1) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
@@ -251,6 +253,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
   p.num_blocks = desc->num_blocks;
   p.heads = desc->num_heads;
   p.causal_span = (desc->flags & AMLA_FLAG_CAUSAL) ? desc->s_q - 1 : 0;
+  p.s_q = desc->s_q;
+  p.q_lens = desc->q_lens;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   const size_t n_rows = (size_t)desc->batch * p.rows;
   p.part_o = (ns > 1 || balanced) ? static_cast<float*>(desc->workspace) : nullptr;

@@ -3,8 +3,9 @@
 // C-ABI entry points amla_workspace_bytes and amla_decode on host buffers of exactly the documented
 // sizes (AddressSanitizer sees every access past an end), and writes out and lse.
 //
-// input file: 12 int32 (batch, s_q, heads, num_blocks, max_blocks, variant, num_splits, flags, 0, 0, 0, 0),
-//             float softmax_scale, then q bits, cache bits, block table, seqlens
+// input file: 12 int32 (batch, s_q, heads, num_blocks, max_blocks, variant, num_splits, flags, 0,
+//             has q_lens (0/1), 0, 0), float softmax_scale, then q bits, cache bits, block table, seqlens
+//             and, when announced, q_lens
 // output file: int32 status, int32 effective splits; then, when status is 0, out bits
 //             [batch * rows * 512] uint16 and lse [batch * rows] float
 #include "../../paper_2509_25224_amd/csrc/amla_decode.hip"
@@ -39,6 +40,12 @@ int main(int argc, char** argv) {
   int32_t* lens = alloc_exact<int32_t>(d.batch);
   bool ok = std::fread(q, 2, n_rows * kDqk, f) == n_rows * kDqk && std::fread(kv, 2, n_kv, f) == n_kv &&
             std::fread(table, 4, n_tab, f) == n_tab && std::fread(lens, 4, d.batch, f) == (size_t)d.batch;
+  int32_t* q_lens = nullptr;
+  if (ok && h[9]) {
+    q_lens = alloc_exact<int32_t>(d.batch);
+    ok = std::fread(q_lens, 4, d.batch, f) == (size_t)d.batch;
+    d.q_lens = q_lens;
+  }
   std::fclose(f);
   if (!ok) return 2;
   uint16_t* out = static_cast<uint16_t*>(std::aligned_alloc(16, n_rows * kDv * 2));
@@ -61,6 +68,6 @@ int main(int argc, char** argv) {
     std::fwrite(lse, 4, n_rows, f);
   }
   std::fclose(f);
-  std::free(q); std::free(kv); std::free(table); std::free(lens); std::free(out); std::free(lse); std::free(ws);
+  std::free(q); std::free(kv); std::free(table); std::free(lens); std::free(out); std::free(lse); std::free(ws); std::free(q_lens);
   return 0;
 }

@@ -27,10 +27,26 @@ def test_every_declared_symbol_is_exported(amla):
         assert getattr(amla.lib, name) is not None
 
 
-def test_desc_struct_layout_matches_header(amla):
-    # 12 int32 fields, then pointer, size_t, pointer on a 64-bit ABI
-    assert ctypes.sizeof(amla.AmlaDesc) == 12 * 4 + 3 * 8
+def test_desc_struct_layout_matches_header(amla, tmp_path):
+    # 12 int32 fields, then pointer, size_t, pointer, pointer on a 64-bit ABI
+    assert ctypes.sizeof(amla.AmlaDesc) == 12 * 4 + 4 * 8
     assert amla.AmlaDesc.workspace.offset == 48
+    # and as the C compiler lays the header's struct out
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    fields = [name for name, _ in amla.AmlaDesc._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "amla.h"\nint main(void) {\n'
+                   '  printf("%zu\\n", sizeof(amla_desc));\n'
+                   + "".join(f'  printf("%zu\\n", offsetof(amla_desc, {f}));\n' for f in fields)
+                   + "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got[0] == ctypes.sizeof(amla.AmlaDesc)
+    assert got[1:] == [getattr(amla.AmlaDesc, f).offset for f in fields]
 
 
 def test_status_strings(amla):

@@ -41,14 +41,16 @@ def exe(tmp_path_factory):
     return build(tmp_path_factory.mktemp("cpu_build"))
 
 
-def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0):
+def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0, q_lens=None):
     inp, outp = str(tmp_path / "in.bin"), str(tmp_path / "out.bin")
     with open(inp, "wb") as f:
         f.write(struct.pack("<12i", case.batch, case.s_q, case.heads, case.num_blocks, case.max_blocks_per_seq,
-                            variant, ns, flags, 0, 0, 0, 0))
+                            variant, ns, flags, 0, int(q_lens is not None), 0, 0))
         f.write(struct.pack("<f", case.softmax_scale))
         for a in (case.q_bits, case.kv_bits, case.block_table, case.seqlens):
             f.write(np.ascontiguousarray(a).tobytes())
+        if q_lens is not None:
+            f.write(np.ascontiguousarray(np.asarray(q_lens, np.int32)).tobytes())
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", AMLA_ENABLE_BALANCED="1")
     env.pop("LD_PRELOAD", None)
     env.pop("AMLA_ENABLE_ASM_KERNELS", None)
@@ -67,13 +69,13 @@ def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0):
     return out, lse, splits
 
 
-def check(out, lse, case, peaked=False, causal=False):
+def check(out, lse, case, peaked=False, causal=False, q_lens=None):
     """The GPU tests' bounds: |out error| <= 1e-2 where |exact| < 4, else half a bf16 step + 6e-3 for the
     rounding of the softmax weights; with `peaked` (query scale > 1: few keys carry the weight and the
     outputs reach several units) the second form everywhere, as in the GPU tests' wide-logit cases.
     |lse error| <= 1e-3."""
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
-                                causal=causal)
+                                causal=causal, q_lens=q_lens)
     fin = np.isfinite(want_lse)
     assert np.array_equal(lse[~fin], want_lse[~fin])
     half_ulp = 2.0 ** (np.ceil(np.log2(np.maximum(np.abs(want), 2.0 ** -20))) - 9)
@@ -159,6 +161,30 @@ def test_causal_mask_among_the_query_tokens(exe, tmp_path, kind, workers):
     # and the mask matters: the unmasked result differs
     plain, _ = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
     assert np.abs(out[4, 0] - plain[4, 0]).max() > 0.05
+
+
+@pytest.mark.parametrize("kind,workers,causal", [((MUL, 0), 0, False), ((ADD, 0), 3, True), ((ADD, LAZY), 5, False),
+                                                 ((COMP, 0), 2, True), ((MUL, LAZY), 9, True)])
+def test_per_sequence_query_counts(exe, tmp_path, kind, workers, causal):
+    """q_lens: sequences with all, some, one and none of the s_q = 4 tokens (40 heads: one wave holds rows
+    of two tokens, so real and padding rows share a wave), with and without the mask; padding rows come
+    back as zeros / -inf whatever the q array holds there."""
+    case = wl.make_case("qlens", 58, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 200, 130, 300], spare_frac=0.25)
+    q_lens = [4, 2, 3, 1, 0, 3, 4]
+    flags = kind[1] | (CAUSAL if causal else BALANCED)
+    out, lse, _ = run_cpu(exe, tmp_path, case, kind[0], flags=flags, ns=workers, q_lens=q_lens)
+    check(out, lse, case, causal=causal, q_lens=q_lens)
+    for b, k in enumerate(q_lens):
+        assert np.all(out[b, k:] == 0) and np.all(np.isneginf(lse[b, k:]))
+    # out-of-range counts are clamped into 0 .. s_q
+    wild = [9, -3, 3, 1, 0, 3, 4]
+    out2, lse2, _ = run_cpu(exe, tmp_path, case, kind[0], flags=flags, ns=workers, q_lens=wild)
+    check(out2, lse2, case, causal=causal, q_lens=[4, 0, 3, 1, 0, 3, 4])
+
+
+def test_query_counts_need_the_balanced_kernels(exe, tmp_path):
+    case = wl.make_config(0)
+    run_cpu(exe, tmp_path, case, ADD, q_lens=[1], expect_status=-2)
 
 
 def test_auto_split_of_a_long_single_sequence(exe, tmp_path):

@@ -93,6 +93,24 @@ def test_causal_mask_among_the_query_tokens(env, kind, workers):
     assert np.all(out[0, :3] == 0)
 
 
+@pytest.mark.parametrize("kind,workers,causal", [((MUL, 0), 0, False), ((ADD, 0), 3, True), ((ADD, LAZY), 5, False),
+                                                 ((MUL, LAZY), 9, True)])
+def test_per_sequence_query_counts(env, kind, workers, causal):
+    """desc->q_lens: sequences with all, some, one and none of the s_q = 4 tokens, real and padding rows
+    sharing a wave (40 heads), with and without the mask; padding rows come back as zeros / -inf."""
+    torch, orc, amla, wl = env
+    case = wl.make_case("qlens", 45, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 200, 130, 300], spare_frac=0.25)
+    q_lens = np.array([4, 2, 3, 1, 0, 3, 4], np.int32)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                                causal=causal, q_lens=q_lens)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=kind[0],
+                       flags=kind[1] | (CAUSAL if causal else BALANCED), num_splits=workers,
+                       q_lens=torch.from_numpy(q_lens).cuda())
+    check(out, lse, want, want_lse, f"q_lens workers={workers} causal={causal} {kind}")
+    for b, k in enumerate(q_lens):
+        assert np.all(out[b, k:] == 0) and np.all(np.isneginf(lse[b, k:]))
+
+
 def test_causal_headline_shape_rows_match_shorter_caches(env):
     """At the headline shape (batch 128, s_q 2, 128 heads, kv 4096) the first token under the mask equals
     the unmasked run on caches one key shorter, the second token is unchanged."""
