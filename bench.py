@@ -37,8 +37,10 @@ def parse():
     ap.add_argument("--balanced", action="store_true",
                     help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
                          "means workers)")
-    ap.add_argument("--variant", choices=["auto", "add", "mul", "add_lazy", "mul_lazy", "add_comp", "add_ldexp", "add_ldexp_lazy"], default="auto",
-                    help="auto = the fastest exponent-add variant whose output agrees with the strict add variant on this input")
+    _names = ["add", "mul", "add_lazy", "mul_lazy", "add_ldexp", "add_ldexp_lazy"]
+    ap.add_argument("--variant", choices=["auto", "add_comp"] + _names + [n + "_pf" for n in _names], default="auto",
+                    help="auto = the fastest exponent-add variant whose output agrees with the strict add variant on this "
+                         "input; _pf = the loop that issues its LDS operand reads one MFMA ahead")
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
                     help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
                          "s_q SQ, every sequence SK keys, contiguous cache")
@@ -146,6 +148,17 @@ def main():
                 "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0),
                 "add_ldexp": (amla.AMLA_RESCALE_ADD_LDEXP, 0),
                 "add_ldexp_lazy": (amla.AMLA_RESCALE_ADD_LDEXP, amla.AMLA_FLAG_LAZY_RESCALE)}
+    # "_pf": the build of the compiler kernels' loop that issues its LDS operand reads one MFMA ahead
+    # (same arithmetic in the same order); equal-share compiler-built kernels only
+    PREFETCHABLE = ("mul", "add", "mul_lazy", "add_lazy", "add_ldexp", "add_ldexp_lazy")
+    have_pf = args.impl == "compiler" and not args.balanced
+    if have_pf:
+        for name in PREFETCHABLE:
+            v, f = VARIANTS[name]
+            VARIANTS[name + "_pf"] = (v, f | amla.AMLA_FLAG_PREFETCH)
+    if args.variant not in VARIANTS and args.variant != "auto":
+        print(f"bench.py: variant {args.variant} does not exist for this --impl / --balanced", file=sys.stderr)
+        sys.exit(2)
 
     def step(name, o=out, l=lse):
         v, f = VARIANTS[name]
@@ -174,6 +187,8 @@ def main():
                 others.append("add_comp")
             if args.impl == "asm" or not args.balanced:
                 others += ["add_ldexp", "add_ldexp_lazy"]
+            if have_pf:
+                others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf"]
             for name in others:
                 try:
                     step(name, o2, l2)
@@ -221,7 +236,8 @@ def main():
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "amla_decode_kernel" if args.impl == "compiler" else "amla_decode_asm_" + chosen,
+                     "kernel": ("amla_decode_asm_" + chosen) if args.impl == "asm" else
+                               ("amla_decode_prefetch_kernel" if chosen.endswith("_pf") else "amla_decode_kernel"),
                      "kernel_ms": kern_ms,
                      "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": abytes,
                      "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
@@ -234,7 +250,8 @@ def main():
         try:
             ab = {}
             names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
-                (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ())
+                (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ()) + \
+                (tuple(n + "_pf" for n in PREFETCHABLE) if have_pf else ())
             for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)
@@ -247,7 +264,7 @@ def main():
                                  "note": "interleaved runs, best of 2 per variant, same binary; strict = "
                                          "reference moves with every new row max, lazy = only past 2^8, "
                                          "add_comp = Algorithm 2 with its BF16 scale compensation, add_ldexp = the exponent add "
-                                         "done by v_ldexp_f32"}
+                                         "done by v_ldexp_f32, _pf = LDS operand reads issued one MFMA ahead"}
         except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
             notes.append(f"rescale side-by-side failed: {e!r}")
 

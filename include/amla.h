@@ -91,7 +91,7 @@ enum {
                                    rejected with AMLA_ERR_UNSUPPORTED unless the environment variable
                                    AMLA_ENABLE_BALANCED is "1", because this index arithmetic has not
                                    yet run on hardware. */
-  AMLA_FLAG_CAUSAL = 16         /* causal mask among the s_q query tokens of a sequence (multi-token
+  AMLA_FLAG_CAUSAL = 16,        /* causal mask among the s_q query tokens of a sequence (multi-token
                                    prediction: the s_q tokens are the last s_q positions of the cache):
                                    token t attends to keys 0 .. kv_len - s_q + t, i.e. to
                                    kv_len - (s_q - 1 - t) keys; a token whose limit is <= 0 gets
@@ -99,6 +99,12 @@ enum {
                                    kv_len keys.  Runs in the compiler-built balanced kernels (implies
                                    AMLA_FLAG_BALANCED, is switched off with it, and cannot be
                                    combined with AMLA_FLAG_ASM_KERNEL). */
+  AMLA_FLAG_PREFETCH = 32       /* compiler-built equal-share kernels with the LDS operand reads of both
+                                   products issued one MFMA ahead of their use.  Same arithmetic in the
+                                   same order, so the same result bit for bit; MUL, ADD and ADD_LDEXP
+                                   variants, with or without AMLA_FLAG_LAZY_RESCALE; not with
+                                   AMLA_FLAG_ASM_KERNEL, AMLA_FLAG_BALANCED, AMLA_FLAG_CAUSAL or
+                                   AMLA_RESCALE_ADD_COMP. */
 };
 
 typedef struct amla_desc {

@@ -25,6 +25,7 @@ AMLA_FLAG_LAZY_RESCALE = 2
 AMLA_FLAG_ASM_KERNEL = 4
 AMLA_FLAG_BALANCED = 8
 AMLA_FLAG_CAUSAL = 16
+AMLA_FLAG_PREFETCH = 32
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
            "amla_mfma_probe", "amla_plan_segments", "amla_preload_rotation", "amla_status_string")

@@ -1,6 +1,7 @@
 // Absorbed-MLA decode attention for gfx950 (MI355X): kernels and the C-ABI entry points.
-// Device code: amla_decode_kernels.inc (kernels, included below) and amla_decode_piece.inc (the body
-// of the decode loop, shared by the equal-share and the balanced kernel); amla_plan.h holds the
+// Device code: amla_decode_kernels.inc (kernels, included below), amla_decode_equal_share.inc (the
+// equal-share kernel, built twice: plain and prefetching) and amla_decode_piece.inc (the body of the
+// decode loop, shared by the equal-share and the balanced kernels); amla_plan.h holds the
 // balanced decomposition's integer arithmetic; this file holds the host side.
 //
 // One workgroup (4 waves, one per SIMD, up to 512 VGPRs each) owns 128 query rows of one
@@ -162,7 +163,12 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
-                    AMLA_FLAG_CAUSAL)) != 0)
+                    AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH)) != 0)
+    return false;
+  // the prefetching build of the loop exists for the equal-share compiler-built kernels (the compensated
+  // instantiation spills ~90 registers with it and is left out)
+  if ((d->flags & AMLA_FLAG_PREFETCH) &&
+      ((d->flags & AMLA_FLAG_ASM_KERNEL) || uses_balanced(d) || d->variant == AMLA_RESCALE_ADD_COMP))
     return false;
   if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
   if (uses_balanced(d) && !balanced_enabled()) return false;
@@ -269,7 +275,14 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
     const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
     void (*kern)(const DecodeParams) = nullptr;
-    if (!balanced) {
+    if (desc->flags & AMLA_FLAG_PREFETCH) {
+      kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
+                 ? (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_ADD_LDEXP, true>
+                         : amla_decode_prefetch_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
+             : desc->variant == AMLA_RESCALE_ADD
+                 ? (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_ADD, true> : amla_decode_prefetch_kernel<AMLA_RESCALE_ADD, false>)
+                 : (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_MUL, true> : amla_decode_prefetch_kernel<AMLA_RESCALE_MUL, false>);
+    } else if (!balanced) {
       kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
              : desc->variant == AMLA_RESCALE_ADD_LDEXP
                  ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, false>)

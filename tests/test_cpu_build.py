@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SHIM = os.path.join(ROOT, "tests", "cpu_build")
 CLANG = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang++")
 MUL, ADD, COMP, LDEXP = 0, 1, 2, 3
-NO_SKIP, LAZY, ASM, BALANCED, CAUSAL = 1, 2, 4, 8, 16
+NO_SKIP, LAZY, ASM, BALANCED, CAUSAL, PREFETCH = 1, 2, 4, 8, 16, 32
 FLAGS = ["-std=c++20", "-O0", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
          "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi"]
 
@@ -97,6 +97,28 @@ def test_tiny_config(exe, tmp_path, kind):
     out, lse, splits = run_cpu(exe, tmp_path, case, kind[0], flags=kind[1])
     assert splits == 1
     check(out, lse, case)
+
+
+@pytest.mark.parametrize("kind", [k for k in KINDS if k.values[0][0] != COMP])
+def test_prefetching_build_of_the_loop_is_bit_identical(exe, tmp_path, kind):
+    """AMLA_FLAG_PREFETCH moves the LDS operand reads one MFMA ahead and nothing else: same bits, on a
+    ragged split case (partial last block, an empty share, rows past the end of the row range)."""
+    variant, flags = kind
+    case = _ragged(63)
+    a = run_cpu(exe, tmp_path, case, variant, flags=flags, ns=3)
+    b = run_cpu(exe, tmp_path, case, variant, flags=flags | PREFETCH, ns=3)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    check(b[0], b[1], case)
+    tiny = wl.make_config(0)
+    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=flags | PREFETCH)
+    check(out, lse, tiny)
+
+
+def test_prefetch_is_rejected_where_it_does_not_exist(exe, tmp_path):
+    case = wl.make_config(0)
+    run_cpu(exe, tmp_path, case, COMP, flags=PREFETCH, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=PREFETCH | BALANCED, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=PREFETCH | CAUSAL, expect_status=-2)
 
 
 def _ragged(seed, heads=80):
@@ -294,7 +316,8 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
         pytest.skip("no clang++ to build the CPU harness with")
     csrc = tmp_path / "paper_2509_25224_amd" / "csrc"
     csrc.mkdir(parents=True)
-    for name in ("amla_decode.hip", "amla_decode_kernels.inc", "amla_decode_piece.inc", "amla_plan.h"):
+    for name in ("amla_decode.hip", "amla_decode_kernels.inc", "amla_decode_equal_share.inc", "amla_decode_piece.inc",
+                 "amla_plan.h"):
         shutil.copy(os.path.join(ROOT, "paper_2509_25224_amd", "csrc", name), csrc / name)
     piece = (csrc / "amla_decode_piece.inc").read_text()
     barrier = "  // the previous piece's last tile may still be read by a slower wave\n  __syncthreads();\n"
