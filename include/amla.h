@@ -100,7 +100,7 @@ enum {
                                    AMLA_FLAG_BALANCED, is switched off with it, and cannot be
                                    combined with AMLA_FLAG_ASM_KERNEL). */
   AMLA_FLAG_PREFETCH = 32       /* compiler-built equal-share kernels with the LDS operand reads of both
-                                   products issued one MFMA ahead of their use.  Same arithmetic in the
+                                   products issued one to two MFMAs ahead of their use.  Same arithmetic in the
                                    same order, so the same result bit for bit; MUL, ADD and ADD_LDEXP
                                    variants, with or without AMLA_FLAG_LAZY_RESCALE; not with
                                    AMLA_FLAG_ASM_KERNEL, AMLA_FLAG_BALANCED, AMLA_FLAG_CAUSAL or

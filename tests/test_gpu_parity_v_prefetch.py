@@ -1,5 +1,5 @@
 """GPU parity of the prefetching build of the compiler kernels' loop (AMLA_FLAG_PREFETCH: the LDS operand
-reads of both products issued one MFMA ahead of their use).  The arithmetic and its order are those of the
+reads of both products issued ahead of their use).  The arithmetic and its order are those of the
 plain kernels, so each case is checked twice: against the oracle with the usual bounds, and bit for bit
 against the plain kernel of the same variant.  Collected after the files whose cases have run on the GPU."""
 import numpy as np
