@@ -38,9 +38,10 @@ def parse():
                     help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
                          "means workers)")
     _names = ["add", "mul", "add_lazy", "mul_lazy", "add_ldexp", "add_ldexp_lazy"]
-    ap.add_argument("--variant", choices=["auto", "add_comp"] + _names + [n + "_pf" for n in _names], default="auto",
+    ap.add_argument("--variant", choices=["auto", "add_comp"] + _names + [n + "_pf" for n in _names] + [n + "_w8" for n in _names],
+                    default="auto",
                     help="auto = the fastest exponent-add variant whose output agrees with the strict add variant on this "
-                         "input; _pf = the loop that issues its LDS operand reads one MFMA ahead")
+                         "input; _pf = the loop that issues its LDS operand reads ahead of their MFMA; _w8 = the eight-wave kernel")
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
                     help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
                          "s_q SQ, every sequence SK keys, contiguous cache")
@@ -156,6 +157,10 @@ def main():
         for name in PREFETCHABLE:
             v, f = VARIANTS[name]
             VARIANTS[name + "_pf"] = (v, f | amla.AMLA_FLAG_PREFETCH)
+        # "_w8": the eight-wave kernel (16 rows per wave, two waves per SIMD, 16 x 16 x 32 MFMA)
+        for name in PREFETCHABLE:
+            v, f = VARIANTS[name]
+            VARIANTS[name + "_w8"] = (v, f | amla.AMLA_FLAG_EIGHT_WAVES)
     if args.variant not in VARIANTS and args.variant != "auto":
         print(f"bench.py: variant {args.variant} does not exist for this --impl / --balanced", file=sys.stderr)
         sys.exit(2)
@@ -188,7 +193,8 @@ def main():
             if args.impl == "asm" or not args.balanced:
                 others += ["add_ldexp", "add_ldexp_lazy"]
             if have_pf:
-                others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf"]
+                others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf",
+                           "add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8"]
             for name in others:
                 try:
                     step(name, o2, l2)
@@ -237,7 +243,8 @@ def main():
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "kernel": ("amla_decode_asm_" + chosen) if args.impl == "asm" else
-                               ("amla_decode_prefetch_kernel" if chosen.endswith("_pf") else "amla_decode_kernel"),
+                               ("amla_decode_prefetch_kernel" if chosen.endswith("_pf") else
+                                "amla_decode_w8_kernel" if chosen.endswith("_w8") else "amla_decode_kernel"),
                      "kernel_ms": kern_ms,
                      "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": abytes,
                      "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
@@ -251,7 +258,7 @@ def main():
             ab = {}
             names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
                 (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ()) + \
-                (tuple(n + "_pf" for n in PREFETCHABLE) if have_pf else ())
+                (tuple(n + sfx for sfx in ("_pf", "_w8") for n in PREFETCHABLE) if have_pf else ())
             for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)
@@ -264,7 +271,8 @@ def main():
                                  "note": "interleaved runs, best of 2 per variant, same binary; strict = "
                                          "reference moves with every new row max, lazy = only past 2^8, "
                                          "add_comp = Algorithm 2 with its BF16 scale compensation, add_ldexp = the exponent add "
-                                         "done by v_ldexp_f32, _pf = LDS operand reads issued one MFMA ahead"}
+                                         "done by v_ldexp_f32, _pf = LDS operand reads issued ahead of their MFMA, _w8 = eight waves of "
+                                         "16 rows with the 16 x 16 x 32 MFMA"}
         except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
             notes.append(f"rescale side-by-side failed: {e!r}")
 

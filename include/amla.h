@@ -99,11 +99,20 @@ enum {
                                    kv_len keys.  Runs in the compiler-built balanced kernels (implies
                                    AMLA_FLAG_BALANCED, is switched off with it, and cannot be
                                    combined with AMLA_FLAG_ASM_KERNEL). */
-  AMLA_FLAG_PREFETCH = 32       /* compiler-built equal-share kernels with the LDS operand reads of both
+  AMLA_FLAG_PREFETCH = 32,      /* compiler-built equal-share kernels with the LDS operand reads of both
                                    products issued one to two MFMAs ahead of their use.  Same arithmetic in the
                                    same order, so the same result bit for bit; MUL, ADD and ADD_LDEXP
                                    variants, with or without AMLA_FLAG_LAZY_RESCALE; not with
                                    AMLA_FLAG_ASM_KERNEL, AMLA_FLAG_BALANCED, AMLA_FLAG_CAUSAL or
+                                   AMLA_RESCALE_ADD_COMP. */
+  AMLA_FLAG_EIGHT_WAVES = 64    /* compiler-built equal-share kernel with eight waves of 16 rows per
+                                   128-row workgroup (two waves per SIMD) and the 16 x 16 x 32 MFMA: the
+                                   per-wave accumulator and Q fragment fit the architectural VGPRs, and
+                                   one wave's MFMAs run under the other's LDS waits and softmax.  Same
+                                   method and roundings as the default kernels, different summation
+                                   order inside the products.  MUL, ADD and ADD_LDEXP variants, with or
+                                   without AMLA_FLAG_LAZY_RESCALE; not with AMLA_FLAG_ASM_KERNEL,
+                                   AMLA_FLAG_BALANCED, AMLA_FLAG_CAUSAL, AMLA_FLAG_PREFETCH or
                                    AMLA_RESCALE_ADD_COMP. */
 };
 

@@ -1,7 +1,8 @@
 // Absorbed-MLA decode attention for gfx950 (MI355X): kernels and the C-ABI entry points.
 // Device code: amla_decode_kernels.inc (kernels, included below), amla_decode_equal_share.inc (the
-// equal-share kernel, built twice: plain and prefetching) and amla_decode_piece.inc (the body of the
-// decode loop, shared by the equal-share and the balanced kernels); amla_plan.h holds the
+// equal-share kernel, built twice: plain and prefetching), amla_decode_piece.inc (the body of the
+// decode loop, shared by the equal-share and the balanced kernels) and amla_decode_w8.inc (the
+// eight-wave equal-share kernel); amla_plan.h holds the
 // balanced decomposition's integer arithmetic; this file holds the host side.
 //
 // One workgroup (4 waves, one per SIMD, up to 512 VGPRs each) owns 128 query rows of one
@@ -163,7 +164,11 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
-                    AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH)) != 0)
+                    AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES)) != 0)
+    return false;
+  // the eight-wave kernel is an equal-share compiler-built kernel of its own
+  if ((d->flags & AMLA_FLAG_EIGHT_WAVES) &&
+      ((d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH)) || uses_balanced(d) || d->variant == AMLA_RESCALE_ADD_COMP))
     return false;
   // the prefetching build of the loop exists for the equal-share compiler-built kernels (the compensated
   // instantiation spills ~90 registers with it and is left out)
@@ -275,7 +280,15 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
     const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
     void (*kern)(const DecodeParams) = nullptr;
-    if (desc->flags & AMLA_FLAG_PREFETCH) {
+    int threads = kThreads;
+    if (desc->flags & AMLA_FLAG_EIGHT_WAVES) {
+      threads = kThreadsW8;
+      kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
+                 ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
+             : desc->variant == AMLA_RESCALE_ADD
+                 ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD, false>)
+                 : (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_MUL, true> : amla_decode_w8_kernel<AMLA_RESCALE_MUL, false>);
+    } else if (desc->flags & AMLA_FLAG_PREFETCH) {
       kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
                  ? (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_ADD_LDEXP, true>
                          : amla_decode_prefetch_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
@@ -297,7 +310,7 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
                                                              : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
     }
     if (!allow_large_lds(reinterpret_cast<const void*>(kern))) return AMLA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), kLdsBytes, stream, p);
     if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   } else {
     // index arithmetic of the assembly kernels: mulhi-by-magic division and 32-bit row indices

@@ -141,6 +141,28 @@ inline C mfma_32x32x16_bf16(AB a, AB b, C c, int, int, int) {
   return c;
 }
 
+// v_mfma_f32_16x16x32_bf16 with the operand layouts the CDNA4 ISA documents (not measured by this
+// build): A lane l holds row l%16, k = 8*(l/16)+0..7; B lane l holds column l%16, same k; C/D register
+// r of lane l is row 4*(l/16) + r, column l%16.
+template <class AB, class C>
+inline C mfma_16x16x32_bf16(AB a, AB b, C c, int, int, int) {
+  struct Frag {
+    AB a, b;
+  } mine = {a, b};
+  auto all = exchange(mine);
+  const int col = lane & 15, grp = lane >> 4;
+  for (int r = 0; r < 4; ++r) {
+    const int row = 4 * grp + r;
+    double acc = 0.0;
+    for (int kg = 0; kg < 4; ++kg) {
+      const Frag fr = peer<Frag>(all, row + 16 * kg), fc = peer<Frag>(all, col + 16 * kg);
+      for (int e = 0; e < 8; ++e) acc += (double)(float)fr.a[e] * (double)(float)fc.b[e];
+    }
+    c[r] = (float)((double)c[r] + acc);
+  }
+  return c;
+}
+
 template <class V4>
 inline V4 ds_read_tr16_b64(V4* p) {
   V4 mine;
@@ -277,6 +299,7 @@ inline hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned gx, unsigned g
 #define __builtin_amdgcn_readlane(v, l) shim::readlane((v), (l))
 #define __builtin_amdgcn_ballot_w64(p) shim::ballot((p))
 #define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) shim::mfma_32x32x16_bf16((a), (b), (c), (x), (y), (z))
+#define __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, x, y, z) shim::mfma_16x16x32_bf16((a), (b), (c), (x), (y), (z))
 #define __builtin_amdgcn_ds_read_tr16_b64_v4i16(p) shim::ds_read_tr16_b64((p))
 #define __builtin_amdgcn_global_load_lds(g, l, n, o, a) shim::global_load_lds((g), (l), (n), (o), (a))
 #define __builtin_amdgcn_sched_barrier(x) ((void)0)
@@ -300,5 +323,6 @@ inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); 
 #endif
 #define AMLA_OPAQUE(x) ((void)(x))
 #define AMLA_ONE_WAVE_PER_SIMD
+#define AMLA_TWO_WAVES_PER_SIMD
 
 #endif  // AMLA_TESTS_HIP_RUNTIME_SHIM_H_

@@ -65,7 +65,7 @@ def test_argument_validation_error_codes(amla):
     assert _call(amla, good, out=None) == amla.AMLA_ERR_NULL_ARG
     assert amla.lib.amla_decode(16, 16, 16, 16, 0.1, 16, None, None) == amla.AMLA_ERR_NULL_ARG
     for field, val in (("d_qk", 512), ("d_v", 576), ("block_size", 128), ("batch", 0), ("s_q", 0),
-                       ("num_heads", 0), ("variant", 7), ("num_splits", -1), ("flags", 128), ("reserved", 1)):
+                       ("num_heads", 0), ("variant", 7), ("num_splits", -1), ("flags", 256), ("reserved", 1)):
         d = amla.make_desc(2, 1, 16, 8, 4)
         setattr(d, field, val)
         assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED, field

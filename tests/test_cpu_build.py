@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SHIM = os.path.join(ROOT, "tests", "cpu_build")
 CLANG = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang++")
 MUL, ADD, COMP, LDEXP = 0, 1, 2, 3
-NO_SKIP, LAZY, ASM, BALANCED, CAUSAL, PREFETCH = 1, 2, 4, 8, 16, 32
+NO_SKIP, LAZY, ASM, BALANCED, CAUSAL, PREFETCH, W8 = 1, 2, 4, 8, 16, 32, 64
 FLAGS = ["-std=c++20", "-O0", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
          "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi"]
 
@@ -112,6 +112,43 @@ def test_prefetching_build_of_the_loop_is_bit_identical(exe, tmp_path, kind):
     tiny = wl.make_config(0)
     out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=flags | PREFETCH)
     check(out, lse, tiny)
+
+
+NO_COMP = [k for k in KINDS if k.values[0][0] != COMP]
+
+
+@pytest.mark.parametrize("kind", NO_COMP)
+def test_eight_wave_kernel(exe, tmp_path, kind):
+    """AMLA_FLAG_EIGHT_WAVES (16 rows per wave, 16 x 16 x 32 MFMA): the tiny configuration; the ragged
+    case unsplit and in three shares (partial last blocks, an empty sequence and an empty share, a second
+    row tile with 32 of 128 rows valid); wide logits that move the reference several times."""
+    variant, flags = kind
+    tiny = wl.make_config(0)
+    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=flags | W8)
+    check(out, lse, tiny)
+    case = _ragged(64)
+    for ns in (1, 3):
+        out, lse, splits = run_cpu(exe, tmp_path, case, variant, flags=flags | W8, ns=ns)
+        assert splits == ns
+        check(out, lse, case)
+        assert np.all(out[2] == 0) and np.all(np.isneginf(lse[2]))
+    wide = wl.make_case("wide8", 66, batch=1, s_q=1, heads=16, seqlens=[700], q_sigma=6.0)
+    out, lse, _ = run_cpu(exe, tmp_path, wide, variant, flags=flags | W8)
+    check(out, lse, wide, peaked=True)
+
+
+def test_eight_wave_kernel_no_skip_flag_changes_nothing(exe, tmp_path):
+    case = wl.make_case("noskip8", 67, batch=1, s_q=1, heads=8, seqlens=[200])
+    a = run_cpu(exe, tmp_path, case, ADD, flags=W8)
+    b = run_cpu(exe, tmp_path, case, ADD, flags=W8 | NO_SKIP)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_eight_waves_are_rejected_where_they_do_not_exist(exe, tmp_path):
+    case = wl.make_config(0)
+    run_cpu(exe, tmp_path, case, COMP, flags=W8, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=W8 | BALANCED, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=W8 | PREFETCH, expect_status=-2)
 
 
 def test_prefetch_is_rejected_where_it_does_not_exist(exe, tmp_path):
@@ -317,7 +354,7 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
     csrc = tmp_path / "paper_2509_25224_amd" / "csrc"
     csrc.mkdir(parents=True)
     for name in ("amla_decode.hip", "amla_decode_kernels.inc", "amla_decode_equal_share.inc", "amla_decode_piece.inc",
-                 "amla_plan.h"):
+                 "amla_decode_w8.inc", "amla_plan.h"):
         shutil.copy(os.path.join(ROOT, "paper_2509_25224_amd", "csrc", name), csrc / name)
     piece = (csrc / "amla_decode_piece.inc").read_text()
     barrier = "  // the previous piece's last tile may still be read by a slower wave\n  __syncthreads();\n"
