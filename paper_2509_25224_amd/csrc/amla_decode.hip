@@ -1,8 +1,9 @@
 // Absorbed-MLA decode attention for gfx950 (MI355X): kernels and the C-ABI entry points.
 // Device code: amla_decode_kernels.inc (kernels, included below), amla_decode_equal_share.inc (the
 // equal-share kernel, built twice: plain and prefetching), amla_decode_piece.inc (the body of the
-// decode loop, shared by the equal-share and the balanced kernels) and amla_decode_w8.inc (the
-// eight-wave equal-share kernel); amla_plan.h holds the
+// decode loop, shared by the equal-share and the balanced kernels), amla_decode_balanced.inc (the
+// balanced walk, built once per wave shape) and amla_decode_w8.inc / amla_decode_w8_piece.inc (the
+// eight-wave kernels and their loop body); amla_plan.h holds the
 // balanced decomposition's integer arithmetic; this file holds the host side.
 //
 // One workgroup (4 waves, one per SIMD, up to 512 VGPRs each) owns 128 query rows of one
@@ -89,7 +90,7 @@ const DeviceKernels* device_kernels() {
 // The decode kernels use more dynamic LDS than a launch may ask for by default; the attribute that
 // allows it is set once per kernel and device, on the first call, so that later calls (for instance
 // under stream capture) consist of launches only.
-constexpr int kMaxDecodeKernels = 32;
+constexpr int kMaxDecodeKernels = 64;
 const void* g_lds_ok[kMaxDevices][kMaxDecodeKernels];
 std::mutex g_lds_ok_mutex;
 
@@ -158,17 +159,19 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD && d->variant != AMLA_RESCALE_ADD_COMP &&
       d->variant != AMLA_RESCALE_ADD_LDEXP)
     return false;
-  // ldexp rescale with the balanced decomposition: hand-scheduled kernels only (this compiler's AGPR-copy
-  // rewrite pass crashes on the balanced compiler-built instantiation)
-  if (d->variant == AMLA_RESCALE_ADD_LDEXP && uses_balanced(d) && !(d->flags & AMLA_FLAG_ASM_KERNEL)) return false;
+  // ldexp rescale with the balanced decomposition: hand-scheduled and eight-wave kernels only (this
+  // compiler's AGPR-copy rewrite pass crashes on the balanced four-wave instantiation)
+  if (d->variant == AMLA_RESCALE_ADD_LDEXP && uses_balanced(d) &&
+      !(d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_EIGHT_WAVES)))
+    return false;
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
                     AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES)) != 0)
     return false;
-  // the eight-wave kernel is an equal-share compiler-built kernel of its own
+  // the eight-wave kernels are compiler-built kernels of their own (equal-share and balanced)
   if ((d->flags & AMLA_FLAG_EIGHT_WAVES) &&
-      ((d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH)) || uses_balanced(d) || d->variant == AMLA_RESCALE_ADD_COMP))
+      ((d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH)) || d->variant == AMLA_RESCALE_ADD_COMP))
     return false;
   // the prefetching build of the loop exists for the equal-share compiler-built kernels (the compensated
   // instantiation spills ~90 registers with it and is left out)
@@ -281,7 +284,15 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
     void (*kern)(const DecodeParams) = nullptr;
     int threads = kThreads;
-    if (desc->flags & AMLA_FLAG_EIGHT_WAVES) {
+    if ((desc->flags & AMLA_FLAG_EIGHT_WAVES) && balanced) {
+      threads = kThreadsW8;
+      kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
+                 ? (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_LDEXP, true>
+                         : amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
+             : desc->variant == AMLA_RESCALE_ADD
+                 ? (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD, true> : amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD, false>)
+                 : (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_MUL, true> : amla_decode_w8_balanced_kernel<AMLA_RESCALE_MUL, false>);
+    } else if (desc->flags & AMLA_FLAG_EIGHT_WAVES) {
       threads = kThreadsW8;
       kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
                  ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, false>)

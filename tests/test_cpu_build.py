@@ -147,8 +147,33 @@ def test_eight_wave_kernel_no_skip_flag_changes_nothing(exe, tmp_path):
 def test_eight_waves_are_rejected_where_they_do_not_exist(exe, tmp_path):
     case = wl.make_config(0)
     run_cpu(exe, tmp_path, case, COMP, flags=W8, expect_status=-2)
-    run_cpu(exe, tmp_path, case, ADD, flags=W8 | BALANCED, expect_status=-2)
+    run_cpu(exe, tmp_path, case, COMP, flags=W8 | BALANCED, expect_status=-2)
     run_cpu(exe, tmp_path, case, ADD, flags=W8 | PREFETCH, expect_status=-2)
+
+
+@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, 0), 3), ((ADD, LAZY), 7), ((LDEXP, 0), 41),
+                                          ((LDEXP, LAZY), 2), ((MUL, LAZY), 11)])
+def test_eight_wave_balanced_kernels(exe, tmp_path, kind, workers):
+    """The eight-wave build of the balanced kernels on the cases of the four-wave one: the ragged batch
+    over worker counts below, at and above the number of sequences and blocks; the causal mask around
+    block boundaries; per-sequence query counts with and without the mask."""
+    variant, flags = kind
+    case = _ragged(68)
+    out, lse, splits = run_cpu(exe, tmp_path, case, variant, flags=flags | W8 | BALANCED, ns=workers)
+    assert splits == (workers if workers else min(128, case.batch * case.max_blocks_per_seq))
+    check(out, lse, case)
+    assert np.all(out[2] == 0)
+    causal = wl.make_case("causal8", 69, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
+    out, lse, _ = run_cpu(exe, tmp_path, causal, variant, flags=flags | W8 | CAUSAL, ns=workers)
+    check(out, lse, causal, causal=True)
+    assert np.all(out[0, :3] == 0) and np.all(np.isneginf(lse[0, :3]))
+    q_lens = [4, 2, 3, 1, 0, 3, 4]
+    for masked in (False, True):
+        out, lse, _ = run_cpu(exe, tmp_path, causal, variant, flags=flags | W8 | (CAUSAL if masked else BALANCED),
+                              ns=workers, q_lens=q_lens)
+        check(out, lse, causal, causal=masked, q_lens=q_lens)
+        for b, k in enumerate(q_lens):
+            assert np.all(out[b, k:] == 0) and np.all(np.isneginf(lse[b, k:]))
 
 
 def test_prefetch_is_rejected_where_it_does_not_exist(exe, tmp_path):
@@ -354,7 +379,7 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
     csrc = tmp_path / "paper_2509_25224_amd" / "csrc"
     csrc.mkdir(parents=True)
     for name in ("amla_decode.hip", "amla_decode_kernels.inc", "amla_decode_equal_share.inc", "amla_decode_piece.inc",
-                 "amla_decode_w8.inc", "amla_plan.h"):
+                 "amla_decode_w8.inc", "amla_decode_w8_piece.inc", "amla_decode_balanced.inc", "amla_plan.h"):
         shutil.copy(os.path.join(ROOT, "paper_2509_25224_amd", "csrc", name), csrc / name)
     piece = (csrc / "amla_decode_piece.inc").read_text()
     barrier = "  // the previous piece's last tile may still be read by a slower wave\n  __syncthreads();\n"

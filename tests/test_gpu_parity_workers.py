@@ -111,6 +111,33 @@ def test_per_sequence_query_counts(env, kind, workers, causal):
         assert np.all(out[b, k:] == 0) and np.all(np.isneginf(lse[b, k:]))
 
 
+W8 = 64
+LDEXP = 3
+
+
+@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, 0), 3), ((ADD, LAZY), 7), ((LDEXP, 0), 41),
+                                          ((LDEXP, LAZY), 2), ((MUL, LAZY), 11)])
+def test_eight_wave_balanced_kernels(env, kind, workers):
+    """AMLA_FLAG_EIGHT_WAVES with the balanced decomposition: the ragged batch, the causal mask around block
+    boundaries, per-sequence query counts with and without the mask."""
+    torch, orc, amla, wl = env
+    variant, flags = kind
+    case = wl.make_case("edges", 46, batch=7, s_q=2, heads=80, seqlens=[1, 63, 0, 64, 65, 200, 330], spare_frac=0.25)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant, flags=flags | W8 | BALANCED,
+                       num_splits=workers)
+    check(out, lse, want, want_lse, f"eight waves balanced workers={workers} {kind}")
+    causal = wl.make_case("causal8", 47, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
+    dev = to_dev(torch, causal)
+    q_lens = np.array([4, 2, 3, 1, 0, 3, 4], np.int32)
+    for masked, counts in ((True, None), (False, q_lens), (True, q_lens)):
+        want, want_lse = orc.decode(causal.q_bits, causal.kv_bits, causal.block_table, causal.seqlens,
+                                    causal.softmax_scale, causal=masked, q_lens=counts)
+        out, lse = run_gpu(torch, amla, causal, dev, variant=variant, flags=flags | W8 | (CAUSAL if masked else BALANCED),
+                           num_splits=workers, q_lens=None if counts is None else torch.from_numpy(counts).cuda())
+        check(out, lse, want, want_lse, f"eight waves masked={masked} q_lens={counts is not None} workers={workers} {kind}")
+
+
 def test_causal_headline_shape_rows_match_shorter_caches(env):
     """At the headline shape (batch 128, s_q 2, 128 heads, kv 4096) the first token under the mask equals
     the unmasked run on caches one key shorter, the second token is unchanged."""
