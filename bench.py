@@ -157,7 +157,10 @@ def main():
         for name in PREFETCHABLE:
             v, f = VARIANTS[name]
             VARIANTS[name + "_pf"] = (v, f | amla.AMLA_FLAG_PREFETCH)
-        # "_w8": the eight-wave kernel (16 rows per wave, two waves per SIMD, 16 x 16 x 32 MFMA)
+    # "_w8": the eight-wave kernels (16 rows per wave, two waves per SIMD, 16 x 16 x 32 MFMA), equal-share
+    # or balanced
+    have_w8 = args.impl == "compiler"
+    if have_w8:
         for name in PREFETCHABLE:
             v, f = VARIANTS[name]
             VARIANTS[name + "_w8"] = (v, f | amla.AMLA_FLAG_EIGHT_WAVES)
@@ -193,8 +196,9 @@ def main():
             if args.impl == "asm" or not args.balanced:
                 others += ["add_ldexp", "add_ldexp_lazy"]
             if have_pf:
-                others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf",
-                           "add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8"]
+                others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf"]
+            if have_w8:
+                others += ["add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8"]
             for name in others:
                 try:
                     step(name, o2, l2)
@@ -258,7 +262,8 @@ def main():
             ab = {}
             names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
                 (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ()) + \
-                (tuple(n + sfx for sfx in ("_pf", "_w8") for n in PREFETCHABLE) if have_pf else ())
+                (tuple(n + "_pf" for n in PREFETCHABLE) if have_pf else ()) + \
+                (tuple(n + "_w8" for n in PREFETCHABLE) if have_w8 else ())
             for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)
