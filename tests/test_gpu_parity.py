@@ -85,12 +85,14 @@ def describe_mismatch(out, lse, want, want_lse, what):
                      f"{int(np.isnan(lse).sum())} NaN")
     text = "\n".join(lines)
     print(text, flush=True)
-    try:
-        os.makedirs("gpurun_out", exist_ok=True)
-        with open(os.path.join("gpurun_out", "mismatch_report.txt"), "a") as f:
-            f.write(text + "\n")
-    except OSError:
-        pass
+    report_dir = os.environ.get("AMLA_TEST_REPORT_DIR")          # also kept as a file where a run asks for it
+    if report_dir:
+        try:
+            os.makedirs(report_dir, exist_ok=True)
+            with open(os.path.join(report_dir, "mismatch_report.txt"), "a") as f:
+                f.write(text + "\n")
+        except OSError:
+            pass
 
 
 def check(out, lse, want, want_lse, what):
