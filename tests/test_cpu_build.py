@@ -343,7 +343,7 @@ def test_thread_sanitizer_sees_no_race_between_waves(tmp_path):
                     "-I" + os.path.join(ROOT, "include"), "-I" + str(tmp_path), os.path.join(SHIM, "decode_cpu.cpp"),
                     "-o", exe], check=True)
     case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
-    for flags, ns in ((BALANCED, 3), (0, 2)):
+    for flags, ns in ((BALANCED, 3), (0, 2), (PREFETCH, 2), (W8, 2), (W8 | BALANCED, 3)):
         out, lse, _ = run_cpu(exe, tmp_path, case, ADD, flags=flags, ns=ns)      # a report makes the exit code non-zero
         check(out, lse, case)
 
