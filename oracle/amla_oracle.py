@@ -11,7 +11,8 @@ What it holds
                        fp64 over the exact values of the bf16 inputs, with K the 576-wide
                        cached row and V its first 512 columns (Section 2.2, Section 3.1),
                        two-pass safe softmax, plus lse = max + ln(sum).  The paper's
-                       "Golden" (Section 5.1) in fp64 instead of fp32.
+                       "Golden" (Section 5.1) in fp64 instead of fp32.  Options outside the paper:
+                       a causal mask among the s_q tokens and per-sequence query counts.
 * `flash_attention`    Algorithm 1 (FlashAttention / "Base") written step by step in fp64.
 * `amla_recurrence`    Eq. (4): the AMLA transform with n_i = round(-m_i / ln 2) and
                        r_i = exp(-n_i ln 2 - m_i), in fp64.
