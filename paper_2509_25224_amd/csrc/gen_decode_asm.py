@@ -408,6 +408,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
     g(f"v_and_b32 v{T1}, 31, v{T0}")
     g(f"v_add_u32 v{V_M}, {sr(S_T1)}, v{T1}")                   # row within the sequence
     g(f"v_cmp_gt_i32 vcc, {sr(S_ROWS)}, v{V_M}")
+    g("s_nop 1")                                                 # a VALU-written VCC needs two wait states before a VALU reads it
     g(f"v_cndmask_b32 v{T1}, 0, v{V_M}, vcc")                   # rows past the end read row 0
     g(f"s_mul_i32 {sr(S_T2)}, {sr(S_B)}, {sr(S_ROWS)}")
     g(f"v_add_u32 v{T1}, {sr(S_T2)}, v{T1}")                    # global row
@@ -415,6 +416,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
     g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T1}, v{T3}, {sr(S_QP, 2)}")
     g(f"v_lshlrev_b32 v{T2}, 4, v{T2}")                         # h * 16
     g(f"v_add_co_u32 v{V_L32}, vcc, v{V_L32}, v{T2}")
+    g("s_nop 1")                                                 # the carry in VCC: two wait states before the VALU that reads it
     g(f"v_addc_co_u32 v{V_L16}, vcc, 0, v{V_L16}, vcc")
     for ks in range(36):
         g(f"global_load_dwordx4 {vr(Q + 4 * ks, 4)}, {vr(V_L32, 2)}, off offset:{32 * ks}")
@@ -613,6 +615,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
         if lazy:
             v.append(f"v_add_f32 v{T4}, {LAZY_THRESHOLD}, v{V_REF}")
             v.append(f"v_cmp_gt_f32 vcc, v{T0}, v{T4}")
+            v.append("s_nop 1")                                  # VCC from a VALU: two wait states before a VALU reads it
             v.append(f"v_cndmask_b32 v{T1}, v{V_REF}, v{T1}, vcc")      # keep the old reference unless exceeded
         # factor on the old state, and whether any row of the wave needs the accumulator rescaled
         if rescale == "mul":
@@ -684,6 +687,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
             const = 8 * (r >> 2) + (r & 3)
             g(f"s_sub_i32 {sr(S_T1)}, {sr(S_REM)}, {const}")      # key >= rem  <=>  4 h >= rem - const
             g(f"v_cmp_le_i32 vcc, {sr(S_T1)}, v{T0}")
+            g("s_nop 1")                                          # VCC from a VALU: two wait states before a VALU reads it
             g(f"v_cndmask_b32 v{SC + r}, v{SC + r}, v{T1}, vcc")
 
     # ---- prologue: scores of sub-tile u0, then the first K fetches of sub-tile u0+1 --------------
@@ -884,7 +888,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
         g(f"v_add_f32 v{reg}, v{reg}, v{T1}")
     g(f"v_rcp_f32 v{T2}, v{V_L16}")
     g(f"v_cmp_lt_f32 vcc, 0, v{V_L16}")
-    g("s_nop 0")
+    g("s_nop 1")                                                 # trans result above; VCC: two wait states before a VALU reads it
     g(f"v_cndmask_b32 v{T2}, 0, v{T2}, vcc")                     # 1 / l (0 for an empty range)
     g(f"v_log_f32 v{T3}, v{V_L32}")
     g("s_nop 0")
@@ -892,6 +896,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
     g(f"v_mul_f32 v{T3}, 0x3f317218, v{T3}")                    # * ln 2
     g(f"v_cmp_lt_f32 vcc, 0, v{V_L32}")
     g(f"v_mov_b32 v{T4}, 0xff800000")
+    g("s_nop 0")                                                 # second wait state between the VCC write and its VALU read
     g(f"v_cndmask_b32 v{T3}, v{T4}, v{T3}, vcc")                 # lse (-inf for an empty range)
     # row index and store mask
     g(f"v_mbcnt_lo_u32_b32 v{T0}, -1, 0")
@@ -915,6 +920,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
     g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_OUTP, 2)}")
     g(f"v_lshlrev_b32 v{T4}, 3, v{V_KOFF}")                      # h * 8 B
     g(f"v_add_co_u32 v{V_L32}, vcc, v{V_L32}, v{T4}")
+    g("s_nop 1")                                                 # the carry in VCC: two wait states before the VALU that reads it
     g(f"v_addc_co_u32 v{V_L16}, vcc, 0, v{V_L16}, vcc")
     if os.environ.get("AMLA_ASM_DEBUG") == "3":
         g(f"v_mov_b32 v{V_VOFF}, 0")
@@ -970,6 +976,7 @@ def kernel(g: Gen, name: str, rescale: str, lazy: bool, balanced: bool = False):
     g(f"v_mad_u64_u32 {vr(V_L32, 2)}, vcc, v{T0}, v{T4}, {sr(S_POP, 2)}")
     g(f"v_lshlrev_b32 v{T4}, 4, v{V_KOFF}")                      # h * 16 B
     g(f"v_add_co_u32 v{V_L32}, vcc, v{V_L32}, v{T4}")
+    g("s_nop 1")                                                 # the carry in VCC: two wait states before the VALU that reads it
     g(f"v_addc_co_u32 v{V_L16}, vcc, 0, v{V_L16}, vcc")
     for dt in range(16):
         for rg in range(4):

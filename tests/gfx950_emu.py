@@ -809,6 +809,8 @@ class Workgroup:
 # static hazard check over the instruction stream (straight-line distance, conservative)
 # --------------------------------------------------------------------------------------------
 def _regs_of(tok):
+    if tok in ("vcc", "vcc_lo", "vcc_hi"):
+        return {("s", 106), ("s", 107)} if tok == "vcc" else {("s", 106 if tok == "vcc_lo" else 107)}
     r = parse_reg(tok)
     if not r:
         return set()
@@ -876,6 +878,8 @@ def check_hazards(ins, labels):
                 if m == "v_dot2c_f32_bf16" and gap < 3 and not (m2 == m and hit <= _regs_of(ops2[0])
                                                                 and not hit & (_regs_of(ops2[1]) | _regs_of(ops2[2]))):
                     problems.append(f"{i}:{m} -> {j}:{m2}: dot result read after {gap} wait states")
+                if _is_valu(m) and _is_valu(m2) and gap < 2 and any(k == "s" for k, _ in hit):
+                    problems.append(f"{i}:{m} -> {j}:{m2}: VALU-written SGPR / VCC read by a VALU instruction after {gap} wait states")
                 if m in TRANS and _is_valu(m2) and gap < 1:
                     problems.append(f"{i}:{m} -> {j}:{m2}: trans result used by the next VALU op")
                 if m.startswith("v_mfma") and not m2.startswith("v_mfma") and gap < 18:

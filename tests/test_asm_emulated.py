@@ -200,6 +200,13 @@ def test_hazard_checker_follows_branches_and_counts_nops():
     assert not _problems(dot + "\ts_nop 2\n\tv_fma_f32 v240, v240, v250, v254\n")
     assert _problems(dot + "\ts_nop 1\n\tv_dot2c_f32_bf16 v253, s41, v254\n")
     assert _problems(dot + "\ts_nop 1\n\tv_mov_b32 v254, 0\n")
+    # an SGPR or VCC written by a VALU instruction: two wait states before a VALU instruction reads it
+    assert _problems("\tv_cmp_le_i32 vcc, s5, v1\n\tv_cndmask_b32 v2, v2, v3, vcc\n")
+    assert _problems("\tv_cmp_le_i32 vcc, s5, v1\n\ts_nop 0\n\tv_cndmask_b32 v2, v2, v3, vcc\n")
+    assert not _problems("\tv_cmp_le_i32 vcc, s5, v1\n\ts_nop 1\n\tv_cndmask_b32 v2, v2, v3, vcc\n")
+    assert _problems("\tv_add_co_u32 v4, vcc, v4, v6\n\tv_addc_co_u32 v5, vcc, 0, v5, vcc\n")      # the carry of an address
+    assert _problems("\tv_readfirstlane_b32 s36, v252\n\tv_add_u32 v1, s36, v1\n")
+    assert not _problems("\tv_cmp_gt_i32 vcc, s5, v1\n\ts_and_saveexec_b64 s[56:57], vcc\n")         # scalar readers are interlocked
     acc = "\tv_mfma_f32_32x32x16_bf16 a[0:15], v[200:203], v[0:3], a[0:15]\n"
     assert _problems(acc + "\ts_nop 7\n\tv_accvgpr_read_b32 v5, a3\n")
     assert _problems(acc + "\ts_nop 7\n\tv_accvgpr_write_b32 a3, 0\n")            # overwritten while in flight
