@@ -70,17 +70,13 @@ enum {
                                    accumulator rescale becomes a rare event.  Same result up to
                                    rounding.  Not available with AMLA_RESCALE_ADD_COMP, whose
                                    reference follows the row max by construction. */
-  AMLA_FLAG_ASM_KERNEL = 4      /* run the hand-scheduled assembly kernels (32-key steps, explicit
+  AMLA_FLAG_ASM_KERNEL = 4,     /* run the hand-scheduled assembly kernels (32-key steps, explicit
                                    MFMA / VALU / LDS interleave) instead of the compiler-built HIP
                                    kernel (64-key steps); MUL, ADD and ADD_LDEXP variants.  SWITCHED OFF:
                                    rejected with
                                    AMLA_ERR_UNSUPPORTED unless the environment variable
                                    AMLA_ENABLE_ASM_KERNELS is "1", because these kernels have not
                                    yet passed on hardware. */
-};
-
-/* desc->flags, continued */
-enum {
   AMLA_FLAG_BALANCED = 8,       /* decomposition for ragged batches: the 64-key
                                    blocks of all sequences are laid end to end and cut into equal
                                    ranges, one per worker workgroup; a worker walks its range sequence
