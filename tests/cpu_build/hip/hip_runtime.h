@@ -324,5 +324,6 @@ inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); 
 #define AMLA_OPAQUE(x) ((void)(x))
 #define AMLA_ONE_WAVE_PER_SIMD
 #define AMLA_TWO_WAVES_PER_SIMD
+#define AMLA_UNIFORM_LOAD_I32(p, i) ((p)[i])
 
 #endif  // AMLA_TESTS_HIP_RUNTIME_SHIM_H_
