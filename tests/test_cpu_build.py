@@ -369,9 +369,9 @@ def test_extreme_inputs(exe, tmp_path, kind):
 
 def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
     """A copy of the source with the barrier at the start of a piece taken out (a wave may then refill
-    an LDS buffer that a slower wave still reads from the previous piece): the strict direct-to-LDS
-    semantics turn that into wrong results, ThreadSanitizer into a reported race.  Planted in a copy,
-    on the CPU."""
+    an LDS buffer that a slower wave still reads from the previous piece): ThreadSanitizer reports the
+    race between the threads that stand in for the waves (whether the race also shows as wrong results
+    depends on the timing of a run, so that is not what is asserted).  Planted in a copy, on the CPU."""
     import shutil
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ to build the CPU harness with")
@@ -390,12 +390,16 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
     (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
     (tmp_path / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
-    for sanitizer in ("address", "thread"):
-        exe = str(tmp_path / ("decode_" + sanitizer))
-        subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=" + sanitizer, "-pthread",
-                        "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi", "-I" + str(shim),
-                        "-I" + os.path.join(ROOT, "include"), "-I" + str(tmp_path), str(shim / "decode_cpu.cpp"),
-                        "-o", exe], check=True)
-        with pytest.raises(AssertionError):
-            out, lse, _ = run_cpu(exe, tmp_path, case, ADD, flags=BALANCED, ns=2)
-            check(out, lse, case)
+    exe = str(tmp_path / "decode_thread")
+    subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=thread", "-pthread",
+                    "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi", "-I" + str(shim),
+                    "-I" + os.path.join(ROOT, "include"), "-I" + str(tmp_path), str(shim / "decode_cpu.cpp"),
+                    "-o", exe], check=True)
+    seen = False
+    for attempt in range(3):                      # a report makes the exit code non-zero, which run_cpu asserts on
+        try:
+            run_cpu(exe, tmp_path, case, ADD, flags=BALANCED, ns=2)
+        except AssertionError:
+            seen = True
+            break
+    assert seen
