@@ -325,5 +325,7 @@ inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); 
 #define AMLA_ONE_WAVE_PER_SIMD
 #define AMLA_TWO_WAVES_PER_SIMD
 #define AMLA_UNIFORM_LOAD_I32(p, i) ((p)[i])
+#define AMLA_ARRIVED(x) ((void)(x))
+#define AMLA_HIDDEN_LDS_LOAD(gptr, lds) shim::global_load_lds((gptr), (lds), 16, 0, 0)
 
 #endif  // AMLA_TESTS_HIP_RUNTIME_SHIM_H_
