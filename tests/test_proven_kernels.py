@@ -19,7 +19,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 PINNED = ("amla_decode_kernelILi0ELb0E", "amla_decode_kernelILi1ELb0E", "amla_combine_kernelE", "amla_exponent_add_kernelE")
 
 
-def kernel_hashes(tmp):
+def device_assembly(tmp):
+    """Compiles the library's device code to gfx950 assembly text; returns the path."""
     sys.path.insert(0, ROOT)
     import __graft_entry__ as entry
     gen = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "_build")
@@ -32,8 +33,12 @@ def kernel_hashes(tmp):
     out = os.path.join(tmp, "device.s")
     subprocess.run([HIPCC, *flags, "-I" + gen, "--cuda-device-only", "-S", "-o", out, SRC], check=True,
                    stderr=subprocess.DEVNULL)
+    return out
+
+
+def kernel_hashes(asm_path):
     hashes, cur, body = {}, None, []
-    for ln in open(out):
+    for ln in open(asm_path):
         m = re.match(r"^(_ZN\S+):", ln)
         if m:
             cur, body = m.group(1), []
@@ -52,18 +57,82 @@ def kernel_hashes(tmp):
     return hashes
 
 
-def test_gpu_proven_kernels_are_instruction_identical(tmp_path):
+@pytest.fixture(scope="module")
+def asm_path(tmp_path_factory):
     if not os.path.exists(HIPCC):
         pytest.skip("no hipcc")
+    return device_assembly(str(tmp_path_factory.mktemp("device_asm")))
+
+
+def test_gpu_proven_kernels_are_instruction_identical(asm_path):
     want = dict(ln.split() for ln in open(GOLD) if ln.strip() and not ln.startswith("#"))
-    got = kernel_hashes(str(tmp_path))
+    got = kernel_hashes(asm_path)
     assert set(got) == set(PINNED)
     assert got == want, "a GPU-proven kernel's instruction stream changed: see this file's header"
 
 
+def _kernel_bodies(asm_path):
+    """name -> list of instruction lines (comments and directives dropped, labels kept)"""
+    bodies, cur = {}, None
+    for ln in open(asm_path):
+        m = re.match(r"^(_ZN\S+):", ln)
+        if m:
+            cur = m.group(1)
+            bodies[cur] = []
+            continue
+        if cur is None:
+            continue
+        code = re.sub(r";.*", "", ln).strip()
+        if code and not code.startswith("."):
+            bodies[cur].append(code)
+        elif re.match(r"^\.LBB\d+_\d+:", code or ""):
+            bodies[cur].append(code)
+        if code == "s_endpgm":
+            cur = None
+    return bodies
+
+
+def _steady_loop(body):
+    """The instructions from the loop-top barrier to the backward branch that closes the block loop: the
+    innermost backward branch region that holds all 136 MFMAs of a block, extended back to its barrier."""
+    labels = {ln[:-1]: i for i, ln in enumerate(body) if ln.endswith(":")}
+    best = None
+    for i, ln in enumerate(body):
+        m = re.match(r"s_c?branch\w*\s+(\.LBB\d+_\d+)", ln)
+        if m and m.group(1) in labels and labels[m.group(1)] < i:
+            a = labels[m.group(1)]
+            if sum("v_mfma" in x for x in body[a:i]) >= 136 and (best is None or i - a < best[1] - best[0]):
+                best = (a, i)
+    assert best is not None
+    return body[best[0]:best[1] + 1]
+
+
+def test_tile_loads_are_not_serialised_in_the_new_kernels(asm_path):
+    """What the prefetching, balanced and eight-wave builds are built around, read off the compiled loops
+    (one in-order vmcnt for tile loads and scratch reloads; see the comments at AMLA_HIDDEN_LDS_LOAD and
+    AMLA_PIECE_LATE_LOADS): inside the block loop no register is reloaded from scratch after the next tile's
+    loads were issued, and no vmcnt wait follows them -- only the loop-top wait orders the tile.  The
+    eight-wave kernels have no reload in the loop at all."""
+    bodies = _kernel_bodies(asm_path)
+    checked = 0
+    for name, body in bodies.items():
+        if not re.search(r"amla_decode_(prefetch|balanced|w8|w8_balanced)_kernel", name):
+            continue
+        loop = _steady_loop(body)
+        issue = [i for i, ln in enumerate(loop) if ln.startswith("s_mov_b32 m0")]
+        assert issue, name                                   # the loads are issued inside the loop
+        after = loop[issue[0]:]                              # from the first issue point to the closing branch
+        assert not [ln for ln in after if ln.startswith("scratch_load")], (name, "reload behind the tile loads")
+        assert not [ln for ln in after if ln.startswith("s_waitcnt") and "vmcnt" in ln], (name, "vmcnt wait behind the tile loads")
+        if "w8" in name:
+            assert not [ln for ln in loop if ln.startswith("scratch_load")], (name, "reload inside the loop")
+        checked += 1
+    assert checked == 6 + 5 + 6 + 6
+
+
 if __name__ == "__main__" and "--write" in sys.argv:
     import tempfile
-    h = kernel_hashes(tempfile.mkdtemp())
+    h = kernel_hashes(device_assembly(tempfile.mkdtemp()))
     with open(GOLD, "w") as f:
         f.write("# sha256 of the label-normalised gfx950 instruction stream of each compiler-built kernel that has\n"
                 "# passed the GPU parity tests (written by tests/test_proven_kernels.py --write)\n")
