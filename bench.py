@@ -38,7 +38,7 @@ def parse():
                     help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
                          "means workers)")
     _names = ["add", "mul", "add_lazy", "mul_lazy", "add_ldexp", "add_ldexp_lazy"]
-    ap.add_argument("--variant", choices=["auto", "add_comp"] + _names + [n + "_pf" for n in _names] + [n + "_w8" for n in _names],
+    ap.add_argument("--variant", choices=["auto", "add_comp"] + _names + [n + "_pf" for n in _names] + [n + "_w8" for n in _names + ["add_comp"]],
                     default="auto",
                     help="auto = the fastest exponent-add variant whose output agrees with the strict add variant on this "
                          "input; _pf = the loop that issues its LDS operand reads ahead of their MFMA; _w8 = the eight-wave kernel")
@@ -161,7 +161,7 @@ def main():
     # or balanced
     have_w8 = args.impl == "compiler"
     if have_w8:
-        for name in PREFETCHABLE:
+        for name in PREFETCHABLE + ("add_comp",):
             v, f = VARIANTS[name]
             VARIANTS[name + "_w8"] = (v, f | amla.AMLA_FLAG_EIGHT_WAVES)
     if args.variant not in VARIANTS and args.variant != "auto":
@@ -198,7 +198,7 @@ def main():
             if have_pf:
                 others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf"]
             if have_w8:
-                others += ["add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8"]
+                others += ["add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8", "add_comp_w8"]
             for name in others:
                 try:
                     step(name, o2, l2)
@@ -263,7 +263,7 @@ def main():
             names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
                 (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ()) + \
                 (tuple(n + "_pf" for n in PREFETCHABLE) if have_pf else ()) + \
-                (tuple(n + "_w8" for n in PREFETCHABLE) if have_w8 else ())
+                (tuple(n + "_w8" for n in PREFETCHABLE + ("add_comp",)) if have_w8 else ())
             for name in names * 2:
                 t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
                 ab.setdefault(name, []).append(t / args.steps)

@@ -106,11 +106,11 @@ enum {
                                    per-wave accumulator and Q fragment fit the architectural VGPRs, and
                                    one wave's MFMAs run under the other's LDS waits and softmax.  Same
                                    method and roundings as the default kernels, different summation
-                                   order inside the products.  MUL, ADD and ADD_LDEXP variants, with or
-                                   without AMLA_FLAG_LAZY_RESCALE; also with AMLA_FLAG_BALANCED,
+                                   order inside the products.  All four variants (MUL, ADD, ADD_LDEXP with or
+                                   without AMLA_FLAG_LAZY_RESCALE, ADD_COMP without); also with AMLA_FLAG_BALANCED,
                                    AMLA_FLAG_CAUSAL and desc->q_lens (an eight-wave build of the balanced
-                                   kernels, switched off with them); not with AMLA_FLAG_ASM_KERNEL,
-                                   AMLA_FLAG_PREFETCH or AMLA_RESCALE_ADD_COMP. */
+                                   kernels, switched off with them); not with AMLA_FLAG_ASM_KERNEL or
+                                   AMLA_FLAG_PREFETCH. */
 };
 
 typedef struct amla_desc {

@@ -170,9 +170,7 @@ bool desc_supported(const amla_desc* d) {
                     AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES)) != 0)
     return false;
   // the eight-wave kernels are compiler-built kernels of their own (equal-share and balanced)
-  if ((d->flags & AMLA_FLAG_EIGHT_WAVES) &&
-      ((d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH)) || d->variant == AMLA_RESCALE_ADD_COMP))
-    return false;
+  if ((d->flags & AMLA_FLAG_EIGHT_WAVES) && (d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH))) return false;
   // the prefetching build of the loop exists for the equal-share compiler-built kernels (the compensated
   // instantiation spills ~90 registers with it and is left out)
   if ((d->flags & AMLA_FLAG_PREFETCH) &&
@@ -286,7 +284,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     int threads = kThreads;
     if ((desc->flags & AMLA_FLAG_EIGHT_WAVES) && balanced) {
       threads = kThreadsW8;
-      kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
+      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
+             : desc->variant == AMLA_RESCALE_ADD_LDEXP
                  ? (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_LDEXP, true>
                          : amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
              : desc->variant == AMLA_RESCALE_ADD
@@ -294,7 +293,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
                  : (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_MUL, true> : amla_decode_w8_balanced_kernel<AMLA_RESCALE_MUL, false>);
     } else if (desc->flags & AMLA_FLAG_EIGHT_WAVES) {
       threads = kThreadsW8;
-      kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
+      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_w8_kernel<AMLA_RESCALE_ADD_COMP, false>
+             : desc->variant == AMLA_RESCALE_ADD_LDEXP
                  ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
              : desc->variant == AMLA_RESCALE_ADD
                  ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD, false>)

@@ -78,7 +78,7 @@ def test_default_line_has_the_contract_keys(fake_gpu, monkeypatch):
     # auto: every exponent-add candidate was tried against the strict add kernel, and only those
     assert set(r["config"]["auto_self_check"]) - {"quick_ms"} == {
         "add_lazy", "add_comp", "add_ldexp", "add_ldexp_lazy", "add_pf", "add_lazy_pf", "add_ldexp_pf",
-        "add_ldexp_lazy_pf", "add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8"}
+        "add_ldexp_lazy_pf", "add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8", "add_comp_w8"}
     assert r["config"]["variant"] in r["config"]["auto_self_check"]["quick_ms"]
     assert not r["config"]["variant"].startswith("mul")
     assert {"mul", "add", "mul_lazy", "add_lazy"} <= set(r["rescale"]["tflops"])

@@ -117,7 +117,7 @@ def test_prefetching_build_of_the_loop_is_bit_identical(exe, tmp_path, kind):
 NO_COMP = [k for k in KINDS if k.values[0][0] != COMP]
 
 
-@pytest.mark.parametrize("kind", NO_COMP)
+@pytest.mark.parametrize("kind", KINDS)
 def test_eight_wave_kernel(exe, tmp_path, kind):
     """AMLA_FLAG_EIGHT_WAVES (16 rows per wave, 16 x 16 x 32 MFMA): the tiny configuration; the ragged
     case unsplit and in three shares (partial last blocks, an empty sequence and an empty share, a second
@@ -146,12 +146,13 @@ def test_eight_wave_kernel_no_skip_flag_changes_nothing(exe, tmp_path):
 
 def test_eight_waves_are_rejected_where_they_do_not_exist(exe, tmp_path):
     case = wl.make_config(0)
-    run_cpu(exe, tmp_path, case, COMP, flags=W8, expect_status=-2)
-    run_cpu(exe, tmp_path, case, COMP, flags=W8 | BALANCED, expect_status=-2)
+    run_cpu(exe, tmp_path, case, COMP, flags=W8 | LAZY, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=W8 | ASM, expect_status=-2)
     run_cpu(exe, tmp_path, case, ADD, flags=W8 | PREFETCH, expect_status=-2)
 
 
-@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, LAZY), 7), ((LDEXP, 0), 41), ((LDEXP, LAZY), 2)])
+@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, LAZY), 7), ((LDEXP, 0), 41), ((LDEXP, LAZY), 2),
+                                          ((COMP, 0), 5)])
 def test_eight_wave_balanced_kernels(exe, tmp_path, kind, workers):
     """The eight-wave build of the balanced kernels on the cases of the four-wave one: the ragged batch
     over worker counts below, at and above the number of sequences and blocks; the causal mask around

@@ -10,11 +10,12 @@ from test_gpu_parity import ADD, LAZY, LSE_TOL, MUL, check, env, out_tolerance, 
 
 pytestmark = pytest.mark.gpu
 
+COMP = 2
 LDEXP = 3
 W8 = 64
 KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((MUL, LAZY), id="mul_lazy"),
          pytest.param((ADD, LAZY), id="add_lazy"), pytest.param((LDEXP, 0), id="add_ldexp"),
-         pytest.param((LDEXP, LAZY), id="add_ldexp_lazy")]
+         pytest.param((LDEXP, LAZY), id="add_ldexp_lazy"), pytest.param((COMP, 0), id="add_comp")]
 
 
 @pytest.mark.parametrize("kind", KINDS)

@@ -112,7 +112,7 @@ def test_tile_loads_are_not_serialised_in_the_new_kernels(asm_path):
     (one in-order vmcnt for tile loads and scratch reloads; see the comments at AMLA_HIDDEN_LDS_LOAD and
     AMLA_PIECE_LATE_LOADS): inside the block loop no register is reloaded from scratch after the next tile's
     loads were issued, and no vmcnt wait follows them -- only the loop-top wait orders the tile.  The
-    eight-wave kernels have no reload in the loop at all."""
+    equal-share eight-wave kernels have no reload in the loop at all."""
     bodies = _kernel_bodies(asm_path)
     checked = 0
     for name, body in bodies.items():
@@ -124,10 +124,10 @@ def test_tile_loads_are_not_serialised_in_the_new_kernels(asm_path):
         after = loop[issue[0]:]                              # from the first issue point to the closing branch
         assert not [ln for ln in after if ln.startswith("scratch_load")], (name, "reload behind the tile loads")
         assert not [ln for ln in after if ln.startswith("s_waitcnt") and "vmcnt" in ln], (name, "vmcnt wait behind the tile loads")
-        if "w8" in name:
+        if "amla_decode_w8_kernel" in name:
             assert not [ln for ln in loop if ln.startswith("scratch_load")], (name, "reload inside the loop")
         checked += 1
-    assert checked == 6 + 5 + 6 + 6
+    assert checked == 6 + 5 + 7 + 7
 
 
 if __name__ == "__main__" and "--write" in sys.argv:
