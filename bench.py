@@ -257,6 +257,13 @@ def main():
     if self_check is not None:
         result["config"]["auto_self_check"] = self_check
     notes = []
+    try:
+        # what ran it: the datasheet peak above assumes 256 compute units at 2.4 GHz
+        prop = torch.cuda.get_device_properties(0)
+        result["config"]["device"] = {"name": prop.name, "compute_units": int(prop.multi_processor_count),
+                                      "clock_mhz": float(getattr(prop, "clock_rate", 0)) / 1e3}
+    except Exception as e:  # noqa: BLE001
+        notes.append(f"device properties unavailable: {e!r}")
     if not args.no_ab:
         try:
             ab = {}
