@@ -1,7 +1,7 @@
 """amla_decode under HIP graph capture: the entry point allocates nothing, synchronises nothing and
 records no memset, so a caller may capture it once and replay it.  The graph is replayed several times
 with eager work and synchronisations in between, and every replay is compared with the eager result.
-Collected after the parity files: added after the last GPU run of this build."""
+Collected behind the files of the four-wave variants and ahead of those of the newest kernels."""
 import numpy as np
 import pytest
 
