@@ -66,3 +66,19 @@ def test_headline_shape_eight_waves(env, kind):
         worst[1] = max(worst[1], float(np.abs(lse[b] - want_lse[b]).max()))
     print(f"config 2 eight waves {kind}: max|out err| {worst[0]:.3e} max|lse err| {worst[1]:.3e}", flush=True)
     assert worst[1] <= LSE_TOL
+
+
+@pytest.mark.parametrize("family,param,base_printed,amla_printed", [("n", 1.0, 1.77e-3, 1.81e-3), ("u", 1.0, 1.97e-3, 2.01e-3)])
+def test_accuracy_tables_eight_waves(env, family, param, base_printed, amla_printed):
+    """Section 5.1's experiment (Tables 3 and 4, the two flat columns) through the eight-wave MUL ('Base')
+    and compensated ('AMLA') kernels."""
+    torch, orc, amla, wl = env
+    case = wl.make_accuracy_case(family, param)
+    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
+    dev = to_dev(torch, case)
+    for variant, printed in ((MUL, base_printed), (COMP, amla_printed)):
+        out, lse = run_gpu(torch, amla, case, dev, variant=variant, flags=W8)
+        err = orc.frobenius_error(out.reshape(-1, 512), want.reshape(-1, 512))
+        print(f"{family} {param:g} eight waves v{variant}: {err:.3e} (printed {printed:.2e})", flush=True)
+        assert abs(err - printed) < 0.03 * printed, (variant, err)
+        assert np.abs(lse - want_lse).max() <= LSE_TOL
