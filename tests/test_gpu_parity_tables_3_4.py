@@ -28,7 +28,7 @@ def test_kernels_reproduce_the_printed_accuracy_tables(env, family, param, base_
     dev = to_dev(torch, case)
     err = {}
     for name, v in (("mul", MUL), ("add", ADD), ("comp", COMP)):
-        out, lse = run_gpu(torch, amla, case, dev, variant=v)
+        out, lse = run_gpu(torch, amla, case, dev, variant=v, num_splits=1)
         err[name] = orc.frobenius_error(out.reshape(-1, 512), want.reshape(-1, 512))
         assert np.abs(lse - want_lse).max() <= LSE_TOL, name
     print(f"{family} {param:g}: printed Base {base_printed:.2e} AMLA {amla_printed:.2e} | "

@@ -77,7 +77,7 @@ def test_accuracy_tables_eight_waves(env, family, param, base_printed, amla_prin
     want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
     dev = to_dev(torch, case)
     for variant, printed in ((MUL, base_printed), (COMP, amla_printed)):
-        out, lse = run_gpu(torch, amla, case, dev, variant=variant, flags=W8)
+        out, lse = run_gpu(torch, amla, case, dev, variant=variant, flags=W8, num_splits=1)
         err = orc.frobenius_error(out.reshape(-1, 512), want.reshape(-1, 512))
         print(f"{family} {param:g} eight waves v{variant}: {err:.3e} (printed {printed:.2e})", flush=True)
         assert abs(err - printed) < 0.03 * printed, (variant, err)
