@@ -101,6 +101,16 @@ enum {
                                    variants, with or without AMLA_FLAG_LAZY_RESCALE; not with
                                    AMLA_FLAG_ASM_KERNEL, AMLA_FLAG_BALANCED, AMLA_FLAG_CAUSAL or
                                    AMLA_RESCALE_ADD_COMP. */
+  AMLA_FLAG_ROW_RESCALE = 128,  /* compiler-built kernels that lay the accumulator out query row by register
+                                   (second product computed as O = P V instead of O^T = V^T P^T): a register
+                                   then belongs to two query rows, and the rescale touches only the 16
+                                   registers of each row whose reference moved in the block instead of all
+                                   256 whenever any of the wave's 32 rows moved; the accumulator lives in
+                                   AccVGPRs.  Strict MUL, ADD and ADD_COMP variants; not with
+                                   AMLA_FLAG_LAZY_RESCALE, _ASM_KERNEL, _PREFETCH or _EIGHT_WAVES.  Cache slots
+                                   past a sequence's end are cleared on chip before use (they need not hold
+                                   finite values), lengths and block-table entries are clamped into their
+                                   documented ranges. */
   AMLA_FLAG_EIGHT_WAVES = 64    /* compiler-built equal-share kernel with eight waves of 16 rows per
                                    128-row workgroup (two waves per SIMD) and the 16 x 16 x 32 MFMA: the
                                    per-wave accumulator and Q fragment fit the architectural VGPRs, and

@@ -27,6 +27,7 @@ AMLA_FLAG_BALANCED = 8
 AMLA_FLAG_CAUSAL = 16
 AMLA_FLAG_PREFETCH = 32
 AMLA_FLAG_EIGHT_WAVES = 64
+AMLA_FLAG_ROW_RESCALE = 128
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
            "amla_mfma_probe", "amla_plan_segments", "amla_preload_rotation", "amla_status_string")

@@ -36,6 +36,7 @@
 #include <mutex>
 
 #include "amla.h"
+#include "amla_device.h"
 #include "amla_plan.h"
 
 namespace {
@@ -94,14 +95,14 @@ constexpr int kMaxDecodeKernels = 64;
 const void* g_lds_ok[kMaxDevices][kMaxDecodeKernels];
 std::mutex g_lds_ok_mutex;
 
-bool allow_large_lds(const void* kernel) {
+bool allow_large_lds(const void* kernel, int lds_bytes = kLdsBytes) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
   std::lock_guard<std::mutex> lock(g_lds_ok_mutex);
   int n = 0;
   for (; n < kMaxDecodeKernels && g_lds_ok[dev][n] != nullptr; ++n)
     if (g_lds_ok[dev][n] == kernel) return true;
-  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess) {
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) {
     (void)hipGetLastError();
     return false;
   }
@@ -167,7 +168,12 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
-                    AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES)) != 0)
+                    AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES | AMLA_FLAG_ROW_RESCALE)) != 0)
+    return false;
+  // the row-rescale kernels: strict MUL / ADD / ADD_COMP, equal-share decomposition
+  if ((d->flags & AMLA_FLAG_ROW_RESCALE) &&
+      ((d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES)) ||
+       d->variant == AMLA_RESCALE_ADD_LDEXP || uses_balanced(d) || d->q_lens != nullptr))
     return false;
   // the eight-wave kernels are compiler-built kernels of their own (equal-share and balanced)
   if ((d->flags & AMLA_FLAG_EIGHT_WAVES) && (d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH))) return false;
@@ -282,7 +288,11 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
     const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
     void (*kern)(const DecodeParams) = nullptr;
     int threads = kThreads;
-    if ((desc->flags & AMLA_FLAG_EIGHT_WAVES) && balanced) {
+    int lds_bytes = kLdsBytes;
+    if (desc->flags & AMLA_FLAG_ROW_RESCALE) {
+      kern = amla_row_rescale_kernel(desc->variant);
+      lds_bytes = amla_row_rescale_lds_bytes();
+    } else if ((desc->flags & AMLA_FLAG_EIGHT_WAVES) && balanced) {
       threads = kThreadsW8;
       kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
              : desc->variant == AMLA_RESCALE_ADD_LDEXP
@@ -320,8 +330,8 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
                                                      : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
                                                              : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
     }
-    if (!allow_large_lds(reinterpret_cast<const void*>(kern))) return AMLA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), kLdsBytes, stream, p);
+    if (!allow_large_lds(reinterpret_cast<const void*>(kern), lds_bytes)) return AMLA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, stream, p);
     if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   } else {
     // index arithmetic of the assembly kernels: mulhi-by-magic division and 32-bit row indices

@@ -1,0 +1,517 @@
+// Absorbed-MLA decode for gfx950 (MI355X): the decode kernels whose output accumulator is laid out query
+// row by register.
+//
+// One workgroup (4 waves, one per SIMD, 512 registers each) owns 128 query rows of one sequence; wave w
+// owns rows 32 w .. 32 w + 31 and keeps their Q fragment (144 VGPRs) and their 32 x 512 FP32 output
+// accumulator (256 accumulator registers) resident for the whole loop over the 64-key cache blocks.
+//
+// Per block (one iteration of Algorithm 1 / Algorithm 2):
+//   [C1]  S^T = K Q^T, v_mfma_f32_32x32x16_bf16 with A = K rows from LDS and B = the Q fragment: every
+//         register of a lane then holds a score of query row lane % 32, so the row max and row sums are
+//         in-lane reductions plus one exchange with lane ^ 32.
+//   [V1]  online softmax in base 2; the weights are rounded to BF16 straight into MFMA operand layout.
+//   [C2]  O += P V, the same MFMA with A = P (query rows) and B = V read from the same LDS tile through
+//         the transposing LDS read: the result tile has value column lane % 32 in every lane and query
+//         row 8 (i / 4) + 4 (lane / 32) + i % 4 in register i.
+//   [V2]  Because a register of the accumulator belongs to two query rows only (one per half of the
+//         wave), the rescale O <- O * 2^(m_old - m_new) -- FP32 multiply (Algorithm 1, Eq. (2)) or INT32
+//         add on the exponent field (Lemma 3.1, Algorithm 2's N) -- touches just the 16 registers of the
+//         rows whose reference moved in this block, typically one or two rows out of 32, instead of all
+//         256 registers whenever any row of the wave moved.  That is what lets the accumulator live in
+//         AccVGPRs, which VALU instructions reach only through copies.
+// KV blocks come HBM -> LDS by direct-to-LDS loads, double buffered; operand reads of both products run a
+// few MFMAs ahead of their use.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <type_traits>
+#include <utility>
+
+#include "amla.h"
+#include "amla_device.h"
+#include "amla_plan.h"
+
+namespace {
+
+// LDS tile of these kernels, two regions.
+//   Region A, the first 64 16-byte chunks of every row (the 512 value columns; K and V operands): 64 rows of 68
+//   chunks (64 of data, 4 unused), the chunks of a row permuted within aligned groups of four: chunk c of row r
+//   sits at position (c & ~3) | ((c + (r >> 2)) & 3).  With 64 banks of 4 bytes, the 16 lanes a 128-bit read
+//   serves per cycle (16 rows, one chunk column) and the 32 lanes a transposing 64-bit read serves per cycle
+//   (4 rows x 4 chunk columns) then both touch every bank once; a plain padded row cannot do that for both (the
+//   first needs an odd multiple of four banks between rows, the second a multiple of sixteen).
+//   Region B, chunks 64 .. 71 of every row (the last 64 of the 576 columns, K operands only): 64 rows of 8 chunks,
+//   chunk 64 + c of row r at position c ^ ((r >> 1) & 7).
+// The direct-to-LDS loads place the chunks: a load writes one KiB, lane l at + 16 l, and fetches whatever chunk
+// belongs there.  Region A takes one load per row, region B one per 8 rows; with rows aligned to loads the
+// address of a lane is a shift, an add and a mask away (18 loads per wave and tile, a handful of
+// instructions each: they are issued between the MFMAs of the first product and must not cost more issue
+// time than an MFMA leaves).
+constexpr int kRgRowA = 68 * 16;                      // 1088 bytes between rows of region A
+constexpr int kRgRegionA = kBlock * kRgRowA;          // 69632
+constexpr int kRgRowB = 8 * 16;
+constexpr int kRgTileBytes = kRgRegionA + kBlock * kRgRowB;   // 77824 = 76 KiB
+constexpr int kRgLoadsA = kBlock / 4;                 // per wave: rows wave, wave + 4, ...
+constexpr int kRgLoadsB = 2;                          // per wave: row groups wave and wave + 4
+constexpr int kRgLdsBytes = 2 * kRgTileBytes;         // double buffer, 155648 of the 163840 bytes
+
+// One 16-byte-per-lane direct-to-LDS load from scalar base + per-lane 32-bit offset (lane l lands at lds + 16 l,
+// lds wave-uniform), issued from inline assembly like AMLA_HIDDEN_LDS_LOAD and for the same reason.
+#ifndef AMLA_TARGET_HOOKS
+#define AMLA_HIDDEN_LDS_LOAD_AT(base, off, lds)                                                              \
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"                              \
+               :                                                                                             \
+               : "v"(off), "s"(__builtin_amdgcn_readfirstlane((unsigned)(__UINTPTR_TYPE__)(lds))), "s"(base) \
+               : "memory", "m0")
+#else
+#define AMLA_HIDDEN_LDS_LOAD_AT(base, off, lds) AMLA_HIDDEN_LDS_LOAD((base) + (off), (lds))
+#endif
+
+// Per-lane constants of the tile loads.
+struct TileLoadLane {
+  int lane;      // 0 .. 63
+  int off_b;     // region B: byte offset of this lane's chunk within the block for row group 0
+};
+__device__ __forceinline__ TileLoadLane tile_load_lane(const int wave, const int lane) {
+  // rows 8 m + (lane >> 3) of row group m = wave + 4 k: (4 m) & 7 = 4 (wave & 1) whatever k
+  const int c8 = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+  return {lane, (lane >> 3) * kRowBytes + 64 * 16 + c8 * 16};
+}
+// Region A, load k (0 .. 15) of this wave: row i = wave + 4 k, whose permutation is i >> 2 = k.
+__device__ __forceinline__ void issue_tile_load_a(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
+                                                  const TileLoadLane& t, const int k) {
+  const int i = wave + 4 * k;
+  // recomputed at every load: hoisted out of the block loop these offsets would be spilled, and a reload from
+  // scratch in front of a load waits (in-order vmcnt) for every tile load in flight
+  int l = t.lane;
+  AMLA_OPAQUE(l);
+  const int c = (l & ~3) | ((l - k) & 3);                        // the chunk that lives at position lane of row i
+  AMLA_HIDDEN_LDS_LOAD_AT(block_base, (unsigned)(i * kRowBytes + c * 16), buf + i * kRgRowA);
+}
+// Region B, load k (0 or 1) of this wave: rows 8 m .. 8 m + 7 of row group m = wave + 4 k.
+__device__ __forceinline__ void issue_tile_load_b(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
+                                                  const TileLoadLane& t, const int k) {
+  const int m = wave + 4 * k;
+  int off = t.off_b;
+  AMLA_OPAQUE(off);
+  AMLA_HIDDEN_LDS_LOAD_AT(block_base, (unsigned)(off + m * 8 * kRowBytes), buf + kRgRegionA + m * 1024);
+}
+// load n (0 .. 17) of this wave's share of a tile
+__device__ __forceinline__ void issue_tile_load(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
+                                                const TileLoadLane& t, const int n) {
+  if (n < kRgLoadsA)
+    issue_tile_load_a(block_base, buf, wave, t, n);
+  else
+    issue_tile_load_b(block_base, buf, wave, t, n - kRgLoadsA);
+}
+constexpr int kRgLoadsPerWave = kRgLoadsA + kRgLoadsB;   // 18
+
+constexpr int kKAhead = 3;   // [C1]: K operand pairs (two 32-key tiles of one 16-deep step) read this many steps ahead
+constexpr int kVAhead = 4;   // [C2]: V operands read this many MFMAs ahead
+
+__device__ __forceinline__ float lane_value(float x, int src_lane) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(4 * src_lane, __float_as_int(x)));
+}
+
+// ---- the output accumulator: a register file of its own ------------------------------------------------------
+// The 32 x 512 FP32 accumulator of a wave is the wave's 256 AccVGPRs, addressed by name: tile dt (value columns
+// 32 dt .. 32 dt + 31) is a[16 dt : 16 dt + 15], register i of it holds query row 8 (i / 4) + 4 (lane / 32) + i % 4.
+// Every access goes through the few assembly statements below, so the compiler never sees the accumulator as
+// a value: it cannot move it, split it or copy it, and it allocates no AccVGPR itself (the library is built
+// with MFMA results of the first product in VGPRs; the build checks the compiled kernels for stray AccVGPR
+// uses).  What the compiler cannot see it cannot protect either, so the wait states these instructions need
+// are written out here:
+//   * an MFMA's operands come from VALU-written VGPRs (the packed weights): two idle states lead the product;
+//   * consecutive MFMAs of the second product use different tiles, a tile recurs after 16 MFMAs;
+//   * a rescale reads registers last written by the previous block's second product, which lies a whole first
+//     product and softmax back (the shift depends on them), and is followed by idle states before the next
+//     MFMA reads what it wrote;
+//   * the epilogue waits for the last MFMA to drain before it copies the accumulator out.
+#ifndef AMLA_TARGET_HOOKS
+// Every statement that writes the accumulator names all 256 AccVGPRs as clobbered: no value of the compiler's
+// can then live in an AccVGPR across it (the register allocator would otherwise park loop-invariant values
+// there, to be overwritten by the MFMAs it cannot see).
+#define AMLA_ACC_A10(n) "a" #n "0", "a" #n "1", "a" #n "2", "a" #n "3", "a" #n "4", "a" #n "5", "a" #n "6", "a" #n "7", "a" #n "8", "a" #n "9"
+#define AMLA_ACC_ALL                                                                                                  \
+  "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", AMLA_ACC_A10(1), AMLA_ACC_A10(2), AMLA_ACC_A10(3),      \
+      AMLA_ACC_A10(4), AMLA_ACC_A10(5), AMLA_ACC_A10(6), AMLA_ACC_A10(7), AMLA_ACC_A10(8), AMLA_ACC_A10(9),           \
+      AMLA_ACC_A10(10), AMLA_ACC_A10(11), AMLA_ACC_A10(12), AMLA_ACC_A10(13), AMLA_ACC_A10(14), AMLA_ACC_A10(15),     \
+      AMLA_ACC_A10(16), AMLA_ACC_A10(17), AMLA_ACC_A10(18), AMLA_ACC_A10(19), AMLA_ACC_A10(20), AMLA_ACC_A10(21),     \
+      AMLA_ACC_A10(22), AMLA_ACC_A10(23), AMLA_ACC_A10(24), "a250", "a251", "a252", "a253", "a254", "a255"
+template <int DT>
+__device__ __forceinline__ void acc_mfma(const bf16x8 a, const bf16x8 b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 a[%2*16:%2*16+15], %0, %1, a[%2*16:%2*16+15]"
+               :
+               : "v"(a), "v"(b), "n"(DT)
+               : AMLA_ACC_ALL);
+}
+template <int R>
+__device__ __forceinline__ void acc_clear() {
+  asm volatile("v_accvgpr_write_b32 a[%0], 0" : : "n"(R) : AMLA_ACC_ALL);
+}
+template <int R>
+__device__ __forceinline__ float acc_read() {
+  float x;
+  asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(x) : "n"(R));
+  return x;
+}
+// The rescale of register I of all 16 tiles (the two query rows that own it), one statement: FP32 multiply, or
+// Lemma 3.1 with its guard as in exponent_add() (saturating INT32 add, then max with the sign bit).
+#define AMLA_ACC_EACH_TILE(M) M(0) M(16) M(32) M(48) M(64) M(80) M(96) M(112) M(128) M(144) M(160) M(176) M(192) M(208) M(224) M(240)
+#define AMLA_ACC_SCALE_ONE(off) "v_accvgpr_read_b32 %0, a[%2+" #off "]\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a[%2+" #off "], %0\n\t"
+#define AMLA_ACC_ADD_ONE(off)                                                                              \
+  "v_accvgpr_read_b32 %0, a[%3+" #off "]\n\tv_and_b32 %1, 0x80000000, %0\n\tv_add_i32 %0, %0, %2 clamp\n\t" \
+  "v_max_i32 %0, %0, %1\n\tv_accvgpr_write_b32 a[%3+" #off "], %0\n\t"
+template <int I>
+__device__ __forceinline__ void acc_scale_rows(const float factor) {
+  int t;
+  asm volatile(AMLA_ACC_EACH_TILE(AMLA_ACC_SCALE_ONE) : "=&v"(t) : "v"(factor), "n"(I) : AMLA_ACC_ALL);
+}
+template <int I>
+__device__ __forceinline__ void acc_exponent_add_rows(const int n23) {
+  int t, u;
+  asm volatile(AMLA_ACC_EACH_TILE(AMLA_ACC_ADD_ONE) : "=&v"(t), "=&v"(u) : "v"(n23), "n"(I) : AMLA_ACC_ALL);
+}
+__device__ __forceinline__ void acc_idle(void) { asm volatile("s_nop 7"); }
+// the kernel owns every AccVGPR from here on
+__device__ __forceinline__ void acc_claim(void) { asm volatile("" : : : AMLA_ACC_ALL); }
+#endif
+
+template <int N, class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
+}
+
+// One piece of the decode loop: blocks [j0, j1) of sequence b for the 128 rows of row tile `tile`, one
+// softmax state per row, result written in final form (to_final) or as an FP32 partial row set starting at
+// row part_row0 of the workspace.  causal_shift (per lane: keys between this lane's row limit and the
+// sequence's end; kNoKeys for the row of a padding token) and mask_span (wave-uniform: the piece's largest
+// shift) are 0 without a mask.
+template <int VARIANT, bool MASKED>
+__device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint8_t) smem, const int lane,
+                                             const int wave, const int b, const int kv_len, const int j0,
+                                             const int j1, const int tile, const bool to_final,
+                                             const size_t part_row0, const int causal_shift, const int mask_span) {
+  const int l32 = lane & 31;
+  const int h = lane >> 5;
+  const int row = tile * kRowsPerWg + wave * 32 + l32;   // this lane's query row within the sequence
+  const size_t grow = (size_t)b * p.rows + (row < p.rows ? row : 0);
+
+  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
+  // sequence's row range read row 0 (valid memory); their results are never stored.
+  bf16x8 qf[kDqk / 16];
+  {
+    const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
+#pragma unroll
+    for (int ks = 0; ks < kDqk / 16; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
+    // waited for here: the tile loads are hidden from the compiler's wait counting, and a wait for these
+    // loads left inside the loop would be a wait for the tile
+#pragma unroll
+    for (int ks = 0; ks < kDqk / 16; ++ks) AMLA_ARRIVED(qf[ks]);
+  }
+
+  // accumulator register 16 dt + i: value column 32 dt + l32, query row 32 wave + 8 (i / 4) + 4 h + i % 4
+  static_for<256>([&](auto r) { acc_clear<r.value>(); });
+
+  float m_run = -INFINITY;   // running row max of t = s * scale * log2 e
+  float ref = 0.f;           // reference subtracted in the exponent: m_run (MUL), rint(m_run) (ADD),
+                             // m_run - log2 S16 (ADD_COMP)
+  float mu_run = 0.f;        // ADD_COMP: rint(m_run) = -n_i
+  float c_run = 1.f;         // ADD_COMP: c_i = S16 / S32
+  float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse)
+  float l_b16 = 0.f;         // sum of the BF16-rounded weights (normalises the output)
+
+  const int32_t* tab = p.table + (size_t)b * p.max_blocks;
+  const uint8_t* kvb = reinterpret_cast<const uint8_t*>(p.kv);
+  const size_t blk_bytes = (size_t)kBlock * kRowBytes;
+  auto phys_of = [&](int j) {
+    return min(max(__builtin_amdgcn_readfirstlane(AMLA_UNIFORM_LOAD_I32(tab, j)), 0), p.num_blocks - 1);
+  };
+
+  // the previous piece's last tile may still be read by a slower wave
+  __syncthreads();
+  const TileLoadLane tl = tile_load_lane(wave, lane);
+  if (j0 < j1) {
+    const uint8_t* first = kvb + (size_t)phys_of(j0) * blk_bytes;
+#pragma unroll
+    for (int k = 0; k < kRgLoadsPerWave; ++k) issue_tile_load(first, smem, wave, tl, k);
+  }
+
+  // per-lane LDS offsets of the operand reads (see the tile layout above)
+  // [C1] A operand, steps 0 .. 31 (region A): row l32 (+ 32 for the second key tile), chunk 2 ks + h; even and
+  // odd steps differ in the chunk's low bits only, so two bases and immediate offsets cover these 64 reads
+  const int k_even = l32 * kRgRowA + 16 * ((h + (l32 >> 2)) & 3);
+  const int k_odd = l32 * kRgRowA + 16 * ((h + (l32 >> 2) + 2) & 3);
+  // steps 32 .. 35 (region B): chunk 2 q + h of the row's last eight at position (2 q + h) ^ ((row >> 1) & 7)
+  const int k_tail = kRgRegionA + l32 * kRgRowB + 16 * (h ^ ((l32 >> 1) & 1));
+  const int k_tail_x = (l32 >> 2) & 3;                              // bits 1 .. 2 of the permutation: q ^ this
+  // [C2] B operand through the transposing read: 16 lanes fetch 4 keys x 16 value columns; the second half
+  // of a 16-key step lies 8 rows on, where the permutation is 2 further
+  const int g16 = lane >> 4, i16 = lane & 15;
+  const int v_row = 4 * (g16 >> 1) + (i16 >> 2);
+  const int v_chk = 2 * (g16 & 1) + ((i16 & 3) >> 1);
+  const int v_lo = v_row * kRgRowA + 16 * ((v_chk + (g16 >> 1)) & 3) + 8 * (i16 & 1);
+  const int v_hi = (v_row + 8) * kRgRowA + 16 * ((v_chk + (g16 >> 1) + 2) & 3) + 8 * (i16 & 1);
+
+  for (int j = j0; j < j1; ++j) {
+    LDS_PTR(uint8_t) buf = smem + ((j - j0) & 1) * kRgTileBytes;
+    LDS_PTR(uint8_t) nxt = smem + ((j + 1 - j0) & 1) * kRgTileBytes;
+    // Block j has landed for this wave; the barrier makes that true for all waves and also guarantees that
+    // everyone is done reading the other buffer, which is refilled next.
+    AMLA_WAIT_TILE_LOADS();
+    __syncthreads();
+    // the next block streams in under the first product: its loads are issued between the MFMAs there
+    const bool more = j + 1 < j1;
+    const uint8_t* next_block = kvb + (size_t)(more ? phys_of(j + 1) : 0) * blk_bytes;
+
+    const int rem = kv_len - j * kBlock;           // valid keys in this block (>= 1)
+    if (rem < kBlock) {
+      // Slots past the sequence's end belong to nobody: their weights are zero, but 0 * NaN would still
+      // poison the value product, so the rows are cleared in LDS before anyone reads them.
+      for (int c = (int)threadIdx.x; c < (kBlock - rem) * (kRowBytes / 16); c += kThreads) {
+        const int r = rem + c / (kRowBytes / 16), cc = c % (kRowBytes / 16);
+        LDS_PTR(uint8_t) at = cc < 64 ? buf + r * kRgRowA + cc * 16 : buf + kRgRegionA + r * kRgRowB + (cc - 64) * 16;
+        *(LDS_PTR(i32x4))at = i32x4{0, 0, 0, 0};
+      }
+      __syncthreads();
+    }
+
+    // ---- [C1] S^T[64 keys x 32 rows] ----
+    f32x16 s[2];
+    s[0] = f32x16{0};
+    s[1] = f32x16{0};
+    {
+      bf16x8 ka[kKAhead][2];
+      auto k_addr = [&](int ks, int kt) {
+        if (ks < 32) return buf + ((ks & 1) ? k_odd : k_even) + kt * 32 * kRgRowA + (ks >> 1) * 64;
+        return buf + k_tail + 32 * ((ks - 32) ^ k_tail_x) + kt * 32 * kRgRowB;
+      };
+#pragma unroll
+      for (int d = 0; d < kKAhead; ++d) {
+        ka[d][0] = *(LDS_PTR(bf16x8))k_addr(d, 0);
+        ka[d][1] = *(LDS_PTR(bf16x8))k_addr(d, 1);
+      }
+#pragma unroll
+      for (int ks = 0; ks < kDqk / 16; ++ks) {
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead][0], qf[ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead][1], qf[ks], s[1], 0, 0, 0);
+        if (ks + kKAhead < kDqk / 16) {
+          ka[ks % kKAhead][0] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 0);
+          ka[ks % kKAhead][1] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 1);
+        }
+        // the 18 loads of the next tile: one behind every second step
+        if (more && (ks & 1)) issue_tile_load(next_block, nxt, wave, tl, ks >> 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // the first V operands of [C2] are fetched under the softmax
+    s16x4 vr[kVAhead][2];
+#pragma unroll
+    for (int d = 0; d < kVAhead; ++d) {
+      vr[d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_lo + d * 64));
+      vr[d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_hi + d * 64));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- [V1] online softmax ----
+    if (MASKED ? rem < kBlock + mask_span : rem < kBlock) {
+      // with the causal mask a row's own limit lies causal_shift keys before the sequence's end
+      const int rem_row = MASKED ? rem - causal_shift : rem;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = 32 * kt + 4 * h + 8 * (r >> 2) + (r & 3);
+          if (key >= rem_row) s[kt][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx * p.scale_log2e);
+    // Under a mask a row may have seen no key yet: it starts its recurrence at the first block that holds
+    // one, and until then keeps a finite reference so that its weights are 2^(-inf) = 0 and not NaN.
+    const bool first = MASKED ? ((j == j0) || m_run == -INFINITY) : (j == j0);
+    const float m_use = MASKED ? (m_new == -INFINITY ? 0.f : m_new) : m_new;
+
+    float ref_new;
+    float alpha = 1.f;   // factor on the old row sums (MUL, ADD_COMP) and, for MUL, on the old accumulator
+    int n23 = 0;         // ADD: (n_i - n_{i-1}) << 23, <= 0; ADD_COMP: plus the mantissa term
+    if (VARIANT == AMLA_RESCALE_ADD_COMP) {
+      // Algorithm 2's compensation (S32, S16, c_i, eps, N) in base 2: S32 = 2^(m - mu) in [2^-1/2, 2^1/2], S16 its
+      // BF16 rounding, weights 2^(t - m) S16 = 2^(t - (m - log2 S16)); the shift of the exponent field and the
+      // mantissa nudge 1.5 eps 2^23 travel in one integer
+      const float mu = __builtin_rintf(m_use);
+      const float s32 = fast_exp2(m_use - mu);
+      const float s16 = __uint_as_float(pack_bf16(s32, 0.f) << 16);
+      const float c_new = s16 / s32;
+      ref_new = m_use - fast_log2(s16);
+      if (!first) {
+        const float eps = 1.5f * (c_new / c_run - 1.f);
+        n23 = max((int)(mu_run - mu), -30) * (1 << 23) + (int)__builtin_rintf(eps * 8388608.f);
+        alpha = fast_exp2(ref - ref_new);
+      }
+      mu_run = mu;
+      c_run = c_new;
+    } else if (VARIANT == AMLA_RESCALE_MUL) {
+      ref_new = m_use;
+      if (!first) alpha = fast_exp2(ref - ref_new);
+    } else {
+      ref_new = __builtin_rintf(m_use);
+      if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
+    }
+    m_run = m_new;
+    ref = ref_new;
+
+    float psum = 0.f, bsum = 0.f;
+    unsigned pk[16];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float p0 = fast_exp2(__builtin_fmaf(s[kt][r], p.scale_log2e, -ref_new));
+        const float p1 = fast_exp2(__builtin_fmaf(s[kt][r + 1], p.scale_log2e, -ref_new));
+        psum += p0 + p1;
+        const unsigned w = pack_bf16(p0, p1);
+        pk[kt * 8 + (r >> 1)] = w;
+        bsum += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
+      }
+    psum += __shfl_xor(psum, 32);
+    bsum += __shfl_xor(bsum, 32);
+    if (VARIANT == AMLA_RESCALE_ADD) {
+      l_f32 = exponent_add(l_f32, n23) + psum;
+      l_b16 = exponent_add(l_b16, n23) + bsum;
+    } else {
+      l_f32 = l_f32 * alpha + psum;
+      l_b16 = l_b16 * alpha + bsum;
+    }
+
+    // ---- [V2] rescale the accumulator registers of the rows whose reference moved ----
+    {
+      const bool moved = VARIANT == AMLA_RESCALE_MUL ? alpha != 1.f : n23 != 0;
+      unsigned rows_moved = (unsigned)__builtin_amdgcn_ballot_w64(moved);   // bit r: row r of the wave (both halves agree)
+      if ((p.flags & AMLA_FLAG_NO_SKIP) && j != j0) rows_moved = 0xffffffffu;
+      if (rows_moved != 0) {
+        const int bits = VARIANT == AMLA_RESCALE_MUL ? __float_as_int(alpha) : n23;
+        static_for<4>([&](auto gc) {
+          constexpr int g = gc.value;
+          if (rows_moved & (0xffu << (8 * g))) {
+            static_for<4>([&](auto ec) {
+              constexpr int e = ec.value;
+              // register 4 g + e of every tile holds row 8 g + e in lanes 0..31 and row 8 g + e + 4 in lanes 32..63
+              if (rows_moved & (0x11u << (8 * g + e))) {
+                const int lo = __builtin_amdgcn_readlane(bits, 8 * g + e);
+                const int hi = __builtin_amdgcn_readlane(bits, 8 * g + e + 4);
+                const int mine = h ? hi : lo;
+                if (VARIANT == AMLA_RESCALE_MUL)
+                  acc_scale_rows<4 * g + e>(__int_as_float(mine));
+                else
+                  acc_exponent_add_rows<4 * g + e>(mine);
+              }
+            });
+          }
+        });
+        acc_idle();
+      }
+    }
+
+    // ---- [C2] O[32 rows x 512] += P V ----
+    static_for<4 * (kDv / 32)>([&](auto nc) {
+      constexpr int n = nc.value, st = n / (kDv / 32), dt = n % (kDv / 32);
+      const i32x4 pb = {(int)pk[4 * st], (int)pk[4 * st + 1], (int)pk[4 * st + 2], (int)pk[4 * st + 3]};
+      const i32x2 lo2 = __builtin_bit_cast(i32x2, vr[n % kVAhead][0]), hi2 = __builtin_bit_cast(i32x2, vr[n % kVAhead][1]);
+      const i32x4 vb = {lo2[0], lo2[1], hi2[0], hi2[1]};
+      acc_mfma<dt>(__builtin_bit_cast(bf16x8, pb), __builtin_bit_cast(bf16x8, vb));
+      constexpr int nx = n + kVAhead;
+      if (nx < 4 * (kDv / 32)) {
+        constexpr int step = (nx / (kDv / 32)) * 16 * kRgRowA + (nx % (kDv / 32)) * 64;
+        vr[n % kVAhead][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_lo + step));
+        vr[n % kVAhead][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_hi + step));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  }
+
+  // ---- epilogue (the final division by the row sum of Algorithm 1 / Algorithm 2) ----
+  const float inv = l_b16 > 0.f ? 1.f / l_b16 : 0.f;
+  const float lse = l_f32 > 0.f ? (ref + fast_log2(l_f32)) * 0.6931471805599453f : -INFINITY;
+  if (row < p.rows && h == 0) {
+    if (to_final) {
+      if (p.lse != nullptr) p.lse[grow] = lse;
+    } else {
+      p.part_lse[part_row0 + row] = lse;
+    }
+  }
+  acc_idle();
+  acc_idle();
+  acc_idle();
+  static_for<16>([&](auto ic) {
+    constexpr int i = ic.value;
+    const int rw = 8 * (i >> 2) + 4 * h + (i & 3);          // row of register i within the wave
+    const float inv_i = lane_value(inv, rw);
+    const int row_i = tile * kRowsPerWg + wave * 32 + rw;
+    float o[kDv / 32];
+    static_for<kDv / 32>([&](auto dt) { o[dt.value] = acc_read<16 * dt.value + i>() * inv_i; });
+    if (row_i < p.rows) {
+      if (to_final) {
+        uint16_t* orow = p.out + ((size_t)b * p.rows + row_i) * kDv + l32;
+#pragma unroll
+        for (int dt = 0; dt < kDv / 32; ++dt) orow[32 * dt] = (uint16_t)pack_bf16(o[dt], 0.f);
+      } else {
+        float* orow = p.part_o + (part_row0 + row_i) * kDv + l32;
+#pragma unroll
+        for (int dt = 0; dt < kDv / 32; ++dt) orow[32 * dt] = o[dt];
+      }
+    }
+  });
+}
+
+// Equal-share decomposition: workgroup = (sequence, split, 128-row tile).
+template <int VARIANT>
+__global__ __launch_bounds__(kThreads) AMLA_ONE_WAVE_PER_SIMD
+void amla_decode_rg_kernel(const DecodeParams p) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
+  LDS_PTR(uint8_t) smem = (LDS_PTR(uint8_t))smem_raw;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  acc_claim();
+
+  // Workgroup -> (kv stream, row tile).  Consecutive workgroup ids go round-robin over the 8 XCDs; the row
+  // tiles of one (sequence, split) get ids that differ by 8 so that they land on the same XCD next to each
+  // other and share the KV blocks in that XCD's L2.
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int stream = (slot / p.n_tiles) * 8 + xcd;
+  const int tile = slot % p.n_tiles;
+  if (stream >= p.n_streams) return;
+  const int b = stream / p.n_splits;
+  const int split = stream - b * p.n_splits;
+
+  const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[b]), p.max_blocks, kBlock);
+  const int nb = plan_blocks_of(kv_len, kBlock);
+  const int j0 = (int)(((long long)split * nb) / p.n_splits);
+  const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
+  decode_piece<VARIANT, false>(p, smem, lane, wave, b, kv_len, j0, j1, tile, p.n_splits == 1,
+                               (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0);
+}
+
+}  // namespace
+
+// The kernel of this file for a rescale variant (AMLA_RESCALE_MUL, _ADD or _ADD_COMP), for amla_decode to launch
+// with 256 threads and amla_row_rescale_lds_bytes() of dynamic LDS.
+int amla_row_rescale_lds_bytes() { return kRgLdsBytes; }
+AmlaDecodeKernel amla_row_rescale_kernel(int variant) {
+  return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_kernel<AMLA_RESCALE_ADD_COMP>
+         : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_kernel<AMLA_RESCALE_ADD>
+                                          : amla_decode_rg_kernel<AMLA_RESCALE_MUL>;
+}

@@ -14,6 +14,7 @@ if ROOT not in sys.path:
 # ahead of the listed ones.
 GPU_FILE_ORDER = [
     "test_gpu_parity.py",
+    "test_gpu_parity_row_rescale.py",
     "test_gpu_parity_lazy.py",
     "test_gpu_parity_scale_comp.py",
     "test_gpu_parity_w_eight_waves.py",

@@ -9,9 +9,10 @@
 // output file: int32 status, int32 effective splits; then, when status is 0, out bits
 //             [batch * rows * 512] uint16 and lse [batch * rows] float
 #include "../../paper_2509_25224_amd/csrc/amla_decode.hip"
+#include "../../paper_2509_25224_amd/csrc/amla_decode_rg.hip"
 
 namespace {
-alignas(1024) uint8_t smem_raw[kLdsBytes];   // the workgroup's dynamic LDS
+alignas(1024) uint8_t smem_raw[kRgLdsBytes > kLdsBytes ? kRgLdsBytes : kLdsBytes];   // the workgroup's dynamic LDS
 }  // namespace
 
 template <class T>

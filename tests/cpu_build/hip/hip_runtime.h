@@ -111,6 +111,8 @@ inline T readfirstlane(T v) {
   return peer<T>(exchange(v), 0);
 }
 inline int readlane(int v, int l) { return peer<int>(exchange(v), l & 63); }
+// ds_bpermute_b32: lane l receives the value of lane (addr / 4) % 64
+inline int bpermute(int addr, int v) { return peer<int>(exchange(v), (addr >> 2) & 63); }
 inline unsigned long long ballot(bool p) {
   auto all = exchange((int)p);
   unsigned long long m = 0;
@@ -303,6 +305,7 @@ inline hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned gx, unsigned g
 #define __builtin_amdgcn_ds_read_tr16_b64_v4i16(p) shim::ds_read_tr16_b64((p))
 #define __builtin_amdgcn_global_load_lds(g, l, n, o, a) shim::global_load_lds((g), (l), (n), (o), (a))
 #define __builtin_amdgcn_sched_barrier(x) ((void)0)
+#define __builtin_amdgcn_ds_bpermute(addr, v) shim::bpermute((addr), (v))
 #define __builtin_amdgcn_exp2f(x) exp2f((x))
 #define __builtin_amdgcn_logf(x) log2f((x))
 #define __expf(x) expf((x))
@@ -327,5 +330,42 @@ inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); 
 #define AMLA_UNIFORM_LOAD_I32(p, i) ((p)[i])
 #define AMLA_ARRIVED(x) ((void)(x))
 #define AMLA_HIDDEN_LDS_LOAD(gptr, lds) shim::global_load_lds((gptr), (lds), 16, 0, 0)
+
+
+// The accumulator file of the row-rescale kernels (256 AccVGPRs per lane, addressed by name from assembly
+// statements on the GPU): here an array per work-item behind the same functions.  Tile dt is registers
+// 16 dt .. 16 dt + 15 with the C/D layout of the MFMA.
+#include <array>
+namespace shim {
+inline thread_local float acc_file[256];
+}
+template <int DT, class AB>
+inline void acc_mfma(AB a, AB b) {
+  std::array<float, 16> c;
+  for (int r = 0; r < 16; ++r) c[r] = shim::acc_file[16 * DT + r];
+  c = shim::mfma_32x32x16_bf16(a, b, c, 0, 0, 0);
+  for (int r = 0; r < 16; ++r) shim::acc_file[16 * DT + r] = c[r];
+}
+template <int R>
+inline void acc_clear() { shim::acc_file[R] = 0.f; }
+template <int R>
+inline float acc_read() { return shim::acc_file[R]; }
+template <int I>
+inline void acc_scale_rows(float factor) {
+  for (int dt = 0; dt < 16; ++dt) shim::acc_file[16 * dt + I] *= factor;
+}
+template <int I>
+inline void acc_exponent_add_rows(int n23) {
+  // saturating INT32 add, then max with the sign bit (the instruction pair of the GPU build)
+  for (int dt = 0; dt < 16; ++dt) {
+    const int i = __builtin_bit_cast(int, shim::acc_file[16 * dt + I]);
+    long long r = (long long)i + n23;
+    r = r > 2147483647ll ? 2147483647ll : (r < -2147483648ll ? -2147483648ll : r);
+    const int guard = i & (int)0x80000000;
+    shim::acc_file[16 * dt + I] = __builtin_bit_cast(float, std::max((int)r, guard));
+  }
+}
+inline void acc_idle() {}
+inline void acc_claim() {}
 
 #endif  // AMLA_TESTS_HIP_RUNTIME_SHIM_H_

@@ -419,3 +419,38 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
             seen = True
             break
     assert seen
+
+
+ROW = 128
+
+
+@pytest.mark.parametrize("variant", [MUL, ADD, COMP])
+def test_row_rescale_kernel(exe, tmp_path, variant):
+    """AMLA_FLAG_ROW_RESCALE (accumulator laid out query row by register, rescale per moved row): the tiny
+    configuration; the ragged case unsplit and in three shares (partial last blocks, an empty sequence and an
+    empty share, a second row tile with 32 of 128 rows valid); wide logits that move the reference of many
+    rows several times; NaN bit patterns in the cache slots past a sequence's end (the kernel clears them on
+    chip); the no-skip flag, which must not change a bit of the ADD variant's result."""
+    tiny = wl.make_config(0)
+    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=ROW)
+    check(out, lse, tiny)
+    case = _ragged(71)
+    for ns in (1, 3):
+        out, lse, splits = run_cpu(exe, tmp_path, case, variant, flags=ROW, ns=ns)
+        assert splits == ns
+        check(out, lse, case)
+        assert np.all(out[2] == 0) and np.all(np.isneginf(lse[2]))
+    wide = wl.make_case("wide_row", 72, batch=1, s_q=1, heads=40, seqlens=[700], q_sigma=6.0)
+    a = run_cpu(exe, tmp_path, wide, variant, flags=ROW)
+    check(a[0], a[1], wide, peaked=True)
+    b = run_cpu(exe, tmp_path, wide, variant, flags=ROW | NO_SKIP)
+    check(b[0], b[1], wide, peaked=True)
+    if variant == ADD:
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    import copy
+    dirty = copy.copy(wide)
+    dirty.kv_bits = wide.kv_bits.copy()
+    phys = int(wide.block_table[0, 700 // 64])
+    dirty.kv_bits[phys, 700 % 64:, :] = 0x7FC0          # NaN in every slot past the end of the last block
+    c = run_cpu(exe, tmp_path, dirty, variant, flags=ROW)
+    assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
