@@ -110,6 +110,14 @@ constexpr int kRgLoadsPerWave = kRgLoadsA + kRgLoadsB;   // 18
 constexpr int kKAhead = 3;   // [C1]: K operand pairs (two 32-key tiles of one 16-deep step) read this many steps ahead
 constexpr int kVAhead = 4;   // [C2]: V operands read this many MFMAs ahead
 
+// acc + the two BF16 values packed in w, in FP32: one dot-product instruction with a pair of ones
+#ifndef AMLA_TARGET_HOOKS
+__device__ __forceinline__ float bf16_pair_sum(const unsigned w, const float acc) {
+  const unsigned ones = 0x3f803f80u;
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, ones), acc, false);
+}
+#endif
+
 __device__ __forceinline__ float lane_value(float x, int src_lane) {
   return __int_as_float(__builtin_amdgcn_ds_bpermute(4 * src_lane, __float_as_int(x)));
 }
@@ -224,8 +232,8 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
                              // m_run - log2 S16 (ADD_COMP)
   float mu_run = 0.f;        // ADD_COMP: rint(m_run) = -n_i
   float c_run = 1.f;         // ADD_COMP: c_i = S16 / S32
-  float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse)
-  float l_b16 = 0.f;         // sum of the BF16-rounded weights (normalises the output)
+  float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse), over this half-wave's keys
+  float l_b16 = 0.f;         // sum of the BF16-rounded weights (normalises the output), over this half-wave's keys
 
   const int32_t* tab = p.table + (size_t)b * p.max_blocks;
   const uint8_t* kvb = reinterpret_cast<const uint8_t*>(p.kv);
@@ -384,10 +392,10 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
         psum += p0 + p1;
         const unsigned w = pack_bf16(p0, p1);
         pk[kt * 8 + (r >> 1)] = w;
-        bsum += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
+        bsum = bf16_pair_sum(w, bsum);
       }
-    psum += __shfl_xor(psum, 32);
-    bsum += __shfl_xor(bsum, 32);
+    // the row sums are kept per half of the wave (each half sums its own 32 keys of every block; both halves
+    // apply the same factors) and added once at the end of the piece
     if (VARIANT == AMLA_RESCALE_ADD) {
       l_f32 = exponent_add(l_f32, n23) + psum;
       l_b16 = exponent_add(l_b16, n23) + bsum;
@@ -443,6 +451,8 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   }
 
   // ---- epilogue (the final division by the row sum of Algorithm 1 / Algorithm 2) ----
+  l_b16 += __shfl_xor(l_b16, 32);
+  l_f32 += __shfl_xor(l_f32, 32);
   const float inv = l_b16 > 0.f ? 1.f / l_b16 : 0.f;
   const float lse = l_f32 > 0.f ? (ref + fast_log2(l_f32)) * 0.6931471805599453f : -INFINITY;
   if (row < p.rows && h == 0) {

@@ -189,6 +189,13 @@ inline void wait_tile_loads() {
   for (const PendingLoad& l : *pending) std::memcpy(l.dst, l.src, 16);
   pending->clear();
 }
+// all but the last n loads this wave issued have landed (they land in issue order)
+inline void wait_tile_loads_but(int n) {
+  const size_t keep = std::min<size_t>((size_t)std::max(n, 0), pending->size());
+  const size_t land = pending->size() - keep;
+  for (size_t i = 0; i < land; ++i) std::memcpy((*pending)[i].dst, (*pending)[i].src, 16);
+  pending->erase(pending->begin(), pending->begin() + land);
+}
 inline void syncthreads() { wg_bar->arrive_and_wait(); }
 
 // Runs kernel(args) for every workgroup of a 1-D or 2-D grid with `threads` work-items each (a
@@ -364,6 +371,11 @@ inline void acc_exponent_add_rows(int n23) {
     const int guard = i & (int)0x80000000;
     shim::acc_file[16 * dt + I] = __builtin_bit_cast(float, std::max((int)r, guard));
   }
+}
+inline void wait_tile_loads_but(int n) { shim::wait_tile_loads_but(n); }
+// v_dot2_f32_bf16 with a pair of ones: the two BF16 values of w added to acc in FP32
+inline float bf16_pair_sum(unsigned w, float acc) {
+  return acc + (__builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u));
 }
 inline void acc_idle() {}
 inline void acc_claim() {}
