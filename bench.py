@@ -1,15 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the absorbed-MLA decode hot path on one MI355X.
 
-A step is one pass of the whole path (paged KV gather, QK^T, online softmax, rescale, PV,
-epilogue, and the split-KV combine when the shape needs it) over one synthetic batch that
-is already resident in HBM.  The default workload is the 128-head, s_q = 2 decode batch the
-headline metric is quoted on.  One JSON line is printed:
+A step is one pass of the whole path (paged KV gather, QK^T, online softmax, rescale, PV, epilogue, and the
+split-KV combine when the shape needs it) over one synthetic batch that is already resident in HBM.  The
+default workload is the 128-head, s_q = 2 decode batch the headline metric is quoted on, and the timed kernel
+is the paper's method as the library runs it by default: the strict INT32 exponent add of Lemma 3.1 /
+Algorithm 2 (AMLA_RESCALE_ADD) on the row-rescale kernels.  One JSON line is printed:
 
-  value      whole-job TFLOP/s, FLOPs = 2 * H * s_q * sum(kv_len) * (576 + 512)  (Section 2.4)
-  roofline   the decode kernel against the bf16 dense MFMA peak (2516.6 TFLOP/s)
-  cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample
-  rescale    ADD (exponent add) and MUL (FP32 multiply) variants timed side by side
+  value         whole-job TFLOP/s, FLOPs = 2 * H * s_q * sum(kv_len) * (576 + 512)  (Section 2.4)
+  roofline      the decode kernel against the bf16 dense MFMA peak (2516.6 TFLOP/s)
+  parity        the timed kernel's output against the fp64 CPU oracle on the same input
+  cpu_baseline  the oracle timed on the host cores on a bounded sample
+  rescale       every rescale variant of both kernel families timed side by side, and the ADD / MUL
+                ratio as interleaved medians
+  per_config    the other measured configurations (HBM-bound s_q = 1, ragged, long context)
 """
 from __future__ import annotations
 
@@ -26,6 +30,10 @@ if ROOT not in sys.path:
 METRIC = "MLA decode TFLOPS + % of MI355X bf16 MFMA peak (H=128, s_q=2)"
 MFMA_BF16_PEAK_TFLOPS = 2516.6          # 256 CU x 4096 FLOP/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
+# HBM traffic of one launch of the headline kernel on the headline workload, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs scaled by a copy kernel of known size (profiles/amla_decode_rg_kernel_mtp_b128.md); null for
+# any other kernel or workload
+MEASURED_TRAFFIC = {}
 
 
 def parse():
@@ -34,28 +42,38 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
+    ap.add_argument("--variant", default="add",
+                    help="the kernel that is timed: mul, add, add_comp (row-rescale kernels, the default family), "
+                         "mul_t, add_t, add_comp_t, mul_lazy, add_lazy, add_ldexp, add_ldexp_lazy "
+                         "(transposed-accumulator kernels)")
     ap.add_argument("--balanced", action="store_true",
-                    help="balanced decomposition for ragged batches (needs AMLA_ENABLE_BALANCED=1; --splits then "
-                         "means workers)")
-    _names = ["add", "mul", "add_lazy", "mul_lazy", "add_ldexp", "add_ldexp_lazy"]
-    ap.add_argument("--variant", choices=["auto", "add_comp"] + _names + [n + "_pf" for n in _names] + [n + "_w8" for n in _names + ["add_comp"]],
-                    default="auto",
-                    help="auto = the fastest exponent-add variant whose output agrees with the strict add variant on this "
-                         "input; _pf = the loop that issues its LDS operand reads ahead of their MFMA; _w8 = the eight-wave kernel")
+                    help="balanced decomposition for ragged batches (--splits then means workers)")
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
                     help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
-                         "s_q SQ, every sequence SK keys, contiguous cache")
-    ap.add_argument("--impl", choices=["compiler", "asm"], default="compiler",
-                    help="compiler = the HIP C++ kernel (default); asm = the hand-scheduled kernels, which the "
-                         "library only runs when AMLA_ENABLE_ASM_KERNELS=1")
+                         "s_q SQ, every sequence SK keys, contiguous cache; 'all' times the table's 12 shapes")
     ap.add_argument("--splits", type=int, default=0, help="split-KV factor, 0 = library default")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (and with it the parity block)")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the measured-MFMA-peak probe")
+    ap.add_argument("--no-ab", action="store_true", help="skip the side-by-side timing of the rescale variants")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the other measured configurations")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="instead of the benchmark: copy a buffer of this many MiB `steps` times with a plain "
                          "copy kernel (torch copy_), for scaling the FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--no-ab", action="store_true", help="skip the ADD-vs-MUL side-by-side timing")
     return ap.parse_args()
+
+
+def variants(amla):
+    T, L = amla.AMLA_FLAG_TRANSPOSED_ACC, amla.AMLA_FLAG_LAZY_RESCALE
+    return {"mul": (amla.AMLA_RESCALE_MUL, 0), "add": (amla.AMLA_RESCALE_ADD, 0), "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0),
+            "mul_t": (amla.AMLA_RESCALE_MUL, T), "add_t": (amla.AMLA_RESCALE_ADD, T),
+            "add_comp_t": (amla.AMLA_RESCALE_ADD_COMP, T),
+            "mul_lazy": (amla.AMLA_RESCALE_MUL, L), "add_lazy": (amla.AMLA_RESCALE_ADD, L),
+            "add_ldexp": (amla.AMLA_RESCALE_ADD_LDEXP, 0), "add_ldexp_lazy": (amla.AMLA_RESCALE_ADD_LDEXP, L)}
+
+
+def kernel_name(name, balanced):
+    row = name in ("mul", "add", "add_comp")
+    return ("amla_decode_rg" if row else "amla_decode") + ("_balanced_kernel" if balanced else "_kernel")
 
 
 def time_steps(torch, fn, steps, warmup):
@@ -75,25 +93,83 @@ def time_steps(torch, fn, steps, warmup):
     return total, per
 
 
-def cpu_baseline(case, flops_per_seq, budget_s=12.0):
-    """The oracle as it stands, one sequence at a time, until ~budget_s of CPU work."""
+def median(xs):
+    s = sorted(xs)
+    return s[len(s) // 2]
+
+
+class Problem:
+    """One workload resident in HBM, with output buffers and a workspace large enough for any decomposition."""
+
+    def __init__(self, torch, amla, case):
+        import numpy as np
+        self.torch, self.amla, self.case = torch, amla, case
+        dev = torch.device("cuda:0")
+        self.q = torch.from_numpy(case.q_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        self.kv = torch.from_numpy(case.kv_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        self.tab = torch.from_numpy(case.block_table).to(dev)
+        self.lens = torch.from_numpy(case.seqlens).to(dev)
+        self.out = torch.empty((case.batch, case.s_q, case.heads, 512), dtype=torch.bfloat16, device=dev)
+        self.lse = torch.empty((case.batch, case.s_q, case.heads), dtype=torch.float32, device=dev)
+        self.ws = {}
+
+    def desc(self, name, balanced=False, splits=0):
+        v, f = variants(self.amla)[name]
+        if balanced:
+            f |= self.amla.AMLA_FLAG_BALANCED
+        c = self.case
+        return self.amla.make_desc(c.batch, c.s_q, c.heads, c.num_blocks, c.max_blocks_per_seq, v, splits, f)
+
+    def step(self, name, balanced=False, splits=0):
+        key = (name, balanced, splits)
+        if key not in self.ws:
+            d = self.desc(name, balanced, splits)
+            need = max(self.amla.amla_workspace_bytes(d), 16)
+            self.ws[key] = (d.variant, d.flags, self.torch.empty(need, dtype=self.torch.uint8, device=self.q.device))
+        v, f, ws = self.ws[key]
+        self.amla.amla_decode(self.q, self.kv, self.tab, self.lens, self.case.softmax_scale, self.out, self.lse,
+                              variant=v, flags=f, num_splits=splits, workspace=ws)
+
+    def time(self, name, steps, warmup, balanced=False, splits=0):
+        self.step(name, balanced, splits)            # allocates the workspace outside the timed region
+        return time_steps(self.torch, lambda: self.step(name, balanced, splits), steps, warmup)
+
+
+def oracle_leg(case, flops_per_seq, out, lse, budget_s=14.0):
+    """The oracle as it stands, one sequence at a time, until ~budget_s of CPU work: its speed (the CPU
+    baseline) and, for the sequences it got through, the timed kernel's worst deviation from it (the parity
+    block)."""
+    import numpy as np
     from oracle import amla_oracle as orc
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    done, flops = 0, 0
-    t0 = time.perf_counter()
+    done, flops, worst_out, worst_lse, big = 0, 0, 0.0, 0.0, 0
+    spent = 0.0
     for b in range(case.batch):
-        orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale, seq_ids=[b])
+        t0 = time.perf_counter()
+        want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale, seq_ids=[b])
+        spent += time.perf_counter() - t0
         done += 1
         flops += flops_per_seq[b]
-        if time.perf_counter() - t0 >= budget_s:
+        fin = np.isfinite(want_lse[b])
+        small = np.abs(want[b]) < 4.0           # where |exact| >= 4 the bf16 output format's half step alone is 1.56e-2
+        big += int((~small).sum())
+        if small.any():
+            worst_out = max(worst_out, float(np.abs(out[b] - want[b])[small].max()))
+        if fin.any():
+            worst_lse = max(worst_lse, float(np.abs(lse[b] - want_lse[b])[fin].max()))
+        if spent >= budget_s:
             break
-    dt = time.perf_counter() - t0
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {done} of {case.batch} sequences of the same workload, fp64 numpy, {dt:.1f} s"}
+    cpu = {"value": flops / spent / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"first {done} of {case.batch} sequences of the same workload, fp64 numpy, {spent:.1f} s"}
+    parity = {"max_out_err": worst_out, "max_lse_err": worst_lse, "rows_checked": done * case.s_q * case.heads,
+              "rows_total": case.batch * case.s_q * case.heads, "out_bound": 1e-2, "lse_bound": 1e-3,
+              "elements_with_exact_ge_4_left_to_the_bf16_half_step": big,
+              "passed": bool(worst_out <= 1e-2 and worst_lse <= 1e-3)}
+    return cpu, parity
 
 
 def main():
@@ -119,6 +195,24 @@ def main():
         print(json.dumps({"copy_probe": True, "bytes_read_per_launch": n, "bytes_written_per_launch": n,
                           "launches": args.steps}))
         return
+    names = variants(amla)
+    if args.variant not in names:
+        print(f"bench.py: no variant {args.variant}; one of {', '.join(names)}", file=sys.stderr)
+        sys.exit(2)
+    if args.table5 == "all":
+        rows = []
+        for sq in (1, 2):
+            for sk in (1024, 2048, 3072, 4096, 6144, 16384):
+                case = wl.make_table5_case(sq, sk)
+                prob = Problem(torch, amla, case)
+                total, _ = prob.time(args.variant, 50, 5)
+                fl = acc.decode_flops(case.heads, case.s_q, case.total_kv)
+                rows.append({"s_q": sq, "s_k": sk, "duration_us": total / 50 * 1e3, "tflops": fl / (total / 50 * 1e-3) / 1e12,
+                             "frac_of_mfma_peak": fl / (total / 50 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS})
+                del prob
+        print(json.dumps({"table5": rows, "variant": args.variant, "batch": 96, "heads": 128,
+                          "note": "the shapes of the paper's Table 5 (Section 5.2); its own rows were measured on other hardware"}))
+        return
     if args.table5:
         sq, sk = (int(x) for x in args.table5.split(","))
         case = wl.make_table5_case(sq, sk)
@@ -126,113 +220,24 @@ def main():
     else:
         case = wl.make_config(args.config)
         workload_tag = f"configs[{args.config}] {case.name}"
-    dev = torch.device("cuda:0")
-    q = torch.from_numpy(case.q_bits.view(np.int16)).to(dev).view(torch.bfloat16)
-    kv = torch.from_numpy(case.kv_bits.view(np.int16)).to(dev).view(torch.bfloat16)
-    tab = torch.from_numpy(case.block_table).to(dev)
-    lens = torch.from_numpy(case.seqlens).to(dev)
-    out = torch.empty((case.batch, case.s_q, case.heads, 512), dtype=torch.bfloat16, device=dev)
-    lse = torch.empty((case.batch, case.s_q, case.heads), dtype=torch.float32, device=dev)
+    prob = Problem(torch, amla, case)
+    chosen = args.variant
+    splits = amla.amla_effective_splits(prob.desc(chosen, args.balanced, args.splits))
 
-    impl_flag = amla.AMLA_FLAG_ASM_KERNEL if args.impl == "asm" else 0
-    if args.balanced:
-        impl_flag |= amla.AMLA_FLAG_BALANCED
-    desc = amla.make_desc(case.batch, case.s_q, case.heads, case.num_blocks, case.max_blocks_per_seq,
-                          num_splits=args.splits, flags=impl_flag)
-    splits = amla.amla_effective_splits(desc)
-    ws_bytes = amla.amla_workspace_bytes(desc)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
-
-    VARIANTS = {"mul": (amla.AMLA_RESCALE_MUL, 0), "add": (amla.AMLA_RESCALE_ADD, 0),
-                "mul_lazy": (amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE),
-                "add_lazy": (amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_LAZY_RESCALE),
-                "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0),
-                "add_ldexp": (amla.AMLA_RESCALE_ADD_LDEXP, 0),
-                "add_ldexp_lazy": (amla.AMLA_RESCALE_ADD_LDEXP, amla.AMLA_FLAG_LAZY_RESCALE)}
-    # "_pf": the build of the compiler kernels' loop that issues its LDS operand reads one MFMA ahead
-    # (same arithmetic in the same order); equal-share compiler-built kernels only
-    PREFETCHABLE = ("mul", "add", "mul_lazy", "add_lazy", "add_ldexp", "add_ldexp_lazy")
-    have_pf = args.impl == "compiler" and not args.balanced
-    if have_pf:
-        for name in PREFETCHABLE:
-            v, f = VARIANTS[name]
-            VARIANTS[name + "_pf"] = (v, f | amla.AMLA_FLAG_PREFETCH)
-    # "_w8": the eight-wave kernels (16 rows per wave, two waves per SIMD, 16 x 16 x 32 MFMA), equal-share
-    # or balanced
-    have_w8 = args.impl == "compiler"
-    if have_w8:
-        for name in PREFETCHABLE + ("add_comp",):
-            v, f = VARIANTS[name]
-            VARIANTS[name + "_w8"] = (v, f | amla.AMLA_FLAG_EIGHT_WAVES)
-    if args.variant not in VARIANTS and args.variant != "auto":
-        print(f"bench.py: variant {args.variant} does not exist for this --impl / --balanced", file=sys.stderr)
-        sys.exit(2)
-
-    def step(name, o=out, l=lse):
-        v, f = VARIANTS[name]
-        f |= impl_flag
-        amla.amla_decode(q, kv, tab, lens, case.softmax_scale, o, l, variant=v, flags=f,
-                         num_splits=args.splits, workspace=ws)
-
-    # The strict add variant is the one checked against the oracle on every row of this workload
-    # by the GPU tests.  Another exponent-add variant (lazy reference, or the paper's compensated
-    # form) becomes the headline only if, on this very input, its output stays within one bf16 step
-    # of the strict one and its lse within 1e-4, and a short timing shows it to be faster.
-    chosen, self_check = args.variant, None
-    if args.variant == "auto":
-        chosen = "add"
-        self_check = {}
-        try:
-            o2 = torch.empty_like(out)
-            l2 = torch.empty_like(lse)
-            step("add")
-            torch.cuda.synchronize()
-            passed = ["add"]
-            # what each build of the kernels offers: the compensated form only compiler-built, the ldexp
-            # form compiler-built without the balanced decomposition and hand-scheduled with or without it
-            others = ["add_lazy"]
-            if args.impl == "compiler":
-                others.append("add_comp")
-            if args.impl == "asm" or not args.balanced:
-                others += ["add_ldexp", "add_ldexp_lazy"]
-            if have_pf:
-                others += ["add_pf", "add_lazy_pf", "add_ldexp_pf", "add_ldexp_lazy_pf"]
-            if have_w8:
-                others += ["add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8", "add_comp_w8"]
-            for name in others:
-                try:
-                    step(name, o2, l2)
-                    torch.cuda.synchronize()
-                    a, b = out.float(), o2.float()
-                    d_out = float(((a - b).abs() / a.abs().clamp(min=1.0)).max())
-                    d_lse = float((lse - l2).abs().max())
-                    ok = d_out <= 2.0 ** -7 and d_lse <= 1e-4
-                    self_check[name] = {"max_rel_out_diff_vs_strict": d_out, "max_lse_diff_vs_strict": d_lse,
-                                        "passed": ok}
-                    if ok:
-                        passed.append(name)
-                except Exception as e:  # noqa: BLE001
-                    self_check[name] = {"passed": False, "error": repr(e)}
-            del o2, l2
-            quick = {}
-            for name in passed * 2:
-                t, _ = time_steps(torch, lambda: step(name), 20, 3)
-                quick[name] = min(quick.get(name, float("inf")), t / 20)
-            chosen = min(quick, key=quick.get)
-            self_check["quick_ms"] = quick
-        except Exception as e:  # noqa: BLE001  (fall back to the variant every GPU test covers)
-            chosen = "add"
-            self_check["error"] = repr(e)
     torch.cuda.synchronize()
-    total_ms, per = time_steps(torch, lambda: step(chosen), args.steps, args.warmup)
+    total_ms, per = prob.time(chosen, args.steps, args.warmup, args.balanced, args.splits)
     torch.cuda.synchronize()
+    out_host = prob.out.float().cpu().numpy().astype(np.float64)
+    lse_host = prob.lse.cpu().numpy().astype(np.float64)
 
     flops = acc.decode_flops(case.heads, case.s_q, case.total_kv)
     abytes = acc.algorithmic_bytes(case.heads, case.s_q, case.batch, case.total_kv)
     ms_per_step = total_ms / args.steps
     tflops = flops / (ms_per_step * 1e-3) / 1e12
-    kern_ms = sum(per) / len(per)          # one decode launch per step (+ combine when split)
+    kern_ms = sum(per) / len(per)          # one decode launch per step (+ the combine kernel when split)
     achieved = flops / (kern_ms * 1e-3) / 1e12
+    kname = kernel_name(chosen, args.balanced)
+    traffic = MEASURED_TRAFFIC.get((kname, chosen, case.name, splits))
 
     result = {
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -241,57 +246,30 @@ def main():
         "config": {"workload": f"{workload_tag}: batch {case.batch}, s_q {case.s_q}, "
                                f"{case.heads} heads, sum kv_len {case.total_kv}, paged bf16 latent cache "
                                f"(block 64), d_qk 576 / d_v 512",
-                   "variant": chosen, "kernel_build": args.impl, "kv_splits": splits, "balanced": bool(args.balanced),
-                   "seed": case.seed},
+                   "variant": chosen, "rescale": {"mul": "FP32 multiply (Algorithm 1)", "add": "INT32 exponent add (Lemma 3.1)",
+                                                  "add_comp": "INT32 add with Algorithm 2's BF16 scale compensation"}.get(
+                                                      chosen.replace("_t", ""), chosen),
+                   "kv_splits": splits, "decomposition": "balanced" if args.balanced else "equal_share", "seed": case.seed},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": ("amla_decode_asm_" + chosen) if args.impl == "asm" else
-                               ("amla_decode_prefetch_kernel" if chosen.endswith("_pf") else
-                                "amla_decode_w8_kernel" if chosen.endswith("_w8") else "amla_decode_kernel"),
-                     "kernel_ms": kern_ms,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                     "kernel": kname, "kernel_ms": kern_ms, "kernel_ms_median": median(per), "kernel_ms_min": min(per),
                      "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": abytes,
                      "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
     }
-
-    if self_check is not None:
-        result["config"]["auto_self_check"] = self_check
     notes = []
     try:
-        # what ran it: the datasheet peak above assumes 256 compute units at 2.4 GHz
+        cus, khz = amla.amla_device_info()
         prop = torch.cuda.get_device_properties(0)
-        result["config"]["device"] = {"name": prop.name, "compute_units": int(prop.multi_processor_count),
-                                      "clock_mhz": float(getattr(prop, "clock_rate", 0)) / 1e3}
+        result["config"]["device"] = {"name": prop.name, "compute_units": cus, "max_engine_clock_mhz": khz / 1e3,
+                                      "datasheet_peak_from_these_tflops": cus * 4096 * khz * 1e3 / 1e12}
     except Exception as e:  # noqa: BLE001
         notes.append(f"device properties unavailable: {e!r}")
-    if not args.no_ab:
-        try:
-            ab = {}
-            names = ("mul", "add", "mul_lazy", "add_lazy") + (("add_comp",) if args.impl == "compiler" else ()) + \
-                (("add_ldexp", "add_ldexp_lazy") if args.impl == "asm" or not args.balanced else ()) + \
-                (tuple(n + "_pf" for n in PREFETCHABLE) if have_pf else ()) + \
-                (tuple(n + "_w8" for n in PREFETCHABLE + ("add_comp",)) if have_w8 else ())
-            for name in names * 2:
-                t, _ = time_steps(torch, lambda: step(name), args.steps, 2)
-                ab.setdefault(name, []).append(t / args.steps)
-            best = {k: min(v) for k, v in ab.items()}
-            result["rescale"] = {"add_ms": best["add"], "mul_ms": best["mul"], "add_lazy_ms": best["add_lazy"],
-                                 "mul_lazy_ms": best["mul_lazy"],
-                                 "add_over_mul_speedup": best["mul"] / best["add"],
-                                 "add_lazy_over_mul_lazy_speedup": best["mul_lazy"] / best["add_lazy"],
-                                 "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in best.items()},
-                                 "note": "interleaved runs, best of 2 per variant, same binary; strict = "
-                                         "reference moves with every new row max, lazy = only past 2^8, "
-                                         "add_comp = Algorithm 2 with its BF16 scale compensation, add_ldexp = the exponent add "
-                                         "done by v_ldexp_f32, _pf = LDS operand reads issued ahead of their MFMA, _w8 = eight waves of "
-                                         "16 rows with the 16 x 16 x 32 MFMA"}
-        except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
-            notes.append(f"rescale side-by-side failed: {e!r}")
 
     if not args.no_mfma_probe:
         try:
             # sustained rate of a register-resident MFMA loop on this device, same process: what the
-            # chip delivers under its power limit
+            # chip delivers under its power limit with nothing else running
             probe_flops = [0.0]
 
             def probe():
@@ -302,12 +280,83 @@ def main():
             result["roofline"]["frac_of_measured_peak"] = achieved / measured
         except Exception as e:  # noqa: BLE001
             notes.append(f"mfma probe failed: {e!r}")
+
+    if not args.no_ab:
+        try:
+            # every variant of both families, interleaved, median of the per-launch times
+            ab = {}
+            reps = 2
+            n = max(10, min(40, args.steps))
+            for _ in range(reps):
+                for name in names:
+                    try:
+                        _, p = prob.time(name, n, 2, args.balanced, args.splits)
+                        ab.setdefault(name, []).extend(p)
+                    except Exception as e:  # noqa: BLE001  (a variant that does not exist for this decomposition)
+                        ab.setdefault(name, None)
+            med = {k: median(v) for k, v in ab.items() if v}
+            # the paper's comparison, strict ADD against strict MUL on the same kernel: alternate launches
+            pairs = {}
+            for a, b in (("add", "mul"), ("add_t", "mul_t")):
+                ta, tb = [], []
+                for _ in range(4):
+                    ta.extend(prob.time(a, 10, 2, args.balanced, args.splits)[1])
+                    tb.extend(prob.time(b, 10, 2, args.balanced, args.splits)[1])
+                pairs[f"{a}_over_{b}_speedup"] = median(tb) / median(ta)
+                pairs[f"{a}_ms_median_of_{len(ta)}"] = median(ta)
+                pairs[f"{b}_ms_median_of_{len(tb)}"] = median(tb)
+            result["rescale"] = {"ms_median": med, "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in med.items()}, **pairs,
+                                 "note": "same binary; mul / add / add_comp = row-rescale kernels (rescale per moved row); _t = "
+                                         "transposed-accumulator kernels (rescale of all 256 registers whenever a row of the "
+                                         "wave moved); lazy = reference moves only past 2^8; add_ldexp = the exponent add done "
+                                         "by v_ldexp_f32; strict = reference moves with every new row max"}
+        except Exception as e:  # noqa: BLE001  (an optional leg must not cost the headline line)
+            notes.append(f"rescale side-by-side failed: {e!r}")
+
     if not args.no_cpu_baseline:
         try:
             per_seq = [acc.decode_flops(case.heads, case.s_q, int(L)) for L in case.seqlens]
-            result["cpu_baseline"] = cpu_baseline(case, per_seq)
+            result["cpu_baseline"], result["parity"] = oracle_leg(case, per_seq, out_host, lse_host)
+            result["parity"]["kernel"] = kname
+            result["parity"]["variant"] = chosen
         except Exception as e:  # noqa: BLE001
-            notes.append(f"cpu baseline failed: {e!r}")
+            notes.append(f"oracle leg failed: {e!r}")
+
+    if not args.no_per_config and not args.table5 and args.config == 2:
+        per_config = {}
+        del prob
+        torch.cuda.empty_cache()
+        for idx in (1, 3, 4):
+            try:
+                c = wl.make_config(idx)
+                pr = Problem(torch, amla, c)
+                fl = acc.decode_flops(c.heads, c.s_q, c.total_kv)
+                ab_ = acc.algorithmic_bytes(c.heads, c.s_q, c.batch, c.total_kv)
+                entry = {"workload": f"batch {c.batch}, s_q {c.s_q}, {c.heads} heads, sum kv_len {c.total_kv}"}
+                legs = [("add", False), ("mul", False)] + ([("add", True), ("mul", True)] if idx == 3 else [])
+                times = {}
+                for _ in range(2):                       # interleaved
+                    for name, bal in legs:
+                        _, p = pr.time(name, 20, 3, bal)
+                        times.setdefault((name, bal), []).extend(p)
+                for (name, bal), p in times.items():
+                    ms = median(p)
+                    tf = fl / (ms * 1e-3) / 1e12
+                    gbs = ab_ / (ms * 1e-3) / 1e9
+                    mfma_t, hbm_t = fl / (MFMA_BF16_PEAK_TFLOPS * 1e12), ab_ / (HBM_PEAK_GBS * 1e9)
+                    entry[name + ("_balanced" if bal else "")] = {
+                        "ms_median_of_40": ms, "tflops": tf, "algorithmic_GBps": gbs,
+                        "kv_splits": amla.amla_effective_splits(pr.desc(name, bal)),
+                        "binding_roof": "hbm" if hbm_t > mfma_t else "mfma",
+                        "frac_of_binding_roof": max(mfma_t, hbm_t) / (ms * 1e-3),
+                        "frac_of_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+                entry["add_over_mul_speedup"] = median(times[("mul", False)]) / median(times[("add", False)])
+                per_config[f"configs[{idx}] {c.name}"] = entry
+                del pr
+                torch.cuda.empty_cache()
+            except Exception as e:  # noqa: BLE001
+                notes.append(f"per_config {idx} failed: {e!r}")
+        result["per_config"] = per_config
     if notes:
         result["notes"] = notes
 

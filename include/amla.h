@@ -13,18 +13,13 @@
  * tokens of a sequence attend to the whole cached prefix; there is no mask among them.
  *
  * The kernels run the FlashAttention recurrence (Algorithm 1) over 64-key cache blocks with
- * the output accumulator held in MFMA accumulator registers.  Two rescale variants exist:
+ * the output accumulator held in MFMA accumulator registers.  Rescale variants:
  *   AMLA_RESCALE_MUL  O <- O * 2^(m_old - m_new)            FP32 multiply (Algorithm 1, Eq. (2))
  *   AMLA_RESCALE_ADD  O <- AS_FP32(AS_INT32(O) + (n_new - n_old) * 2^23)
  *                     with the running reference quantised to an integer power of two
  *                     (Eq. (4), Lemma 3.1, Algorithm 2's n_i, N and AtomicAdd<INT32>), the INT32 add
  *                     guarded so that an exponent that would drop to or below zero yields
  *                     a signed zero instead of a wrapped bit pattern.
- *   AMLA_RESCALE_ADD_LDEXP  the ADD variant with the exponent add done by the FP32 ldexp
- *                     instruction (v_ldexp_f32) instead of an INT32 add on the bit pattern: the
- *                     same product x * 2^n wherever Lemma 3.1 applies, one instruction per
- *                     register instead of three, and zeros, signs and underflow handled by the
- *                     instruction itself.
  *   AMLA_RESCALE_ADD_COMP  the ADD variant with the BF16 scale compensation of Algorithm 2
  *                     (S32, S16, c_i, eps) and Appendix A: the weights are 2^(t - m) * S16 with S16 the
  *                     BF16 rounding of S32 = 2^(m - rint(m)), so the largest weight of a row is
@@ -32,11 +27,22 @@
  *                     rint(2^23 * 1.5 * (c_i / c_{i-1} - 1)), c_i = S16 / S32, which multiplies
  *                     the old accumulator by approximately c_i / c_{i-1} (Appendix A's reading
  *                     of c_i; Algorithm 2 prints the reciprocal).
+ *   AMLA_RESCALE_ADD_LDEXP  the ADD variant with the exponent add done by the FP32 ldexp
+ *                     instruction (v_ldexp_f32) instead of an INT32 add on the bit pattern: the
+ *                     same product x * 2^n wherever Lemma 3.1 applies, zeros, signs and underflow
+ *                     handled by the instruction itself.  Transposed-accumulator kernels only.
  *
- * Every pointer below is a DEVICE pointer unless it says host.  The library allocates
- * no device memory, never synchronises the device, and enqueues all work on desc->stream.  The
- * caller owns every buffer.  The only state kept between calls is per device and set up by the
- * first call that needs it: the code object of the hand-scheduled kernels, and the record of which
+ * Two kernel families run the path.  The default lays the accumulator out query row by register
+ * (second product computed as O = P V): a register then belongs to two query rows, and the rescale
+ * touches only the 16 registers of each row whose reference moved in the block.  The other
+ * (AMLA_FLAG_TRANSPOSED_ACC) computes both products transposed, so the rescale factor is a per-lane
+ * scalar and every rescale passes over all 256 accumulator registers of the wave; it is kept as the
+ * baseline in which the cost of the paper's [V2] stage shows, and carries the lazy and ldexp forms.
+ *
+ * Every pointer below is a DEVICE pointer unless it says host.  amla_decode allocates no device
+ * memory, never synchronises the device, reads no environment variable, and enqueues all work on
+ * desc->stream.  The caller owns every buffer.  The only state kept between calls is per device and
+ * set up by the first call that needs it: the number of compute units, and the record of which
  * kernels have been allowed their dynamic LDS size.  After that first call a call consists of kernel
  * launches only, so it may be recorded under stream capture (make the first call of a kind outside it).
  */
@@ -68,59 +74,31 @@ enum {
                                    exceeds it by more than 2^8; in between the softmax weights may
                                    grow up to 2^8 (same relative precision in bf16 and FP32), so the
                                    accumulator rescale becomes a rare event.  Same result up to
-                                   rounding.  Not available with AMLA_RESCALE_ADD_COMP, whose
-                                   reference follows the row max by construction. */
-  AMLA_FLAG_ASM_KERNEL = 4,     /* run the hand-scheduled assembly kernels (32-key steps, explicit
-                                   MFMA / VALU / LDS interleave) instead of the compiler-built HIP
-                                   kernel (64-key steps); MUL, ADD and ADD_LDEXP variants.  SWITCHED OFF:
-                                   rejected with
-                                   AMLA_ERR_UNSUPPORTED unless the environment variable
-                                   AMLA_ENABLE_ASM_KERNELS is "1", because these kernels have not
-                                   yet passed on hardware. */
+                                   rounding.  Transposed-accumulator kernels only (selects them); not
+                                   with AMLA_RESCALE_ADD_COMP, whose reference follows the row max by
+                                   construction. */
   AMLA_FLAG_BALANCED = 8,       /* decomposition for ragged batches: the 64-key
                                    blocks of all sequences are laid end to end and cut into equal
                                    ranges, one per worker workgroup; a worker walks its range sequence
                                    by sequence, and the pieces of a sequence are merged like split-KV
                                    partials.  desc->num_splits then means the number of workers
-                                   (0 = library chooses), and the workspace holds one slot per piece
-                                   (amla_workspace_bytes answers for this flag too).  SWITCHED OFF:
-                                   rejected with AMLA_ERR_UNSUPPORTED unless the environment variable
-                                   AMLA_ENABLE_BALANCED is "1", because this index arithmetic has not
-                                   yet run on hardware. */
+                                   (0 = library chooses: one workgroup per compute unit), and the
+                                   workspace holds one slot per piece (amla_workspace_bytes answers for
+                                   this flag too).  Both kernel families. */
   AMLA_FLAG_CAUSAL = 16,        /* causal mask among the s_q query tokens of a sequence (multi-token
                                    prediction: the s_q tokens are the last s_q positions of the cache):
                                    token t attends to keys 0 .. kv_len - s_q + t, i.e. to
                                    kv_len - (s_q - 1 - t) keys; a token whose limit is <= 0 gets
                                    out = 0, lse = -inf.  Without the flag every token attends to all
-                                   kv_len keys.  Runs in the compiler-built balanced kernels (implies
-                                   AMLA_FLAG_BALANCED, is switched off with it, and cannot be
-                                   combined with AMLA_FLAG_ASM_KERNEL). */
-  AMLA_FLAG_PREFETCH = 32,      /* compiler-built equal-share kernels with the LDS operand reads of both
-                                   products issued one to two MFMAs ahead of their use.  Same arithmetic in the
-                                   same order, so the same result bit for bit; MUL, ADD and ADD_LDEXP
-                                   variants, with or without AMLA_FLAG_LAZY_RESCALE; not with
-                                   AMLA_FLAG_ASM_KERNEL, AMLA_FLAG_BALANCED, AMLA_FLAG_CAUSAL or
-                                   AMLA_RESCALE_ADD_COMP. */
-  AMLA_FLAG_ROW_RESCALE = 128,  /* compiler-built kernels that lay the accumulator out query row by register
-                                   (second product computed as O = P V instead of O^T = V^T P^T): a register
-                                   then belongs to two query rows, and the rescale touches only the 16
-                                   registers of each row whose reference moved in the block instead of all
-                                   256 whenever any of the wave's 32 rows moved; the accumulator lives in
-                                   AccVGPRs.  Strict MUL, ADD and ADD_COMP variants; not with
-                                   AMLA_FLAG_LAZY_RESCALE, _ASM_KERNEL, _PREFETCH or _EIGHT_WAVES.  Cache slots
-                                   past a sequence's end are cleared on chip before use (they need not hold
-                                   finite values), lengths and block-table entries are clamped into their
-                                   documented ranges. */
-  AMLA_FLAG_EIGHT_WAVES = 64    /* compiler-built equal-share kernel with eight waves of 16 rows per
-                                   128-row workgroup (two waves per SIMD) and the 16 x 16 x 32 MFMA: the
-                                   per-wave accumulator and Q fragment fit the architectural VGPRs, and
-                                   one wave's MFMAs run under the other's LDS waits and softmax.  Same
-                                   method and roundings as the default kernels, different summation
-                                   order inside the products.  All four variants (MUL, ADD, ADD_LDEXP with or
-                                   without AMLA_FLAG_LAZY_RESCALE, ADD_COMP without); also with AMLA_FLAG_BALANCED,
-                                   AMLA_FLAG_CAUSAL and desc->q_lens (an eight-wave build of the balanced
-                                   kernels, switched off with them); not with AMLA_FLAG_ASM_KERNEL or
-                                   AMLA_FLAG_PREFETCH. */
+                                   kv_len keys.  Runs in the balanced kernels (implies
+                                   AMLA_FLAG_BALANCED). */
+  AMLA_FLAG_TRANSPOSED_ACC = 128 /* run the kernels that compute both products transposed (S^T = K Q^T,
+                                   O^T = V^T P^T): the accumulator's rescale factor is then a per-lane
+                                   scalar and a rescale passes over all 256 accumulator registers of the
+                                   wave whenever any of its 32 rows moved.  Same method and roundings as
+                                   the default kernels.  These kernels read block-table entries and (in
+                                   the equal-share decomposition) lengths as they are, and need finite
+                                   values in the cache slots past a sequence's end. */
 };
 
 typedef struct amla_desc {
@@ -149,9 +127,8 @@ typedef struct amla_desc {
                                   numbers of new tokens.  Sequence b is then the problem with
                                   s_q = q_lens[b] (also for AMLA_FLAG_CAUSAL: token t attends to
                                   kv_len - (q_lens[b] - 1 - t) keys); the rows of its padding tokens are
-                                  written as out = 0, lse = -inf.  Runs in the compiler-built balanced
-                                  kernels: needs AMLA_FLAG_BALANCED or AMLA_FLAG_CAUSAL, is switched off
-                                  with them, and cannot be combined with AMLA_FLAG_ASM_KERNEL. */
+                                  written as out = 0, lse = -inf.  Runs in the balanced kernels (implies
+                                  AMLA_FLAG_BALANCED). */
 } amla_desc;
 
 /*
@@ -159,15 +136,15 @@ typedef struct amla_desc {
  * Algorithm 1 / Algorithm 2 of the paper per 64-key block, Section 3).
  *
  *   q            bf16 [batch, s_q, num_heads, 576], contiguous, read only
- *   kv_cache     bf16 [num_blocks, 64, 576], contiguous, read only.  Every slot of every block
- *                a sequence references must hold a finite value, including slots past the
- *                sequence's end inside its last block (they are masked, but a NaN there would
- *                still poison the value product).
+ *   kv_cache     bf16 [num_blocks, 64, 576], contiguous, read only.  Slots past a sequence's end
+ *                inside its last block may hold anything (the default kernels clear them on chip
+ *                before the value product); with AMLA_FLAG_TRANSPOSED_ACC they must hold finite
+ *                values (they are masked, but a NaN there would still poison the value product).
  *   block_table  int32 [batch, max_blocks_per_seq]; entry j of row b is the physical block of
  *                keys 64j .. 64j+63 of sequence b.  Entries j >= ceil(kv_len[b]/64) are never
- *                read.  Entries that are read must lie in [0, num_blocks).  The balanced and the
- *                hand-scheduled kernels clamp them into that range (a wrong entry then gives a
- *                wrong result, not a wild access); the default kernels read them as they are.
+ *                read.  Entries that are read must lie in [0, num_blocks).  The default kernels
+ *                clamp them into that range and lengths into [0, 64 * max_blocks_per_seq] (a wrong
+ *                entry then gives a wrong result, not a wild access).
  *   seqlens      int32 [batch], 0 <= kv_len[b] <= 64 * max_blocks_per_seq
  *   softmax_scale  multiplies q.k before the softmax (the paper's 1/sqrt(D_k) generalised);
  *                finite and > 0
@@ -223,6 +200,14 @@ int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* s
 int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stream);
 
 /*
+ * amla_device_info -- measurement support: the number of compute units and the maximum engine clock (kHz) of
+ * the current device as the HIP runtime reports them (host pointers).  The datasheet MFMA peak that utilisation
+ * is quoted against is compute units x 4096 FLOP per clock x this clock.  AMLA_ERR_LAUNCH when the runtime
+ * refuses the query.
+ */
+int amla_device_info(int32_t* compute_units, int32_t* clock_khz);
+
+/*
  * amla_plan_segments -- host-only view of the balanced decomposition (AMLA_FLAG_BALANCED), computed
  * with the same integer routines the kernels use; for tests and for sizing.  `seqlens` is a HOST
  * array of `batch` lengths.  Writes up to `capacity` pieces as rows of six int32
@@ -249,8 +234,7 @@ int amla_plan_segments(const int32_t* seqlens, int32_t batch, int32_t workers, i
  * (= n) to *preload_count.  Requires sum(vec) <= sum(cube) -- the matrix-bound case the theorem is
  * proved for -- and 1 <= n <= 4096; otherwise AMLA_ERR_UNSUPPORTED.  For the chain of this library
  * (n = 2, V_2 = 0) the answer is first_stage 2, external_pair 1, count 2 for any durations: the Cycle
- * [C1, C2, V1] of Section 4.1 in which V1 consumes the previous Cycle's C1, which is the pass order
- * the hand-scheduled kernels hard-code.
+ * [C1, C2, V1] of Section 4.1 in which V1 consumes the previous Cycle's C1.
  */
 int amla_preload_rotation(const int64_t* cube, const int64_t* vec, int32_t n, int32_t* first_stage,
                           int32_t* external_pair, int32_t* preload_count);

@@ -22,15 +22,12 @@ AMLA_RESCALE_ADD_COMP = 2
 AMLA_RESCALE_ADD_LDEXP = 3
 AMLA_FLAG_NO_SKIP = 1
 AMLA_FLAG_LAZY_RESCALE = 2
-AMLA_FLAG_ASM_KERNEL = 4
 AMLA_FLAG_BALANCED = 8
 AMLA_FLAG_CAUSAL = 16
-AMLA_FLAG_PREFETCH = 32
-AMLA_FLAG_EIGHT_WAVES = 64
-AMLA_FLAG_ROW_RESCALE = 128
+AMLA_FLAG_TRANSPOSED_ACC = 128
 
 EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
-           "amla_mfma_probe", "amla_plan_segments", "amla_preload_rotation", "amla_status_string")
+           "amla_mfma_probe", "amla_device_info", "amla_plan_segments", "amla_preload_rotation", "amla_status_string")
 
 
 class AmlaDesc(ctypes.Structure):
@@ -56,6 +53,8 @@ lib.amla_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, c
                             ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(AmlaDesc)]
 lib.amla_workspace_bytes.restype = ctypes.c_size_t
 lib.amla_workspace_bytes.argtypes = [ctypes.POINTER(AmlaDesc)]
+lib.amla_device_info.restype = ctypes.c_int
+lib.amla_device_info.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
 lib.amla_effective_splits.restype = ctypes.c_int
 lib.amla_effective_splits.argtypes = [ctypes.POINTER(AmlaDesc)]
 lib.amla_exponent_add.restype = ctypes.c_int
@@ -160,6 +159,15 @@ def amla_exponent_add(x, delta: int, y=None):
     if st != AMLA_OK:
         raise AmlaError(st)
     return y
+
+
+def amla_device_info():
+    """(compute units, maximum engine clock in kHz) of the current device."""
+    cus, khz = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib.amla_device_info(ctypes.byref(cus), ctypes.byref(khz))
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return int(cus.value), int(khz.value)
 
 
 def amla_mfma_probe(iters: int, workgroups: int) -> float:

@@ -1,37 +1,31 @@
-// Absorbed-MLA decode attention for gfx950 (MI355X): kernels and the C-ABI entry points.
-// Device code: amla_decode_kernels.inc (kernels, included below), amla_decode_equal_share.inc (the
-// equal-share kernel, built twice: plain and prefetching), amla_decode_piece.inc (the body of the
-// decode loop, shared by the equal-share and the balanced kernels), amla_decode_balanced.inc (the
-// balanced walk, built once per wave shape) and amla_decode_w8.inc / amla_decode_w8_piece.inc (the
-// eight-wave kernels and their loop body); amla_plan.h holds the
-// balanced decomposition's integer arithmetic; this file holds the host side.
+// Absorbed-MLA decode attention for gfx950 (MI355X): the C-ABI entry points, the host side (argument checks,
+// split choice, dispatch) and the kernels that keep the output accumulator transposed.
 //
-// One workgroup (4 waves, one per SIMD, up to 512 VGPRs each) owns 128 query rows of one
-// sequence and a contiguous range of that sequence's 64-key cache blocks.  Wave w owns
-// rows 32w .. 32w+31 and keeps, for those rows, the whole Q fragment (144 VGPRs) and the
-// whole 32 x 512 FP32 output accumulator (256 registers) resident for the entire loop, so
-// the accumulator never leaves the register file (the data movement that the paper's
-// Section 3.1 identifies as the bottleneck of the [V2] stage does not exist here).
+// Two kernel families run the same path (paged KV gather -> [C1] S = Q K^T -> [V1] online softmax -> [V2]
+// rescale -> [C2] O += P V -> epilogue; Algorithm 1 / Algorithm 2 per 64-key block):
+//   * the row-rescale kernels of amla_decode_rg.hip, the default: second product computed as O = P V, so a
+//     register of the accumulator belongs to two query rows and the rescale touches only rows whose reference
+//     moved;
+//   * the kernels below (AMLA_FLAG_TRANSPOSED_ACC, and the lazy and ldexp variants, which exist here only):
+//     both products transposed, S^T = K Q^T and O^T = V^T P^T, so every register of a lane belongs to query
+//     row lane % 32, the rescale factor is a per-lane scalar, and a rescale passes over all 256 accumulator
+//     registers whenever any of the wave's 32 rows moved -- the cost of the paper's [V2] stage as it appears on
+//     this hardware, kept as the baseline the row-rescale kernels are measured against.
+// Device code of this file: amla_decode_kernels.inc (kernels, included below), amla_decode_equal_share.inc
+// (the equal-share kernel), amla_decode_piece.inc (the body of the decode loop, shared by the equal-share and
+// the balanced kernels), amla_decode_balanced.inc (the balanced walk); amla_plan.h holds the balanced
+// decomposition's integer arithmetic; amla_device.h what both families share.
 //
-// Per block (Algorithm 1 / Algorithm 2, one iteration of the loop):
-//   [C1]  S^T = K Q^T   : v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q registers.
-//         Computing the transpose puts query row (lane % 32) in every register of a lane,
-//         so row max / row sum are in-lane reductions plus one exchange with lane ^ 32.
-//   [V1]  online softmax in base 2; P rounded to bf16 straight into the B-operand layout of
-//         the second product (no cross-lane movement).
-//   [V2]  rescale of the accumulator registers: FP32 multiply (MUL variant) or guarded INT32
-//         add on the exponent field (ADD variants, Lemma 3.1; ADD_COMP adds Algorithm 2's
-//         mantissa term to the same integer), skipped when no row of the wave changed its
-//         reference.
-//   [C2]  O^T += V^T P^T : A = V^T from the same LDS tile through the transposing LDS read
-//         (ds_read_b64_tr_b16), B = P registers.
-// The KV block is brought HBM -> LDS by direct-to-LDS loads (global_load_lds_dwordx4), double
-// buffered: block j+1 streams in while block j is consumed.
+// One workgroup (4 waves, one per SIMD, up to 512 registers each) owns 128 query rows of one sequence and a
+// contiguous range of that sequence's 64-key cache blocks.  Wave w owns rows 32 w .. 32 w + 31 and keeps, for
+// those rows, the whole Q fragment (144 VGPRs) and the whole 32 x 512 FP32 output accumulator (256 registers)
+// resident for the entire loop, so the accumulator never leaves the register file (the data movement that the
+// paper's Section 3.1 identifies as the bottleneck of the [V2] stage does not exist here).  The KV block is
+// brought HBM -> LDS by direct-to-LDS loads (global_load_lds_dwordx4), double buffered.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -43,50 +37,7 @@ namespace {
 
 #include "amla_decode_kernels.inc"
 
-// ---- hand-scheduled kernels: code object assembled from the generated gfx950 assembly --------
-const unsigned char kDecodeCodeObject[] = {
-#include "amla_decode_gfx950.hsaco.inc"
-};
-// The same kernels in their diagnostic form (every wait a full drain, idle issue slots after every
-// instruction): loaded instead when AMLA_ASM_SAFE_BUILD=1.  A wrong result that disappears with it
-// points at a timing hazard, one that stays at a semantic mistake.
-const unsigned char kDecodeCodeObjectSafe[] = {
-#include "amla_decode_gfx950_safe.hsaco.inc"
-};
-
 constexpr int kMaxDevices = 64;
-constexpr int kAsmKernels = 12;   // index = kind (mul, add, ldexp) + 3 * lazy + 6 * balanced
-const char* const kAsmNames[kAsmKernels] = {
-    "amla_decode_asm_mul",          "amla_decode_asm_add",          "amla_decode_asm_ldexp",
-    "amla_decode_asm_mul_lazy",     "amla_decode_asm_add_lazy",     "amla_decode_asm_ldexp_lazy",
-    "amla_decode_asm_mul_bal",      "amla_decode_asm_add_bal",      "amla_decode_asm_ldexp_bal",
-    "amla_decode_asm_mul_lazy_bal", "amla_decode_asm_add_lazy_bal", "amla_decode_asm_ldexp_lazy_bal"};
-struct DeviceKernels {
-  bool tried = false;
-  bool ok = false;
-  hipModule_t module = nullptr;
-  hipFunction_t fn[kAsmKernels] = {};
-};
-DeviceKernels g_kernels[kMaxDevices];
-std::mutex g_kernels_mutex;
-
-// The code object is loaded once per device, on the first call made with that device current.
-const DeviceKernels* device_kernels() {
-  int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-  std::lock_guard<std::mutex> lock(g_kernels_mutex);
-  DeviceKernels& k = g_kernels[dev];
-  if (!k.tried) {
-    k.tried = true;
-    const char* safe = std::getenv("AMLA_ASM_SAFE_BUILD");
-    const bool use_safe = safe != nullptr && std::strcmp(safe, "1") == 0;
-    bool ok = hipModuleLoadData(&k.module, use_safe ? kDecodeCodeObjectSafe : kDecodeCodeObject) == hipSuccess;
-    for (int i = 0; ok && i < kAsmKernels; ++i) ok = hipModuleGetFunction(&k.fn[i], k.module, kAsmNames[i]) == hipSuccess;
-    if (!ok) (void)hipGetLastError();
-    k.ok = ok;
-  }
-  return k.ok ? &k : nullptr;
-}
 
 // The decode kernels use more dynamic LDS than a launch may ask for by default; the attribute that
 // allows it is set once per kernel and device, on the first call, so that later calls (for instance
@@ -110,48 +61,33 @@ bool allow_large_lds(const void* kernel, int lds_bytes = kLdsBytes) {
   return true;
 }
 
-// Kernel argument block of the assembly kernels (offsets are fixed in the generator).
-struct AsmArgs {
-  const void* q;
-  const void* kv;
-  const void* table;
-  const void* seqlens;
-  void* out;
-  float* lse;
-  float* part_o;
-  float* part_lse;
-  float scale_log2e;
-  int32_t batch;
-  int32_t rows;
-  int32_t n_splits;
-  int32_t max_blocks;
-  int32_t n_streams;
-  int32_t flags;
-  uint32_t split_magic;   // floor(2^32 / n_splits) + 1: x / n_splits == mulhi(x, magic) for x * n_splits < 2^32
-  int32_t num_blocks;     // physical blocks in the pool: table entries are clamped into it
-  int32_t pad;
-  int32_t workers;        // balanced kernels: number of workers W (= n_streams)
-  uint32_t worker_magic;  // floor(2^32 / W) + 1: x / W == mulhi(x, magic) for x * W < 2^32 (W == 1 is special-cased)
-};
-static_assert(sizeof(AsmArgs) == 0x70, "kernel argument block layout");
-
-// The hand-scheduled kernels are switched off unless the process opts in: their first run on
-// the GPU faulted (a missing wait state before v_readfirstlane, since fixed in the generator)
-// and the fix has not been run on hardware yet.
-bool asm_kernels_enabled() {
-  const char* e = std::getenv("AMLA_ENABLE_ASM_KERNELS");
-  return e != nullptr && std::strcmp(e, "1") == 0;
+// Compute units of the current device, read once per device.
+int g_cu_count[kMaxDevices];
+std::mutex g_cu_count_mutex;
+int device_cu_count() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  std::lock_guard<std::mutex> lock(g_cu_count_mutex);
+  if (g_cu_count[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    g_cu_count[dev] = n;
+  }
+  return g_cu_count[dev];
 }
 
-// The balanced decomposition has new index arithmetic that has not run on hardware yet; until it
-// has, a process must opt in.
-bool balanced_enabled() {
-  const char* e = std::getenv("AMLA_ENABLE_BALANCED");
-  return e != nullptr && std::strcmp(e, "1") == 0;
+// The causal mask and the per-sequence query counts live in the balanced kernels only, so they select them.
+bool uses_balanced(const amla_desc* d) {
+  return (d->flags & (AMLA_FLAG_BALANCED | AMLA_FLAG_CAUSAL)) != 0 || d->q_lens != nullptr;
 }
 
-// The causal mask lives in the balanced kernels only, so it selects them.
-bool uses_balanced(const amla_desc* d) { return (d->flags & (AMLA_FLAG_BALANCED | AMLA_FLAG_CAUSAL)) != 0; }
+// The lazy reference and the ldexp variant exist in the transposed-accumulator kernels only.
+bool uses_transposed(const amla_desc* d) {
+  return (d->flags & (AMLA_FLAG_TRANSPOSED_ACC | AMLA_FLAG_LAZY_RESCALE)) != 0 || d->variant == AMLA_RESCALE_ADD_LDEXP;
+}
 
 bool desc_supported(const amla_desc* d) {
   if (d == nullptr) return false;
@@ -160,33 +96,15 @@ bool desc_supported(const amla_desc* d) {
   if (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD && d->variant != AMLA_RESCALE_ADD_COMP &&
       d->variant != AMLA_RESCALE_ADD_LDEXP)
     return false;
-  // ldexp rescale with the balanced decomposition: hand-scheduled and eight-wave kernels only (this
-  // compiler's AGPR-copy rewrite pass crashes on the balanced four-wave instantiation)
-  if (d->variant == AMLA_RESCALE_ADD_LDEXP && uses_balanced(d) &&
-      !(d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_EIGHT_WAVES)))
-    return false;
-  if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL))) return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
-  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_BALANCED |
-                    AMLA_FLAG_CAUSAL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES | AMLA_FLAG_ROW_RESCALE)) != 0)
+  if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_BALANCED | AMLA_FLAG_CAUSAL |
+                    AMLA_FLAG_TRANSPOSED_ACC)) != 0)
     return false;
-  // the row-rescale kernels: strict MUL / ADD / ADD_COMP, equal-share decomposition
-  if ((d->flags & AMLA_FLAG_ROW_RESCALE) &&
-      ((d->flags & (AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH | AMLA_FLAG_EIGHT_WAVES)) ||
-       d->variant == AMLA_RESCALE_ADD_LDEXP || uses_balanced(d) || d->q_lens != nullptr))
-    return false;
-  // the eight-wave kernels are compiler-built kernels of their own (equal-share and balanced)
-  if ((d->flags & AMLA_FLAG_EIGHT_WAVES) && (d->flags & (AMLA_FLAG_ASM_KERNEL | AMLA_FLAG_PREFETCH))) return false;
-  // the prefetching build of the loop exists for the equal-share compiler-built kernels (the compensated
-  // instantiation spills ~90 registers with it and is left out)
-  if ((d->flags & AMLA_FLAG_PREFETCH) &&
-      ((d->flags & AMLA_FLAG_ASM_KERNEL) || uses_balanced(d) || d->variant == AMLA_RESCALE_ADD_COMP))
-    return false;
-  if ((d->flags & AMLA_FLAG_ASM_KERNEL) && !asm_kernels_enabled()) return false;
-  if (uses_balanced(d) && !balanced_enabled()) return false;
-  if ((d->flags & AMLA_FLAG_CAUSAL) && (d->flags & AMLA_FLAG_ASM_KERNEL)) return false;   // the mask is in the compiler-built kernels only
-  // per-sequence query counts are a per-row key limit like the mask: same kernels
-  if (d->q_lens != nullptr && (!uses_balanced(d) || (d->flags & AMLA_FLAG_ASM_KERNEL))) return false;
+  // ldexp rescale with the balanced decomposition does not exist (the compiler's AGPR-copy rewrite pass
+  // crashes on that instantiation of the transposed-accumulator kernels)
+  if (d->variant == AMLA_RESCALE_ADD_LDEXP && uses_balanced(d)) return false;
+  // the compensated reference follows the row max by construction: no lazy form
+  if (d->variant == AMLA_RESCALE_ADD_COMP && (d->flags & AMLA_FLAG_LAZY_RESCALE)) return false;
   if ((long long)d->batch * d->max_blocks_per_seq > (1ll << 31) - 1) return false;
   const long long rows = (long long)d->s_q * d->num_heads;
   if (rows > (1 << 20) || (long long)d->batch * rows > (1ll << 31) - 1) return false;
@@ -197,21 +115,105 @@ int choose_splits(const amla_desc* d) {
   if (d->num_splits > 0) return d->num_splits;
   const long long rows = (long long)d->s_q * d->num_heads;
   const long long tiles = (rows + kRowsPerWg - 1) / kRowsPerWg;
+  const long long cus = device_cu_count();
   if (uses_balanced(d)) {
     // workers: one workgroup per CU over all row tiles, never more workers than blocks can exist
-    long long w = 256 / tiles > 0 ? 256 / tiles : 1;
+    long long w = cus / tiles > 0 ? cus / tiles : 1;
     const long long most = (long long)d->batch * d->max_blocks_per_seq;
     if (w > most) w = most;
+    if (w > 256) w = 256;
     return (int)w;
   }
   const long long base = (long long)d->batch * tiles;       // workgroups without splitting
-  const long long cus = 256;
   if (base >= cus) return 1;
   long long ns = (cus + base - 1) / base;
   const long long cap = d->max_blocks_per_seq / 4 > 0 ? d->max_blocks_per_seq / 4 : 1;   // >= 4 blocks per split
   if (ns > cap) ns = cap;
   if (ns > 64) ns = 64;
   return (int)(ns < 1 ? 1 : ns);
+}
+
+// Everything a call enqueues, shared by amla_decode and its variants: the decode kernel of the selected
+// family and decomposition, then the combine kernel where pieces have to be merged.  `workspace` holds
+// amla_workspace_bytes(desc) bytes (checked by the caller).
+int enqueue_decode(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* seqlens,
+                   float softmax_scale, void* out, float* lse, const amla_desc* desc, void* workspace, int ns) {
+  const bool balanced = uses_balanced(desc);
+  DecodeParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.kv = static_cast<const uint16_t*>(kv_cache);
+  p.table = block_table;
+  p.seqlens = seqlens;
+  p.out = static_cast<uint16_t*>(out);
+  p.lse = lse;
+  p.batch = desc->batch;
+  p.rows = desc->s_q * desc->num_heads;
+  p.n_tiles = (p.rows + kRowsPerWg - 1) / kRowsPerWg;
+  p.n_splits = ns;
+  p.max_blocks = desc->max_blocks_per_seq;
+  p.n_streams = balanced ? ns : desc->batch * ns;
+  p.flags = desc->flags;
+  p.num_blocks = desc->num_blocks;
+  p.heads = desc->num_heads;
+  p.causal_span = (desc->flags & AMLA_FLAG_CAUSAL) ? desc->s_q - 1 : 0;
+  p.s_q = desc->s_q;
+  p.q_lens = desc->q_lens;
+  p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  const size_t n_rows = (size_t)desc->batch * p.rows;
+  p.part_o = (ns > 1 || balanced) ? static_cast<float*>(workspace) : nullptr;
+  p.part_lse = ns > 1 ? p.part_o + (size_t)ns * n_rows * kDv : nullptr;
+  if (balanced) p.part_lse = p.part_o + ((size_t)ns + desc->batch - 1) * p.rows * kDv;
+
+  hipStream_t stream = static_cast<hipStream_t>(desc->stream);
+  const long long streams_pad = ((long long)p.n_streams + 7) / 8 * 8;
+  const long long grid = streams_pad * p.n_tiles;
+  if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
+  const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
+  AmlaDecodeKernel kern = nullptr;
+  int lds_bytes = kLdsBytes;
+  if (!uses_transposed(desc)) {
+    kern = amla_row_rescale_kernel(desc->variant, balanced);
+    lds_bytes = amla_row_rescale_lds_bytes();
+  } else if (!balanced) {
+    kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
+           : desc->variant == AMLA_RESCALE_ADD_LDEXP
+               ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
+           : desc->variant == AMLA_RESCALE_ADD
+               ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
+               : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
+  } else {
+    kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
+           : desc->variant == AMLA_RESCALE_ADD     ? (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD, true>
+                                                             : amla_decode_balanced_kernel<AMLA_RESCALE_ADD, false>)
+                                                   : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
+                                                           : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
+  }
+  if (!allow_large_lds(reinterpret_cast<const void*>(kern), lds_bytes)) return AMLA_ERR_LAUNCH;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds_bytes, stream, p);
+  if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  if (balanced) {
+    hipLaunchKernelGGL(amla_combine_balanced_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o,
+                       p.part_lse, p.seqlens, p.out, p.lse, p.batch, p.rows, ns, p.max_blocks);
+    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  } else if (ns > 1) {
+    hipLaunchKernelGGL(amla_combine_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
+                       p.out, p.lse, (int)n_rows, ns);
+    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
+  }
+  return AMLA_OK;
+}
+
+// the argument checks every decode entry point makes
+int check_decode_args(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* seqlens,
+                      float softmax_scale, void* out, const amla_desc* desc) {
+  if (q == nullptr || kv_cache == nullptr || block_table == nullptr || seqlens == nullptr || out == nullptr ||
+      desc == nullptr)
+    return AMLA_ERR_NULL_ARG;
+  if (!desc_supported(desc)) return AMLA_ERR_UNSUPPORTED;
+  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return AMLA_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(kv_cache) | reinterpret_cast<uintptr_t>(out)) & 15)
+    return AMLA_ERR_UNSUPPORTED;
+  return AMLA_OK;
 }
 
 }  // namespace
@@ -238,159 +240,15 @@ size_t amla_workspace_bytes(const amla_desc* desc) {
 
 int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* seqlens,
                 float softmax_scale, void* out, float* lse, const amla_desc* desc) {
-  if (q == nullptr || kv_cache == nullptr || block_table == nullptr || seqlens == nullptr || out == nullptr ||
-      desc == nullptr)
-    return AMLA_ERR_NULL_ARG;
-  if (!desc_supported(desc)) return AMLA_ERR_UNSUPPORTED;
-  if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return AMLA_ERR_UNSUPPORTED;
-  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(kv_cache) | reinterpret_cast<uintptr_t>(out)) & 15)
-    return AMLA_ERR_UNSUPPORTED;
-
+  const int bad = check_decode_args(q, kv_cache, block_table, seqlens, softmax_scale, out, desc);
+  if (bad != AMLA_OK) return bad;
   const int ns = choose_splits(desc);
   const size_t need = amla_workspace_bytes(desc);
-  const bool balanced = uses_balanced(desc);
-  if (ns > 1 || balanced) {
+  if (need > 0) {
     if (desc->workspace == nullptr || desc->workspace_bytes < need) return AMLA_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(desc->workspace) & 15) return AMLA_ERR_WORKSPACE;
   }
-
-  DecodeParams p;
-  p.q = static_cast<const uint16_t*>(q);
-  p.kv = static_cast<const uint16_t*>(kv_cache);
-  p.table = block_table;
-  p.seqlens = seqlens;
-  p.out = static_cast<uint16_t*>(out);
-  p.lse = lse;
-  p.batch = desc->batch;
-  p.rows = desc->s_q * desc->num_heads;
-  p.n_tiles = (p.rows + kRowsPerWg - 1) / kRowsPerWg;
-  p.n_splits = ns;
-  p.max_blocks = desc->max_blocks_per_seq;
-  p.n_streams = balanced ? ns : desc->batch * ns;
-  p.flags = desc->flags;
-  p.num_blocks = desc->num_blocks;
-  p.heads = desc->num_heads;
-  p.causal_span = (desc->flags & AMLA_FLAG_CAUSAL) ? desc->s_q - 1 : 0;
-  p.s_q = desc->s_q;
-  p.q_lens = desc->q_lens;
-  p.scale_log2e = softmax_scale * 1.4426950408889634f;
-  const size_t n_rows = (size_t)desc->batch * p.rows;
-  p.part_o = (ns > 1 || balanced) ? static_cast<float*>(desc->workspace) : nullptr;
-  p.part_lse = ns > 1 ? p.part_o + (size_t)ns * n_rows * kDv : nullptr;
-  if (balanced) p.part_lse = p.part_o + ((size_t)ns + desc->batch - 1) * p.rows * kDv;
-
-  hipStream_t stream = static_cast<hipStream_t>(desc->stream);
-  const long long streams_pad = ((long long)p.n_streams + 7) / 8 * 8;
-
-  if (!(desc->flags & AMLA_FLAG_ASM_KERNEL)) {
-    const long long grid = streams_pad * p.n_tiles;
-    if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
-    const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
-    void (*kern)(const DecodeParams) = nullptr;
-    int threads = kThreads;
-    int lds_bytes = kLdsBytes;
-    if (desc->flags & AMLA_FLAG_ROW_RESCALE) {
-      kern = amla_row_rescale_kernel(desc->variant);
-      lds_bytes = amla_row_rescale_lds_bytes();
-    } else if ((desc->flags & AMLA_FLAG_EIGHT_WAVES) && balanced) {
-      threads = kThreadsW8;
-      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
-             : desc->variant == AMLA_RESCALE_ADD_LDEXP
-                 ? (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_LDEXP, true>
-                         : amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
-             : desc->variant == AMLA_RESCALE_ADD
-                 ? (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD, true> : amla_decode_w8_balanced_kernel<AMLA_RESCALE_ADD, false>)
-                 : (lazy ? amla_decode_w8_balanced_kernel<AMLA_RESCALE_MUL, true> : amla_decode_w8_balanced_kernel<AMLA_RESCALE_MUL, false>);
-    } else if (desc->flags & AMLA_FLAG_EIGHT_WAVES) {
-      threads = kThreadsW8;
-      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_w8_kernel<AMLA_RESCALE_ADD_COMP, false>
-             : desc->variant == AMLA_RESCALE_ADD_LDEXP
-                 ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
-             : desc->variant == AMLA_RESCALE_ADD
-                 ? (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_ADD, true> : amla_decode_w8_kernel<AMLA_RESCALE_ADD, false>)
-                 : (lazy ? amla_decode_w8_kernel<AMLA_RESCALE_MUL, true> : amla_decode_w8_kernel<AMLA_RESCALE_MUL, false>);
-    } else if (desc->flags & AMLA_FLAG_PREFETCH) {
-      kern = desc->variant == AMLA_RESCALE_ADD_LDEXP
-                 ? (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_ADD_LDEXP, true>
-                         : amla_decode_prefetch_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
-             : desc->variant == AMLA_RESCALE_ADD
-                 ? (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_ADD, true> : amla_decode_prefetch_kernel<AMLA_RESCALE_ADD, false>)
-                 : (lazy ? amla_decode_prefetch_kernel<AMLA_RESCALE_MUL, true> : amla_decode_prefetch_kernel<AMLA_RESCALE_MUL, false>);
-    } else if (!balanced) {
-      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>
-             : desc->variant == AMLA_RESCALE_ADD_LDEXP
-                 ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, true> : amla_decode_kernel<AMLA_RESCALE_ADD_LDEXP, false>)
-             : desc->variant == AMLA_RESCALE_ADD
-                 ? (lazy ? amla_decode_kernel<AMLA_RESCALE_ADD, true> : amla_decode_kernel<AMLA_RESCALE_ADD, false>)
-                 : (lazy ? amla_decode_kernel<AMLA_RESCALE_MUL, true> : amla_decode_kernel<AMLA_RESCALE_MUL, false>);
-    } else {
-      kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
-             : desc->variant == AMLA_RESCALE_ADD     ? (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_ADD, true>
-                                                               : amla_decode_balanced_kernel<AMLA_RESCALE_ADD, false>)
-                                                     : (lazy ? amla_decode_balanced_kernel<AMLA_RESCALE_MUL, true>
-                                                             : amla_decode_balanced_kernel<AMLA_RESCALE_MUL, false>);
-    }
-    if (!allow_large_lds(reinterpret_cast<const void*>(kern), lds_bytes)) return AMLA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, stream, p);
-    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
-  } else {
-    // index arithmetic of the assembly kernels: mulhi-by-magic division and 32-bit row indices
-    const unsigned long long ns2 = (unsigned long long)ns * ns;
-    if (ns2 * (unsigned long long)desc->max_blocks_per_seq >= (1ull << 32) ||
-        ns2 * (unsigned long long)desc->batch >= (1ull << 32) ||
-        (unsigned long long)ns * n_rows >= (1ull << 31) || p.n_tiles * 8ll > 65535 || streams_pad / 8 > 65535 ||
-        desc->max_blocks_per_seq > (1 << 24))
-      return AMLA_ERR_UNSUPPORTED;
-    // balanced: worker ranges w T / W by the same kind of division, T <= batch * max_blocks_per_seq
-    if (balanced && (unsigned long long)ns * ns * (unsigned long long)desc->batch * desc->max_blocks_per_seq >= (1ull << 32))
-      return AMLA_ERR_UNSUPPORTED;
-    const DeviceKernels* dk = device_kernels();
-    if (dk == nullptr) return AMLA_ERR_LAUNCH;
-    AsmArgs a;
-    a.q = q;
-    a.kv = kv_cache;
-    a.table = block_table;
-    a.seqlens = seqlens;
-    a.out = out;
-    a.lse = lse;
-    a.part_o = p.part_o;
-    a.part_lse = p.part_lse;
-    a.scale_log2e = p.scale_log2e;
-    a.batch = p.batch;
-    a.rows = p.rows;
-    a.n_splits = ns;
-    a.max_blocks = p.max_blocks;
-    a.n_streams = p.n_streams;
-    a.flags = p.flags;
-    a.split_magic = ns > 1 ? (uint32_t)((1ull << 32) / (unsigned)ns) + 1u : 0u;
-    a.num_blocks = desc->num_blocks;
-    a.pad = 0;
-    a.workers = balanced ? ns : 0;
-    a.worker_magic = balanced ? (uint32_t)((1ull << 32) / (unsigned)ns) + 1u : 0u;
-    if (balanced) {
-      a.n_splits = 1;
-      a.split_magic = 0;
-    }
-    size_t arg_size = sizeof(a);
-    void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, &a, HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_size, HIP_LAUNCH_PARAM_END};
-    const int kind = desc->variant == AMLA_RESCALE_ADD ? 1 : desc->variant == AMLA_RESCALE_ADD_LDEXP ? 2 : 0;
-    const int which = kind + ((desc->flags & AMLA_FLAG_LAZY_RESCALE) ? 3 : 0) + (balanced ? 6 : 0);
-    if (hipModuleLaunchKernel(dk->fn[which], (unsigned)(8 * p.n_tiles), (unsigned)(streams_pad / 8), 1, kThreads, 1, 1,
-                              0, stream, nullptr, config) != hipSuccess) {
-      (void)hipGetLastError();
-      return AMLA_ERR_LAUNCH;
-    }
-  }
-  if (balanced) {
-    hipLaunchKernelGGL(amla_combine_balanced_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o,
-                       p.part_lse, p.seqlens, p.out, p.lse, p.batch, p.rows, ns, p.max_blocks);
-    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
-  } else if (ns > 1) {
-    hipLaunchKernelGGL(amla_combine_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
-                       p.out, p.lse, (int)n_rows, ns);
-    if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
-  }
-  return AMLA_OK;
+  return enqueue_decode(q, kv_cache, block_table, seqlens, softmax_scale, out, lse, desc, desc->workspace, ns);
 }
 
 int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* stream) {
@@ -412,6 +270,20 @@ int amla_mfma_probe(int32_t iters, int32_t workgroups, double* flops, void* stre
   if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   // 4 waves per workgroup, 4 MFMAs of 32 x 32 x 16 multiply-adds per iteration and wave
   *flops = (double)iters * 4.0 * 4.0 * (2.0 * 32 * 32 * 16) * (double)workgroups;
+  return AMLA_OK;
+}
+
+int amla_device_info(int32_t* compute_units, int32_t* clock_khz) {
+  if (compute_units == nullptr || clock_khz == nullptr) return AMLA_ERR_NULL_ARG;
+  int dev = -1, cus = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return AMLA_ERR_LAUNCH;
+  }
+  *compute_units = cus;
+  *clock_khz = khz;
   return AMLA_OK;
 }
 

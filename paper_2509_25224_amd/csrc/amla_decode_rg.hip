@@ -515,12 +515,88 @@ void amla_decode_rg_kernel(const DecodeParams p) {
                                (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0);
 }
 
+// Balanced decomposition (ragged batches, causal mask among the s_q tokens, per-sequence query counts):
+// workgroup = (worker, row tile).  The 64-key blocks of all sequences are laid end to end and cut into
+// p.n_streams equal worker ranges (amla_plan.h); a worker walks its range sequence by sequence, every (worker,
+// sequence) pair is a piece with its own softmax state.  A piece that covers its whole sequence writes the
+// final result, any other writes a partial row set into slot worker + sequence of the workspace, which
+// amla_combine_balanced_kernel merges.
+template <int VARIANT>
+__global__ __launch_bounds__(kThreads) AMLA_ONE_WAVE_PER_SIMD
+void amla_decode_rg_balanced_kernel(const DecodeParams p) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
+  LDS_PTR(uint8_t) smem = (LDS_PTR(uint8_t))smem_raw;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  acc_claim();
+
+  // workers go round-robin over the 8 XCDs; the row tiles of one worker sit next to each other on the same
+  // XCD and share the worker's KV blocks in that XCD's L2
+  const int xcd = blockIdx.x & 7;
+  const int slot = blockIdx.x >> 3;
+  const int stream = (slot / p.n_tiles) * 8 + xcd;
+  const int tile = slot % p.n_tiles;
+  if (stream >= p.n_streams) return;
+
+  // total number of blocks of the batch, then this worker's range of the concatenated list
+  int total = 0;
+  for (int c = 0; c < p.batch; c += 64) {
+    const int i = c + lane;
+    total += wave_sum(i < p.batch ? plan_blocks_of(plan_len(p.seqlens[i], p.max_blocks, kBlock), kBlock) : 0);
+  }
+  total = __builtin_amdgcn_readfirstlane(total);
+  const long long g0 = plan_worker_begin(stream, total, p.n_streams);
+  const long long g1 = plan_worker_begin(stream + 1, total, p.n_streams);
+  if (g0 >= g1) return;
+  // the sequence that holds global block g0, and g0's position in it
+  int b0 = -1, jstart = 0, base = 0;
+  for (int c = 0; c < p.batch && b0 < 0; c += 64) {
+    const int i = c + lane;
+    const int nbi = i < p.batch ? plan_blocks_of(plan_len(p.seqlens[i], p.max_blocks, kBlock), kBlock) : 0;
+    const int incl = wave_inclusive_scan(nbi, lane);
+    const int excl = incl - nbi;
+    const bool hit = (long long)base + excl <= g0 && g0 < (long long)base + incl;
+    const unsigned long long mask = __builtin_amdgcn_ballot_w64(hit);
+    if (mask != 0) {
+      const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(mask));
+      b0 = c + l;
+      jstart = (int)(g0 - ((long long)base + __builtin_amdgcn_readlane(excl, l)));
+    }
+    base += __builtin_amdgcn_readlane(incl, 63);
+  }
+  if (b0 < 0) return;   // unreachable when g0 < total
+
+  const int row = tile * kRowsPerWg + wave * 32 + (lane & 31);   // this lane's query row within the sequence
+  PlanWalk walk = {b0, jstart, g1 - g0};
+  while (walk.left > 0 && walk.b < p.batch) {
+    const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[walk.b]), p.max_blocks, kBlock);
+    PlanPiece piece;
+    if (!plan_next(&walk, plan_blocks_of(kv_len, kBlock), &piece)) continue;
+    // A row's limit lies causal_shift keys before the sequence's end.  Causal mask among the q_len query
+    // tokens of the sequence: token t sits q_len - 1 - t positions before the end of the cache and sees the
+    // keys up to and including its own, kv_len - (q_len - 1 - t) of them.  A padding token (t >= q_len) sees
+    // none and ends as out = 0, lse = -inf like any row without keys.  mask_span is the largest shift of the
+    // piece (wave-uniform): blocks closer than that to the end need the mask.
+    int q_len = p.s_q;
+    if (p.q_lens != nullptr) q_len = min(max(__builtin_amdgcn_readfirstlane(p.q_lens[piece.b]), 0), p.s_q);
+    const int mask_span = q_len < p.s_q ? kNoKeys : p.causal_span;
+    const int t_row = row / p.heads;
+    const int causal_shift = t_row >= q_len ? kNoKeys : (p.causal_span != 0 ? q_len - 1 - t_row : 0);
+    decode_piece<VARIANT, true>(p, smem, lane, wave, piece.b, kv_len, piece.j0, piece.j1, tile, piece.full != 0,
+                                ((size_t)stream + piece.b) * p.rows, causal_shift, mask_span);
+  }
+}
+
 }  // namespace
 
-// The kernel of this file for a rescale variant (AMLA_RESCALE_MUL, _ADD or _ADD_COMP), for amla_decode to launch
-// with 256 threads and amla_row_rescale_lds_bytes() of dynamic LDS.
+// The kernels of this file for a rescale variant (AMLA_RESCALE_MUL, _ADD or _ADD_COMP), for amla_decode to
+// launch with 256 threads and amla_row_rescale_lds_bytes() of dynamic LDS.
 int amla_row_rescale_lds_bytes() { return kRgLdsBytes; }
-AmlaDecodeKernel amla_row_rescale_kernel(int variant) {
+AmlaDecodeKernel amla_row_rescale_kernel(int variant, bool balanced) {
+  if (balanced)
+    return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD_COMP>
+           : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD>
+                                            : amla_decode_rg_balanced_kernel<AMLA_RESCALE_MUL>;
   return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_kernel<AMLA_RESCALE_ADD_COMP>
          : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_kernel<AMLA_RESCALE_ADD>
                                           : amla_decode_rg_kernel<AMLA_RESCALE_MUL>;

@@ -14,14 +14,11 @@ if ROOT not in sys.path:
 # ahead of the listed ones.
 GPU_FILE_ORDER = [
     "test_gpu_parity.py",
-    "test_gpu_parity_row_rescale.py",
-    "test_gpu_parity_lazy.py",
+    "test_gpu_parity_workers.py",
     "test_gpu_parity_scale_comp.py",
-    "test_gpu_parity_w_eight_waves.py",
-    "test_gpu_parity_v_prefetch.py",
+    "test_gpu_parity_lazy.py",
     "test_gpu_parity_y_long_context.py",
     "test_gpu_parity_t_graph.py",
-    "test_gpu_parity_workers.py",
     "test_gpu_parity_tables_3_4.py",
     "test_zz_no_alloc.py",
 ]

@@ -248,6 +248,9 @@ enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
+enum { hipDeviceAttributeMultiprocessorCount = 63, hipDeviceAttributeClockRate = 5 };
+// no device here: the query fails and the library falls back to its documented default of 256 compute units
+inline hipError_t hipDeviceGetAttribute(int*, int, int) { return hipErrorNotSupported; }
 // a __device__ variable is an ordinary host variable here, and its "device address" is its address
 #define __align__(n) __attribute__((aligned(n)))
 #define HIP_SYMBOL(x) (&(x))

@@ -83,28 +83,24 @@ def test_argument_validation_error_codes(amla):
     assert _call(amla, split) == amla.AMLA_ERR_WORKSPACE                 # too small
 
 
-def test_assembly_kernels_are_gated_off(amla, monkeypatch):
-    monkeypatch.delenv("AMLA_ENABLE_ASM_KERNELS", raising=False)
-    d = amla.make_desc(2, 1, 16, 8, 4, flags=amla.AMLA_FLAG_ASM_KERNEL)
-    assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
+def test_retired_flag_bits_are_rejected(amla):
+    for bit in (4, 32, 64, 256):
+        d = amla.make_desc(2, 1, 16, 8, 4, flags=bit)
+        assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
+        assert amla.amla_effective_splits(d) == 0
 
 
-def test_balanced_decomposition_is_gated_off_and_sized(amla, monkeypatch):
-    monkeypatch.delenv("AMLA_ENABLE_BALANCED", raising=False)
-    d = amla.make_desc(32, 2, 128, 5000, 256, flags=amla.AMLA_FLAG_BALANCED)
-    assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
-    assert amla.amla_effective_splits(d) == 0 and amla.amla_workspace_bytes(d) == 0
-    monkeypatch.setenv("AMLA_ENABLE_BALANCED", "1")
-    workers = amla.amla_effective_splits(d)
-    assert workers == 128                                    # 256 workgroups over two row tiles
-    assert amla.amla_workspace_bytes(d) == (workers + 32 - 1) * 256 * 513 * 4
-    assert _call(amla, d) == amla.AMLA_ERR_WORKSPACE         # pieces always need their slots
-    d.flags |= amla.AMLA_FLAG_ASM_KERNEL
-    assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
-    c = amla.make_desc(32, 2, 128, 5000, 256, flags=amla.AMLA_FLAG_CAUSAL)    # the mask selects the balanced kernels
-    assert amla.amla_effective_splits(c) == 128 and amla.amla_workspace_bytes(c) == (128 + 31) * 256 * 513 * 4
-    monkeypatch.delenv("AMLA_ENABLE_BALANCED")
-    assert _call(amla, c) == amla.AMLA_ERR_UNSUPPORTED
+def test_balanced_decomposition_is_sized(amla):
+    for family in (0, amla.AMLA_FLAG_TRANSPOSED_ACC):
+        d = amla.make_desc(32, 2, 128, 5000, 256, flags=amla.AMLA_FLAG_BALANCED | family)
+        workers = amla.amla_effective_splits(d)
+        assert workers == 128                                    # one workgroup per compute unit (256) over two row tiles
+        assert amla.amla_workspace_bytes(d) == (workers + 32 - 1) * 256 * 513 * 4
+        assert _call(amla, d) == amla.AMLA_ERR_WORKSPACE         # pieces always need their slots
+        c = amla.make_desc(32, 2, 128, 5000, 256, flags=amla.AMLA_FLAG_CAUSAL | family)   # the mask selects the balanced kernels
+        assert amla.amla_effective_splits(c) == 128 and amla.amla_workspace_bytes(c) == (128 + 31) * 256 * 513 * 4
+    ld = amla.make_desc(32, 2, 128, 5000, 256, variant=amla.AMLA_RESCALE_ADD_LDEXP, flags=amla.AMLA_FLAG_BALANCED)
+    assert _call(amla, ld) == amla.AMLA_ERR_UNSUPPORTED
 
 
 def test_workspace_and_split_queries(amla):

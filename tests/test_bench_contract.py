@@ -75,22 +75,31 @@ def test_default_line_has_the_contract_keys(fake_gpu, monkeypatch):
     assert roof["kernel"].startswith("amla_decode")
     cpu = r["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["unit"] == "TFLOP/s" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
-    # auto: every exponent-add candidate was tried against the strict add kernel, and only those
-    assert set(r["config"]["auto_self_check"]) - {"quick_ms"} == {
-        "add_lazy", "add_comp", "add_ldexp", "add_ldexp_lazy", "add_pf", "add_lazy_pf", "add_ldexp_pf",
-        "add_ldexp_lazy_pf", "add_w8", "add_lazy_w8", "add_ldexp_w8", "add_ldexp_lazy_w8", "add_comp_w8"}
-    assert r["config"]["variant"] in r["config"]["auto_self_check"]["quick_ms"]
-    assert not r["config"]["variant"].startswith("mul")
-    assert {"mul", "add", "mul_lazy", "add_lazy"} <= set(r["rescale"]["tflops"])
+    # the headline kernel is fixed: the strict exponent add on the default (row-rescale) kernels
+    assert r["config"]["variant"] == "add" and roof["kernel"] == "amla_decode_rg_kernel"
+    assert r["config"]["decomposition"] == "equal_share" and r["config"]["kv_splits"] >= 1
+    par = r["parity"]
+    assert par["rows_checked"] > 0 and par["kernel"] == roof["kernel"] and par["variant"] == "add"
+    assert isinstance(par["max_out_err"], float) and isinstance(par["max_lse_err"], float) and par["passed"] is False
+    assert {"mul", "add", "add_comp", "mul_t", "add_t", "mul_lazy", "add_lazy", "add_ldexp"} <= set(r["rescale"]["tflops"])
+    assert r["rescale"]["add_over_mul_speedup"] > 0 and r["rescale"]["add_t_over_mul_t_speedup"] > 0
 
 
 def test_a_named_variant_is_the_one_timed(fake_gpu, monkeypatch):
     from paper_2509_25224_amd import amla
-    r = _run(monkeypatch, ["--config", "0", "--steps", "2", "--warmup", "0", "--variant", "mul_lazy_w8", "--no-ab",
+    r = _run(monkeypatch, ["--config", "0", "--steps", "2", "--warmup", "0", "--variant", "mul_lazy", "--no-ab",
                            "--no-cpu-baseline", "--no-mfma-probe"])
-    assert r["config"]["variant"] == "mul_lazy_w8" and r["roofline"]["kernel"] == "amla_decode_w8_kernel"
-    assert set(fake_gpu) == {(amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE | amla.AMLA_FLAG_EIGHT_WAVES)}
-    assert "cpu_baseline" not in r and "rescale" not in r
+    assert r["config"]["variant"] == "mul_lazy" and r["roofline"]["kernel"] == "amla_decode_kernel"
+    assert set(fake_gpu) == {(amla.AMLA_RESCALE_MUL, amla.AMLA_FLAG_LAZY_RESCALE)}
+    assert "cpu_baseline" not in r and "rescale" not in r and "parity" not in r
+
+
+def test_balanced_decomposition_names_its_kernel(fake_gpu, monkeypatch):
+    from paper_2509_25224_amd import amla
+    r = _run(monkeypatch, ["--config", "0", "--steps", "2", "--warmup", "0", "--balanced", "--no-ab",
+                           "--no-cpu-baseline", "--no-mfma-probe"])
+    assert r["roofline"]["kernel"] == "amla_decode_rg_balanced_kernel" and r["config"]["decomposition"] == "balanced"
+    assert set(fake_gpu) == {(amla.AMLA_RESCALE_ADD, amla.AMLA_FLAG_BALANCED)}
 
 
 def test_more_than_one_gpu_is_refused(monkeypatch):

@@ -19,16 +19,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SHIM = os.path.join(ROOT, "tests", "cpu_build")
 CLANG = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang++")
 MUL, ADD, COMP, LDEXP = 0, 1, 2, 3
-NO_SKIP, LAZY, ASM, BALANCED, CAUSAL, PREFETCH, W8 = 1, 2, 4, 8, 16, 32, 64
+NO_SKIP, LAZY, BALANCED, CAUSAL, TRANSPOSED = 1, 2, 8, 16, 128
 FLAGS = ["-std=c++20", "-O0", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
          "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi"]
 
 
 def build(tmp, extra=()):
     out = str(tmp / "decode_cpu")
-    # the code object of the hand-scheduled kernels cannot be loaded on the CPU: one byte stands in
-    (tmp / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
-    (tmp / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     subprocess.run([CLANG, "-x", "c++", *FLAGS, *extra, "-I" + SHIM, "-I" + os.path.join(ROOT, "include"),
                     "-I" + str(tmp), os.path.join(SHIM, "decode_cpu.cpp"), "-o", out], check=True)
     return out
@@ -51,9 +48,8 @@ def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0, q_lens
             f.write(np.ascontiguousarray(a).tobytes())
         if q_lens is not None:
             f.write(np.ascontiguousarray(np.asarray(q_lens, np.int32)).tobytes())
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", AMLA_ENABLE_BALANCED="1")
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
     env.pop("LD_PRELOAD", None)
-    env.pop("AMLA_ENABLE_ASM_KERNELS", None)
     r = subprocess.run([exe, inp, outp], capture_output=True, text=True, env=env, timeout=900)
     assert r.returncode == 0, r.stderr[-3000:]
     raw = np.fromfile(outp, dtype=np.uint8)
@@ -85,10 +81,13 @@ def check(out, lse, case, peaked=False, causal=False, q_lens=None):
         assert np.abs(lse[fin] - want_lse[fin]).max() <= 1e-3
 
 
-KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"),
+# (variant, flags).  Without a flag the row-rescale kernels run (the default family); AMLA_FLAG_TRANSPOSED_ACC, the
+# lazy flag and the ldexp variant select the transposed-accumulator kernels.
+KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((COMP, 0), id="add_comp"),
+         pytest.param((MUL, TRANSPOSED), id="mul_t"), pytest.param((ADD, TRANSPOSED), id="add_t"),
+         pytest.param((COMP, TRANSPOSED), id="add_comp_t"),
          pytest.param((MUL, LAZY), id="mul_lazy"), pytest.param((ADD, LAZY), id="add_lazy"),
-         pytest.param((COMP, 0), id="add_comp"), pytest.param((LDEXP, 0), id="add_ldexp"),
-         pytest.param((LDEXP, LAZY), id="add_ldexp_lazy")]
+         pytest.param((LDEXP, 0), id="add_ldexp"), pytest.param((LDEXP, LAZY), id="add_ldexp_lazy")]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -99,112 +98,14 @@ def test_tiny_config(exe, tmp_path, kind):
     check(out, lse, case)
 
 
-@pytest.mark.parametrize("kind", [k for k in KINDS if k.values[0][0] != COMP])
-def test_prefetching_build_of_the_loop_is_bit_identical(exe, tmp_path, kind):
-    """AMLA_FLAG_PREFETCH moves the LDS operand reads one MFMA ahead and nothing else: same bits, on a
-    ragged split case (partial last block, an empty share, rows past the end of the row range)."""
-    variant, flags = kind
-    case = _ragged(63)
-    a = run_cpu(exe, tmp_path, case, variant, flags=flags, ns=3)
-    b = run_cpu(exe, tmp_path, case, variant, flags=flags | PREFETCH, ns=3)
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
-    check(b[0], b[1], case)
-    tiny = wl.make_config(0)
-    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=flags | PREFETCH)
-    check(out, lse, tiny)
-
-
-NO_COMP = [k for k in KINDS if k.values[0][0] != COMP]
-
-
-@pytest.mark.parametrize("kind", KINDS)
-def test_eight_wave_kernel(exe, tmp_path, kind):
-    """AMLA_FLAG_EIGHT_WAVES (16 rows per wave, 16 x 16 x 32 MFMA): the tiny configuration; the ragged
-    case unsplit and in three shares (partial last blocks, an empty sequence and an empty share, a second
-    row tile with 32 of 128 rows valid); wide logits that move the reference several times."""
-    variant, flags = kind
-    tiny = wl.make_config(0)
-    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=flags | W8)
-    check(out, lse, tiny)
-    case = _ragged(64)
-    for ns in (1, 3):
-        out, lse, splits = run_cpu(exe, tmp_path, case, variant, flags=flags | W8, ns=ns)
-        assert splits == ns
-        check(out, lse, case)
-        assert np.all(out[2] == 0) and np.all(np.isneginf(lse[2]))
-    wide = wl.make_case("wide8", 66, batch=1, s_q=1, heads=16, seqlens=[700], q_sigma=6.0)
-    out, lse, _ = run_cpu(exe, tmp_path, wide, variant, flags=flags | W8)
-    check(out, lse, wide, peaked=True)
-
-
-def test_kernels_reproduce_the_printed_accuracy_of_section_5_1(exe, tmp_path):
-    """Tables 3 and 4, N(0, 1) column, through the kernels' own source on the CPU: 32 rows of the paper's
-    accuracy experiment (8K context, scale 1/sqrt(576), V = K[:, :512]).  The MUL kernel runs Algorithm 1's
-    arithmetic (printed 'Base' 1.77e-3), the compensated kernel Algorithm 2's (printed 'AMLA' 1.81e-3); the
-    eight-wave kernels sum in another order and land on the same figures."""
-    case = wl.make_accuracy_case("n", 1.0, batch=1, heads=32)
-    want, _ = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    printed = {MUL: 1.77e-3, COMP: 1.81e-3}
-    for variant, flags in ((COMP, 0), (MUL, W8), (COMP, W8)):
-        out, lse, _ = run_cpu(exe, tmp_path, case, variant, flags=flags, ns=1)
-        err = orc.frobenius_error(out.reshape(-1, 512), want.reshape(-1, 512))
-        assert abs(err - printed[variant]) < 0.03 * printed[variant], (variant, flags, err)
-
-
-def test_eight_wave_kernel_no_skip_flag_changes_nothing(exe, tmp_path):
-    case = wl.make_case("noskip8", 67, batch=1, s_q=1, heads=8, seqlens=[200])
-    a = run_cpu(exe, tmp_path, case, ADD, flags=W8)
-    b = run_cpu(exe, tmp_path, case, ADD, flags=W8 | NO_SKIP)
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
-
-
-def test_eight_waves_are_rejected_where_they_do_not_exist(exe, tmp_path):
-    case = wl.make_config(0)
-    run_cpu(exe, tmp_path, case, COMP, flags=W8 | LAZY, expect_status=-2)
-    run_cpu(exe, tmp_path, case, ADD, flags=W8 | ASM, expect_status=-2)
-    run_cpu(exe, tmp_path, case, ADD, flags=W8 | PREFETCH, expect_status=-2)
-
-
-@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, LAZY), 7), ((LDEXP, 0), 41), ((LDEXP, LAZY), 2),
-                                          ((COMP, 0), 5)])
-def test_eight_wave_balanced_kernels(exe, tmp_path, kind, workers):
-    """The eight-wave build of the balanced kernels on the cases of the four-wave one: the ragged batch
-    over worker counts below, at and above the number of sequences and blocks; the causal mask around
-    block boundaries; per-sequence query counts with and without the mask."""
-    variant, flags = kind
-    case = _ragged(68)
-    out, lse, splits = run_cpu(exe, tmp_path, case, variant, flags=flags | W8 | BALANCED, ns=workers)
-    assert splits == (workers if workers else min(128, case.batch * case.max_blocks_per_seq))
-    check(out, lse, case)
-    assert np.all(out[2] == 0)
-    causal = wl.make_case("causal8", 69, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
-    q_lens = [4, 2, 3, 1, 0, 3, 4]
-    # one of the three mask / count combinations per parameter set (all three are covered over the sets)
-    masked, counts = [(True, None), (False, q_lens), (True, q_lens)][workers % 3]
-    out, lse, _ = run_cpu(exe, tmp_path, causal, variant, flags=flags | W8 | (CAUSAL if masked else BALANCED),
-                          ns=workers, q_lens=counts)
-    check(out, lse, causal, causal=masked, q_lens=counts)
-    if counts is None:
-        assert np.all(out[0, :3] == 0) and np.all(np.isneginf(lse[0, :3]))
-    else:
-        for b, k in enumerate(counts):
-            assert np.all(out[b, k:] == 0) and np.all(np.isneginf(lse[b, k:]))
-
-
-def test_prefetch_is_rejected_where_it_does_not_exist(exe, tmp_path):
-    case = wl.make_config(0)
-    run_cpu(exe, tmp_path, case, COMP, flags=PREFETCH, expect_status=-2)
-    run_cpu(exe, tmp_path, case, ADD, flags=PREFETCH | BALANCED, expect_status=-2)
-    run_cpu(exe, tmp_path, case, ADD, flags=PREFETCH | CAUSAL, expect_status=-2)
-
-
 def _ragged(seed, heads=80):
     # lengths 1, 63, empty, 64, 65, and two of a few blocks; heads * s_q = 160 rows: two row tiles, the
     # second with 32 valid rows; spare blocks in the pool and -1 in the unused table entries
     return wl.make_case("edges", seed, batch=7, s_q=2, heads=heads, seqlens=[1, 63, 0, 64, 65, 200, 330], spare_frac=0.25)
 
 
-@pytest.mark.parametrize("kind,ns", [((MUL, 0), 1), ((ADD, 0), 3), ((ADD, LAZY), 0), ((LDEXP, 0), 2)])
+@pytest.mark.parametrize("kind,ns", [((MUL, 0), 1), ((ADD, 0), 3), ((COMP, 0), 2), ((MUL, TRANSPOSED), 1), ((ADD, TRANSPOSED), 3),
+                                     ((ADD, LAZY), 0), ((LDEXP, 0), 2)])
 def test_ragged_equal_share_splits(exe, tmp_path, kind, ns):
     case = _ragged(51)
     out, lse, splits = run_cpu(exe, tmp_path, case, kind[0], flags=kind[1], ns=ns)
@@ -213,22 +114,26 @@ def test_ragged_equal_share_splits(exe, tmp_path, kind, ns):
     assert np.all(out[2] == 0)
 
 
-@pytest.mark.parametrize("kind,workers", [((MUL, 0), 3), ((ADD, 0), 8), ((ADD, LAZY), 41), ((COMP, 0), 1),
-                                          ((MUL, LAZY), 5), ((ADD, 0), 0)])
+@pytest.mark.parametrize("kind,workers", [((MUL, 0), 3), ((ADD, 0), 8), ((ADD, 0), 41), ((COMP, 0), 1), ((MUL, 0), 5), ((ADD, 0), 0),
+                                          ((MUL, TRANSPOSED), 3), ((ADD, TRANSPOSED), 8), ((ADD, LAZY), 41),
+                                          ((COMP, TRANSPOSED), 1), ((MUL, LAZY), 5)])
 def test_ragged_balanced_decomposition(exe, tmp_path, kind, workers):
     """Worker counts below, at and above the number of sequences and (41) above the number of blocks:
     pieces that start mid-sequence, workers that cross several sequences, full pieces written in
     final form, an empty sequence whose zeros come from the combine kernel."""
     case = _ragged(52)
     out, lse, splits = run_cpu(exe, tmp_path, case, kind[0], flags=kind[1] | BALANCED, ns=workers)
-    # default: 256 workgroups over the two row tiles, but never more workers than blocks can exist
+    # default: one workgroup per compute unit (256 where no device says otherwise) over the two row tiles,
+    # but never more workers than blocks can exist
     assert splits == (workers if workers else min(128, case.batch * case.max_blocks_per_seq))
     check(out, lse, case)
     assert np.all(out[2] == 0)
 
 
 @pytest.mark.parametrize("kind", [pytest.param((ADD, LAZY), id="add_lazy"), pytest.param((MUL, LAZY), id="mul_lazy"),
-                                  pytest.param((COMP, 0), id="add_comp"), pytest.param((LDEXP, 0), id="add_ldexp")])
+                                  pytest.param((COMP, 0), id="add_comp"), pytest.param((COMP, TRANSPOSED), id="add_comp_t"),
+                                  pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"),
+                                  pytest.param((LDEXP, 0), id="add_ldexp")])
 def test_wide_logits_move_the_reference(exe, tmp_path, kind):
     """Logit spread of tens of base-2 units over 11 blocks: the lazy kernels take the deferred update
     several times, the compensated one rescales with mantissa terms of both signs."""
@@ -237,16 +142,18 @@ def test_wide_logits_move_the_reference(exe, tmp_path, kind):
     check(out, lse, case, peaked=True)
 
 
-def test_no_skip_flag_keeps_the_result(exe, tmp_path):
+@pytest.mark.parametrize("family", [0, TRANSPOSED])
+def test_no_skip_flag_keeps_the_result(exe, tmp_path, family):
     case = wl.make_case("noskip", 54, batch=1, s_q=1, heads=8, seqlens=[200])
-    a = run_cpu(exe, tmp_path, case, ADD, flags=0)
-    b = run_cpu(exe, tmp_path, case, ADD, flags=NO_SKIP)
+    a = run_cpu(exe, tmp_path, case, ADD, flags=family)
+    b = run_cpu(exe, tmp_path, case, ADD, flags=family | NO_SKIP)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
     check(b[0], b[1], case)
 
 
-@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, 0), 3), ((ADD, LAZY), 7), ((COMP, 0), 2),
-                                          ((MUL, LAZY), 11)])
+@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, 0), 3), ((ADD, 0), 7), ((COMP, 0), 2), ((MUL, 0), 11),
+                                          ((MUL, TRANSPOSED), 0), ((ADD, TRANSPOSED), 3), ((ADD, LAZY), 7),
+                                          ((COMP, TRANSPOSED), 2), ((MUL, LAZY), 11)])
 def test_causal_mask_among_the_query_tokens(exe, tmp_path, kind, workers):
     """s_q = 4 tokens, lengths around block boundaries: tokens with no key at all (kv_len 1), limits that
     end exactly at or fall into the previous block (kv_len 64, 65, 66, 130: whole blocks masked for the
@@ -262,8 +169,10 @@ def test_causal_mask_among_the_query_tokens(exe, tmp_path, kind, workers):
     assert np.abs(out[4, 0] - plain[4, 0]).max() > 0.05
 
 
-@pytest.mark.parametrize("kind,workers,causal", [((MUL, 0), 0, False), ((ADD, 0), 3, True), ((ADD, LAZY), 5, False),
-                                                 ((COMP, 0), 2, True), ((MUL, LAZY), 9, True)])
+@pytest.mark.parametrize("kind,workers,causal", [((MUL, 0), 0, False), ((ADD, 0), 3, True), ((ADD, 0), 5, False),
+                                                 ((COMP, 0), 2, True), ((MUL, 0), 9, True),
+                                                 ((MUL, TRANSPOSED), 0, False), ((ADD, TRANSPOSED), 3, True),
+                                                 ((ADD, LAZY), 5, False), ((COMP, TRANSPOSED), 2, True), ((MUL, LAZY), 9, True)])
 def test_per_sequence_query_counts(exe, tmp_path, kind, workers, causal):
     """q_lens: sequences with all, some, one and none of the s_q = 4 tokens (40 heads: one wave holds rows
     of two tokens, so real and padding rows share a wave), with and without the mask; padding rows come
@@ -281,9 +190,10 @@ def test_per_sequence_query_counts(exe, tmp_path, kind, workers, causal):
     check(out2, lse2, case, causal=causal, q_lens=[4, 0, 3, 1, 0, 3, 4])
 
 
-def test_query_counts_need_the_balanced_kernels(exe, tmp_path):
+def test_query_counts_select_the_balanced_kernels(exe, tmp_path):
     case = wl.make_config(0)
-    run_cpu(exe, tmp_path, case, ADD, q_lens=[1], expect_status=-2)
+    out, lse, _ = run_cpu(exe, tmp_path, case, ADD, q_lens=[1])
+    check(out, lse, case, q_lens=[1])
 
 
 def test_auto_split_of_a_long_single_sequence(exe, tmp_path):
@@ -297,8 +207,9 @@ def test_entry_point_rejects_what_it_documents(exe, tmp_path):
     case = wl.make_config(0)
     run_cpu(exe, tmp_path, case, COMP, flags=LAZY, expect_status=-2)
     run_cpu(exe, tmp_path, case, 7, expect_status=-2)
-    run_cpu(exe, tmp_path, case, ADD, flags=ASM, expect_status=-2)            # gate closed
-    run_cpu(exe, tmp_path, case, ADD, flags=ASM | BALANCED, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=4, expect_status=-2)              # flag bits that are not (or no longer) defined
+    run_cpu(exe, tmp_path, case, ADD, flags=32, expect_status=-2)
+    run_cpu(exe, tmp_path, case, ADD, flags=64, expect_status=-2)
     run_cpu(exe, tmp_path, case, LDEXP, flags=BALANCED, expect_status=-2)     # equal-share kernels only
 
 
@@ -306,8 +217,9 @@ def test_random_shapes_lengths_and_decompositions(exe, tmp_path):
     """Seeded sweep over small problems: batch, heads, s_q, lengths (with empty sequences and ragged
     last blocks), rescale variant, flags, split factor or worker count."""
     rng = np.random.default_rng(56)
-    kinds = [(MUL, 0), (ADD, 0), (MUL, LAZY), (ADD, LAZY), (COMP, 0), (ADD, NO_SKIP)]
-    for trial in range(10):
+    kinds = [(MUL, 0), (ADD, 0), (COMP, 0), (ADD, NO_SKIP), (MUL, TRANSPOSED), (ADD, TRANSPOSED), (MUL, LAZY), (ADD, LAZY),
+             (COMP, TRANSPOSED), (ADD, NO_SKIP | TRANSPOSED)]
+    for trial in range(14):
         batch = int(rng.integers(1, 6))
         s_q = int(rng.integers(1, 4))
         heads = int(rng.choice([1, 8, 40, 70]))
@@ -351,15 +263,13 @@ def test_thread_sanitizer_sees_no_race_between_waves(tmp_path):
     of a barrier is a data race between the threads that stand in for the waves."""
     if not os.path.exists(CLANG):
         pytest.skip("no clang++ to build the CPU harness with")
-    (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
-    (tmp_path / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     exe = str(tmp_path / "decode_tsan")
     subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=thread", "-pthread",
                     "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi", "-I" + SHIM,
                     "-I" + os.path.join(ROOT, "include"), "-I" + str(tmp_path), os.path.join(SHIM, "decode_cpu.cpp"),
                     "-o", exe], check=True)
     case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
-    for flags, ns in ((BALANCED, 3), (0, 2), (PREFETCH, 2), (W8, 2), (W8 | BALANCED, 3)):
+    for flags, ns in ((BALANCED, 3), (0, 2), (TRANSPOSED | BALANCED, 3), (TRANSPOSED, 2)):
         out, lse, _ = run_cpu(exe, tmp_path, case, ADD, flags=flags, ns=ns)      # a report makes the exit code non-zero
         check(out, lse, case)
 
@@ -393,18 +303,16 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
         pytest.skip("no clang++ to build the CPU harness with")
     csrc = tmp_path / "paper_2509_25224_amd" / "csrc"
     csrc.mkdir(parents=True)
-    for name in ("amla_decode.hip", "amla_decode_kernels.inc", "amla_decode_equal_share.inc", "amla_decode_piece.inc",
-                 "amla_decode_w8.inc", "amla_decode_w8_piece.inc", "amla_decode_balanced.inc", "amla_plan.h"):
+    for name in ("amla_decode.hip", "amla_decode_rg.hip", "amla_device.h", "amla_decode_kernels.inc",
+                 "amla_decode_equal_share.inc", "amla_decode_piece.inc", "amla_decode_balanced.inc", "amla_plan.h"):
         shutil.copy(os.path.join(ROOT, "paper_2509_25224_amd", "csrc", name), csrc / name)
-    piece = (csrc / "amla_decode_piece.inc").read_text()
+    piece = (csrc / "amla_decode_rg.hip").read_text()
     barrier = "  // the previous piece's last tile may still be read by a slower wave\n  __syncthreads();\n"
     assert barrier in piece
-    (csrc / "amla_decode_piece.inc").write_text(piece.replace(barrier, ""))
+    (csrc / "amla_decode_rg.hip").write_text(piece.replace(barrier, ""))
     shim = tmp_path / "tests" / "cpu_build"
     shutil.copytree(os.path.join(SHIM, "hip"), shim / "hip")
     shutil.copy(os.path.join(SHIM, "decode_cpu.cpp"), shim / "decode_cpu.cpp")
-    (tmp_path / "amla_decode_gfx950.hsaco.inc").write_text("0,\n")
-    (tmp_path / "amla_decode_gfx950_safe.hsaco.inc").write_text("0,\n")
     case = wl.make_case("edges", 58, batch=4, s_q=2, heads=80, seqlens=[63, 0, 65, 200], spare_frac=0.25)
     exe = str(tmp_path / "decode_thread")
     subprocess.run([CLANG, "-x", "c++", "-std=c++20", "-O0", "-g", "-fsanitize=thread", "-pthread",
@@ -421,29 +329,26 @@ def test_the_harness_notices_a_missing_barrier_between_pieces(tmp_path):
     assert seen
 
 
-ROW = 128
-
-
 @pytest.mark.parametrize("variant", [MUL, ADD, COMP])
 def test_row_rescale_kernel(exe, tmp_path, variant):
-    """AMLA_FLAG_ROW_RESCALE (accumulator laid out query row by register, rescale per moved row): the tiny
+    """The row-rescale kernels (accumulator laid out query row by register, rescale per moved row): the tiny
     configuration; the ragged case unsplit and in three shares (partial last blocks, an empty sequence and an
     empty share, a second row tile with 32 of 128 rows valid); wide logits that move the reference of many
     rows several times; NaN bit patterns in the cache slots past a sequence's end (the kernel clears them on
     chip); the no-skip flag, which must not change a bit of the ADD variant's result."""
     tiny = wl.make_config(0)
-    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant, flags=ROW)
+    out, lse, _ = run_cpu(exe, tmp_path, tiny, variant)
     check(out, lse, tiny)
     case = _ragged(71)
     for ns in (1, 3):
-        out, lse, splits = run_cpu(exe, tmp_path, case, variant, flags=ROW, ns=ns)
+        out, lse, splits = run_cpu(exe, tmp_path, case, variant, ns=ns)
         assert splits == ns
         check(out, lse, case)
         assert np.all(out[2] == 0) and np.all(np.isneginf(lse[2]))
     wide = wl.make_case("wide_row", 72, batch=1, s_q=1, heads=40, seqlens=[700], q_sigma=6.0)
-    a = run_cpu(exe, tmp_path, wide, variant, flags=ROW)
+    a = run_cpu(exe, tmp_path, wide, variant)
     check(a[0], a[1], wide, peaked=True)
-    b = run_cpu(exe, tmp_path, wide, variant, flags=ROW | NO_SKIP)
+    b = run_cpu(exe, tmp_path, wide, variant, flags=NO_SKIP)
     check(b[0], b[1], wide, peaked=True)
     if variant == ADD:
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
@@ -452,5 +357,5 @@ def test_row_rescale_kernel(exe, tmp_path, variant):
     dirty.kv_bits = wide.kv_bits.copy()
     phys = int(wide.block_table[0, 700 // 64])
     dirty.kv_bits[phys, 700 % 64:, :] = 0x7FC0          # NaN in every slot past the end of the last block
-    c = run_cpu(exe, tmp_path, dirty, variant, flags=ROW)
+    c = run_cpu(exe, tmp_path, dirty, variant)
     assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])

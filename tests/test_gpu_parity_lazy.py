@@ -1,7 +1,5 @@
-"""GPU parity of the lazy reference update (AMLA_FLAG_LAZY_RESCALE) of the compiler-built kernel:
-the reference of the exponent moves only when the row max exceeds it by more than 2^8.  Collected
-after tests/test_gpu_parity.py on purpose: these cases were added after the last GPU run of this
-build, and a failure here must not hide the cases that ran before."""
+"""GPU parity of the lazy reference update (AMLA_FLAG_LAZY_RESCALE; transposed-accumulator kernels): the
+reference of the exponent moves only when the row max exceeds it by more than 2^8."""
 import numpy as np
 import pytest
 

@@ -2,18 +2,20 @@
 from N(0, sigma^2) or U(-a, a), context 8K, BF16, relative Frobenius error against the fp64 oracle.
 The MUL variant runs Algorithm 1's arithmetic ("Base"), ADD_COMP runs Algorithm 2's ("AMLA"); the
 printed errors are in tests/golden/table3_table4_accuracy.txt, and the CPU emulations of both
-algorithms reproduce them (tests/test_oracle_method.py).  Collected after the other parity files on
-purpose: these cases were added after the last GPU run of this build."""
+algorithms reproduce them (tests/test_oracle_method.py).  The kernels run unsplit here, as the paper's kernel
+does: under split-KV every split normalises by its own sum of rounded weights, which cancels more of the
+weight-rounding error (FP32 emulation of this sample: 1.770e-3 unsplit, 1.740e-3 in 32 splits), so the
+split figures sit a few per cent under the printed ones.  A statement about error levels, not parity: collected
+after the parity files."""
 import os
 
 import numpy as np
 import pytest
 
-from test_gpu_parity import ADD, LSE_TOL, MUL, env, run_gpu, to_dev  # noqa: F401
+from test_gpu_parity import ADD, COMP, LSE_TOL, MUL, env, run_gpu, to_dev  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
-COMP = 2
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "table3_table4_accuracy.txt")
 with open(GOLD) as f:
     ROWS = [(a, float(b), float(c), float(d)) for a, b, c, d in
@@ -33,7 +35,10 @@ def test_kernels_reproduce_the_printed_accuracy_tables(env, family, param, base_
         assert np.abs(lse - want_lse).max() <= LSE_TOL, name
     print(f"{family} {param:g}: printed Base {base_printed:.2e} AMLA {amla_printed:.2e} | "
           f"mul {err['mul']:.3e} add {err['add']:.3e} comp {err['comp']:.3e}", flush=True)
-    # 256 rows of one sample: spread 0.3 % on the flat columns, 2-4 % on the peaked ones
+    # Band: the printed figures carry three digits (0.3 %); one 256-row sample spreads 0.3 % on the flat columns
+    # (FP32 emulation of Algorithm 1 on four seeds: 1.770e-3 .. 1.777e-3) and 2-4 % on the peaked ones; 64-key
+    # blocks against the paper's 512 and the normalisation by the sum of rounded weights move the emulated figure
+    # by 0.1-0.6 %.  3 % / 8 % leave a factor of two to three on that.
     tol = 0.03 if param == 1.0 else 0.08
     assert abs(err["mul"] - base_printed) < tol * base_printed, err
     assert abs(err["comp"] - amla_printed) < tol * amla_printed, err

@@ -1,29 +1,19 @@
 """GPU parity of the balanced decomposition (AMLA_FLAG_BALANCED): the batch's blocks laid end to end
-and cut into equal worker ranges, pieces merged per sequence.  SWITCHED OFF in the library until its
-index arithmetic has run on hardware: these cases are skipped unless the process sets
-AMLA_ENABLE_BALANCED=1 (the run that tests it).  The integer arithmetic itself is covered on the CPU
-by tests/test_plan.py."""
-import os
-
+and cut into equal worker ranges, pieces merged per sequence; the causal mask among the s_q tokens and
+per-sequence query counts, which live in the same kernels.  Both kernel families.  The integer arithmetic
+itself is covered on the CPU by tests/test_plan.py."""
 import numpy as np
 import pytest
 
-from test_gpu_parity import ADD, LAZY, LSE_TOL, MUL, check, env, out_tolerance, run_gpu, to_dev  # noqa: F401
+from test_gpu_parity import ADD, COMP, LAZY, LSE_TOL, MUL, TRANSPOSED, check, env, out_tolerance, run_gpu, to_dev  # noqa: F401
 
-pytestmark = [pytest.mark.gpu,
-              pytest.mark.skipif(os.environ.get("AMLA_ENABLE_BALANCED") != "1",
-                                 reason="balanced decomposition switched off: not yet run on hardware")]
+pytestmark = pytest.mark.gpu
 
 BALANCED = 8
 CAUSAL = 16
-COMP = 2
-ASM = 4
-asm_off = pytest.mark.skipif(os.environ.get("AMLA_ENABLE_ASM_KERNELS") != "1",
-                             reason="assembly kernels switched off: not yet run on hardware since the hazard fix")
-KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((ADD, LAZY), id="add_lazy"),
-         pytest.param((COMP, 0), id="add_comp"),
-         pytest.param((MUL, ASM), id="mul_asm", marks=asm_off), pytest.param((ADD, ASM | LAZY), id="add_lazy_asm", marks=asm_off)]
-NO_ASM = [k for k in KINDS if not (k.values[0][1] & ASM)]
+KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((COMP, 0), id="add_comp"),
+         pytest.param((MUL, TRANSPOSED), id="mul_t"), pytest.param((ADD, TRANSPOSED), id="add_t"),
+         pytest.param((ADD, LAZY), id="add_lazy"), pytest.param((COMP, TRANSPOSED), id="add_comp_t")]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -63,22 +53,26 @@ def test_balanced_matches_equal_share_split_on_a_uniform_batch(env):
 
 
 def test_full_size_ragged_config_balanced(env):
+    """The ragged configuration (batch 32, kv_len 1024 .. 16384) under the balanced decomposition, every row."""
     torch, orc, amla, wl = env
     case = wl.make_config(3)
     dev = to_dev(torch, case)
-    out, lse = run_gpu(torch, amla, case, dev, variant=ADD, flags=BALANCED)
-    worst = [0.0, 0.0]
+    kinds = [(MUL, 0), (ADD, 0), (COMP, 0), (ADD, TRANSPOSED)]
+    res = {k: run_gpu(torch, amla, case, dev, variant=k[0], flags=k[1] | BALANCED) for k in kinds}
+    worst = {k: [0.0, 0.0] for k in kinds}
     for b in range(case.batch):
         want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens,
                                     case.softmax_scale, seq_ids=[b])
-        assert np.all(np.abs(out[b] - want[b]) <= out_tolerance(want[b])), b
-        worst[0] = max(worst[0], float(np.abs(out[b] - want[b]).max()))
-        worst[1] = max(worst[1], float(np.abs(lse[b] - want_lse[b]).max()))
-    print(f"config 3 balanced: max|out err| {worst[0]:.3e} max|lse err| {worst[1]:.3e}", flush=True)
-    assert worst[1] <= LSE_TOL
+        for k, (out, lse) in res.items():
+            assert np.all(np.abs(out[b] - want[b]) <= out_tolerance(want[b])), (b, k)
+            worst[k][0] = max(worst[k][0], float(np.abs(out[b] - want[b]).max()))
+            worst[k][1] = max(worst[k][1], float(np.abs(lse[b] - want_lse[b]).max()))
+    for k in kinds:
+        print(f"config 3 balanced {k}: max|out err| {worst[k][0]:.3e} max|lse err| {worst[k][1]:.3e}", flush=True)
+        assert worst[k][1] <= LSE_TOL
 
 
-@pytest.mark.parametrize("kind", NO_ASM)
+@pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("workers", [0, 3, 11])
 def test_causal_mask_among_the_query_tokens(env, kind, workers):
     """s_q = 4 under AMLA_FLAG_CAUSAL: tokens without any key (kv_len 1), limits at and just past block
@@ -93,8 +87,9 @@ def test_causal_mask_among_the_query_tokens(env, kind, workers):
     assert np.all(out[0, :3] == 0)
 
 
-@pytest.mark.parametrize("kind,workers,causal", [((MUL, 0), 0, False), ((ADD, 0), 3, True), ((ADD, LAZY), 5, False),
-                                                 ((MUL, LAZY), 9, True)])
+@pytest.mark.parametrize("kind,workers,causal", [((MUL, 0), 0, False), ((ADD, 0), 3, True), ((COMP, 0), 5, False),
+                                                 ((ADD, 0), 9, False), ((MUL, TRANSPOSED), 0, False),
+                                                 ((ADD, TRANSPOSED), 3, True), ((ADD, LAZY), 5, False), ((MUL, LAZY), 9, True)])
 def test_per_sequence_query_counts(env, kind, workers, causal):
     """desc->q_lens: sequences with all, some, one and none of the s_q = 4 tokens, real and padding rows
     sharing a wave (40 heads), with and without the mask; padding rows come back as zeros / -inf."""
@@ -109,33 +104,6 @@ def test_per_sequence_query_counts(env, kind, workers, causal):
     check(out, lse, want, want_lse, f"q_lens workers={workers} causal={causal} {kind}")
     for b, k in enumerate(q_lens):
         assert np.all(out[b, k:] == 0) and np.all(np.isneginf(lse[b, k:]))
-
-
-W8 = 64
-LDEXP = 3
-
-
-@pytest.mark.parametrize("kind,workers", [((MUL, 0), 0), ((ADD, 0), 3), ((ADD, LAZY), 7), ((LDEXP, 0), 41),
-                                          ((LDEXP, LAZY), 2), ((MUL, LAZY), 11)])
-def test_eight_wave_balanced_kernels(env, kind, workers):
-    """AMLA_FLAG_EIGHT_WAVES with the balanced decomposition: the ragged batch, the causal mask around block
-    boundaries, per-sequence query counts with and without the mask."""
-    torch, orc, amla, wl = env
-    variant, flags = kind
-    case = wl.make_case("edges", 46, batch=7, s_q=2, heads=80, seqlens=[1, 63, 0, 64, 65, 200, 330], spare_frac=0.25)
-    want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale)
-    out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant, flags=flags | W8 | BALANCED,
-                       num_splits=workers)
-    check(out, lse, want, want_lse, f"eight waves balanced workers={workers} {kind}")
-    causal = wl.make_case("causal8", 47, batch=7, s_q=4, heads=40, seqlens=[1, 64, 0, 65, 66, 130, 300], spare_frac=0.25)
-    dev = to_dev(torch, causal)
-    q_lens = np.array([4, 2, 3, 1, 0, 3, 4], np.int32)
-    for masked, counts in ((True, None), (False, q_lens), (True, q_lens)):
-        want, want_lse = orc.decode(causal.q_bits, causal.kv_bits, causal.block_table, causal.seqlens,
-                                    causal.softmax_scale, causal=masked, q_lens=counts)
-        out, lse = run_gpu(torch, amla, causal, dev, variant=variant, flags=flags | W8 | (CAUSAL if masked else BALANCED),
-                           num_splits=workers, q_lens=None if counts is None else torch.from_numpy(counts).cuda())
-        check(out, lse, want, want_lse, f"eight waves masked={masked} q_lens={counts is not None} workers={workers} {kind}")
 
 
 def test_causal_headline_shape_rows_match_shorter_caches(env):

@@ -1,10 +1,8 @@
-"""The long-context configuration (batch 8, s_q 4, kv 65536, q ~ N(0, 16)) for the variants added after the
-last GPU run of this build.  Collected after every other running GPU file on purpose: its margin is the
-thinnest of all cases.  Outputs there reach 2-3 units, where the bf16 output format alone takes 7.8e-3 of
-the 1e-2 bound, and the exponent-add variants' largest weight is not bf16-exact; the strict ADD kernel
-measured 9.0e-3 at worst on this configuration, and CPU emulations of the ADD recurrence land between
-8.4e-3 and 1.006e-2.  A failure here by a few 1e-5 is that margin, not an indexing mistake (the mismatch
-report printed by the check tells the two apart), and it must not hide the other files' cases."""
+"""The long-context configuration (batch 8, s_q 4, kv 65536, q ~ N(0, 16)) for the variants the main file's
+full-size test does not run.  Its margin is the thinnest of all cases: outputs there reach 2-3 units, where the
+bf16 output format alone takes 7.8e-3 of the 1e-2 bound, and the exponent-add variants' largest weight is not
+bf16-exact.  A failure here by a few 1e-5 is that margin, not an indexing mistake (the mismatch report printed by
+the check tells the two apart)."""
 import numpy as np
 import pytest
 
@@ -15,7 +13,7 @@ pytestmark = pytest.mark.gpu
 COMP = 2
 
 
-@pytest.mark.parametrize("kind", [pytest.param((COMP, 0), id="add_comp"), pytest.param((MUL, LAZY), id="mul_lazy"),
+@pytest.mark.parametrize("kind", [pytest.param((COMP, 128), id="add_comp_t"), pytest.param((MUL, LAZY), id="mul_lazy"),
                                   pytest.param((ADD, LAZY), id="add_lazy")])
 def test_long_context_all_rows(env, kind):
     torch, orc, amla, wl = env

@@ -14,24 +14,19 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 GOLD = os.path.join(ROOT, "tests", "golden", "proven_kernels.sha256")
 SRC = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "amla_decode.hip")
+SRC_ROW = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "amla_decode_rg.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # strict MUL / ADD decode kernels, the split combine kernel, the exponent-add test kernel
 PINNED = ("amla_decode_kernelILi0ELb0E", "amla_decode_kernelILi1ELb0E", "amla_combine_kernelE", "amla_exponent_add_kernelE")
 
 
-def device_assembly(tmp):
-    """Compiles the library's device code to gfx950 assembly text; returns the path."""
+def device_assembly(tmp, src=SRC, name="device.s"):
+    """Compiles one source file's device code to gfx950 assembly text; returns the path."""
     sys.path.insert(0, ROOT)
     import __graft_entry__ as entry
-    gen = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "_build")
-    for inc in ("amla_decode_gfx950.hsaco.inc", "amla_decode_gfx950_safe.hsaco.inc"):
-        if not os.path.exists(os.path.join(gen, inc)):
-            os.makedirs(gen, exist_ok=True)
-            with open(os.path.join(gen, inc), "w") as f:
-                f.write("0,\n")
     flags = [f for f in entry.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
-    out = os.path.join(tmp, "device.s")
-    subprocess.run([HIPCC, *flags, "-I" + gen, "--cuda-device-only", "-S", "-o", out, SRC], check=True,
+    out = os.path.join(tmp, name)
+    subprocess.run([HIPCC, *flags, "--cuda-device-only", "-S", "-o", out, src], check=True,
                    stderr=subprocess.DEVNULL)
     return out
 
@@ -107,16 +102,17 @@ def _steady_loop(body):
     return body[best[0]:best[1] + 1]
 
 
-def test_tile_loads_are_not_serialised_in_the_new_kernels(asm_path):
-    """What the prefetching, balanced and eight-wave builds are built around, read off the compiled loops
-    (one in-order vmcnt for tile loads and scratch reloads; see the comments at AMLA_HIDDEN_LDS_LOAD and
-    AMLA_PIECE_LATE_LOADS): inside the block loop no register is reloaded from scratch after the next tile's
-    loads were issued, and no vmcnt wait follows them -- only the loop-top wait orders the tile.  The
-    equal-share eight-wave kernels have no reload in the loop at all."""
-    bodies = _kernel_bodies(asm_path)
+@pytest.fixture(scope="module")
+def row_asm_path(tmp_path_factory):
+    if not os.path.exists(HIPCC):
+        pytest.skip("no hipcc")
+    return device_assembly(str(tmp_path_factory.mktemp("device_asm_row")), SRC_ROW, "row.s")
+
+
+def _check_loads_are_not_serialised(bodies, pattern, expect):
     checked = 0
     for name, body in bodies.items():
-        if not re.search(r"amla_decode_(prefetch|balanced|w8|w8_balanced)_kernel", name):
+        if not re.search(pattern, name):
             continue
         loop = _steady_loop(body)
         issue = [i for i, ln in enumerate(loop) if ln.startswith("s_mov_b32 m0")]
@@ -124,10 +120,31 @@ def test_tile_loads_are_not_serialised_in_the_new_kernels(asm_path):
         after = loop[issue[0]:]                              # from the first issue point to the closing branch
         assert not [ln for ln in after if ln.startswith("scratch_load")], (name, "reload behind the tile loads")
         assert not [ln for ln in after if ln.startswith("s_waitcnt") and "vmcnt" in ln], (name, "vmcnt wait behind the tile loads")
-        if "amla_decode_w8_kernel" in name:
-            assert not [ln for ln in loop if ln.startswith("scratch_load")], (name, "reload inside the loop")
         checked += 1
-    assert checked == 6 + 5 + 7 + 7
+    assert checked == expect
+
+
+def test_tile_loads_are_not_serialised(asm_path, row_asm_path):
+    """What the kernels that issue their tile loads from inline assembly are built around, read off the compiled
+    loops (one in-order vmcnt for tile loads and scratch reloads; see the comments at AMLA_HIDDEN_LDS_LOAD and
+    AMLA_PIECE_LATE_LOADS): inside the block loop no register is reloaded from scratch after the next tile's
+    loads were issued, and no vmcnt wait follows them -- only the loop-top wait orders the tile."""
+    _check_loads_are_not_serialised(_kernel_bodies(asm_path), r"amla_decode_balanced_kernel", 5)
+    _check_loads_are_not_serialised(_kernel_bodies(row_asm_path), r"amla_decode_rg(_balanced)?_kernel", 6)
+
+
+def test_row_rescale_kernels_keep_the_compiler_out_of_the_accumulator(row_asm_path):
+    """The row-rescale kernels address their accumulator, all 256 AccVGPRs, by name from assembly statements:
+    compiler-made code must not touch an AccVGPR (the build refuses such a library too), the kernels must be
+    allotted all 512 registers, and the loop must be free of scratch traffic."""
+    sys.path.insert(0, ROOT)
+    import __graft_entry__ as entry
+    text = open(row_asm_path).read()
+    assert entry.stray_accvgpr_uses(text) == []
+    assert text.count(".agpr_count:     256") == 6 and text.count(".vgpr_count:     512") == 6
+    for name, body in _kernel_bodies(row_asm_path).items():
+        if "amla_decode_rg" in name:
+            assert not [ln for ln in _steady_loop(body) if ln.startswith("scratch_")], name
 
 
 if __name__ == "__main__" and "--write" in sys.argv:
