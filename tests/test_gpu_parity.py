@@ -263,7 +263,7 @@ def test_device_exponent_add(env):
     """The device helper the ADD variants apply to the accumulator registers.  What the mathematics fixes:
     wherever Lemma 3.1 applies (x normal, x * 2^d normal) the result is x * 2^d bit for bit; everywhere else
     (zeros, subnormals, exponents that would drop to or below zero) it is a value of magnitude at most 2^-126
-    carrying x's sign -- never a wrapped bit pattern.  Checked against ldexp, not against the oracle's own
+    carrying x's sign -- never a wrapped bit pattern.  Checked against x * 2^d in fp64, not against the oracle's own
     guarded add, over 2^27 random bit patterns per shift and every shift the kernels can apply (0 .. -30).
     The comparison with oracle.exponent_add_guarded further down is a regression check of the instruction
     pair's exact choice inside the region the paper neglects (mantissa bits kept when the exponent field
@@ -281,10 +281,14 @@ def test_device_exponent_add(env):
             bits = bits[E < 255]                                   # the paper neglects Inf / NaN
             x = bits.view(torch.float32)
             got = amla.amla_exponent_add(x, d)
-            exact = torch.ldexp(x.double(), torch.tensor(d, device="cuda"))       # x * 2^d in fp64: exact
+            # x * 2^d in fp64, exact: a 24-bit significand times a power of two that the host computed (torch.ldexp
+            # builds its factor with the device's pow(), which need not return an exact power of two)
+            exact = x.double() * float(2.0 ** d)
             Ex = (bits >> 23) & 0xFF
             lemma = (Ex > 0) & (Ex + d > 0)                        # 0 < E and 0 < E + d < 255
-            assert torch.equal(got[lemma].double(), exact[lemma]), d
+            bad = lemma & (got.double() != exact)
+            assert not bool(bad.any()), (d, int(bad.sum()), [hex(v & 0xFFFFFFFF) for v in bits[bad][:4].tolist()],
+                                         [hex(v & 0xFFFFFFFF) for v in got[bad][:4].view(torch.int32).tolist()])
             rest = ~lemma
             assert bool((got[rest].abs() <= 2.0 ** -126).all()), d
             assert torch.equal(torch.signbit(got[rest]), torch.signbit(x[rest])), d
