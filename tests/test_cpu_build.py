@@ -48,8 +48,7 @@ def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0, q_lens
             f.write(np.ascontiguousarray(a).tobytes())
         if q_lens is not None:
             f.write(np.ascontiguousarray(np.asarray(q_lens, np.int32)).tobytes())
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
-    env.pop("LD_PRELOAD", None)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0")
     r = subprocess.run([exe, inp, outp], capture_output=True, text=True, env=env, timeout=900)
     assert r.returncode == 0, r.stderr[-3000:]
     raw = np.fromfile(outp, dtype=np.uint8)
@@ -251,8 +250,7 @@ def test_the_harness_notices_a_tile_read_before_it_landed(tmp_path):
         f.write(struct.pack("<f", case.softmax_scale))
         for a in (case.q_bits, case.kv_bits, case.block_table, case.seqlens):
             f.write(np.ascontiguousarray(a).tobytes())
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
-    env.pop("LD_PRELOAD", None)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0")
     r = subprocess.run([bad, inp, outp], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode != 0 and "loads in flight" in r.stderr
 
