@@ -167,6 +167,28 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
                 const amla_desc* desc);
 
 /*
+ * amla_decode_static_workspace -- amla_decode for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels,
+ * same result, but the split-KV / balanced partial results go to a fixed array of
+ * amla_static_workspace_limit() bytes (128 MiB) that is part of the library's device image -- one per GPU
+ * the library runs on, held until the process ends.  desc->workspace and desc->workspace_bytes are
+ * ignored.  The call allocates and frees nothing, on the device or through any library; like amla_decode
+ * it only enqueues kernels on desc->stream.
+ * Returns AMLA_ERR_WORKSPACE, with nothing enqueued, when amla_workspace_bytes(desc) exceeds the limit;
+ * AMLA_ERR_LAUNCH when the array's device address cannot be obtained; otherwise what amla_decode returns.
+ * All calls on one GPU share that GPU's array: two calls whose kernels overlap in time (different
+ * streams, different host threads) race on it; calls on one stream are safe.  The array keeps the last
+ * call's contents and nothing in it has to be cleared: every partial row a call reads was written by
+ * that same call.
+ */
+int amla_decode_static_workspace(const void* q, const void* kv_cache, const int32_t* block_table,
+                                 const int32_t* seqlens, float softmax_scale, void* out, float* lse,
+                                 const amla_desc* desc);
+
+/* Size in bytes of the array amla_decode_static_workspace uses. */
+size_t amla_static_workspace_limit(void);
+
+/*
  * amla_workspace_bytes -- bytes of desc->workspace that amla_decode needs for this desc
  * (0 when the effective split factor is 1).  Only shape fields, num_splits and flags are
  * read.  Returns 0 for a NULL or unsupported desc.

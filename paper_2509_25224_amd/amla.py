@@ -26,7 +26,7 @@ AMLA_FLAG_BALANCED = 8
 AMLA_FLAG_CAUSAL = 16
 AMLA_FLAG_TRANSPOSED_ACC = 128
 
-EXPORTS = ("amla_decode", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
+EXPORTS = ("amla_decode", "amla_decode_static_workspace", "amla_static_workspace_limit", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",
            "amla_mfma_probe", "amla_device_info", "amla_plan_segments", "amla_preload_rotation", "amla_status_string")
 
 
@@ -51,6 +51,10 @@ lib = ctypes.CDLL(_LIB_PATH)
 lib.amla_decode.restype = ctypes.c_int
 lib.amla_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                             ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(AmlaDesc)]
+lib.amla_decode_static_workspace.restype = ctypes.c_int
+lib.amla_decode_static_workspace.argtypes = lib.amla_decode.argtypes
+lib.amla_static_workspace_limit.restype = ctypes.c_size_t
+lib.amla_static_workspace_limit.argtypes = []
 lib.amla_workspace_bytes.restype = ctypes.c_size_t
 lib.amla_workspace_bytes.argtypes = [ctypes.POINTER(AmlaDesc)]
 lib.amla_device_info.restype = ctypes.c_int
@@ -144,6 +148,30 @@ def amla_decode(q, kv_cache, block_table, seqlens, softmax_scale, out=None, lse=
     if st != AMLA_OK:
         raise AmlaError(st)
     return out, lse
+
+
+def amla_decode_static_workspace(q, kv_cache, block_table, seqlens, softmax_scale, out, lse=None, *,
+                                 variant=AMLA_RESCALE_ADD, num_splits=0, flags=0, q_lens=None):
+    """amla_decode through the entry point that allocates nothing: `out` (and `lse` if wanted) are the
+    caller's, and the partial results go to the library's static device array."""
+    import torch
+
+    B, T, H, D = q.shape
+    nblk, bs, _ = kv_cache.shape
+    desc = make_desc(B, T, H, nblk, block_table.shape[1], variant, num_splits, flags, D, 512, bs)
+    if q_lens is not None:
+        desc.q_lens = q_lens.data_ptr()
+    desc.stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = lib.amla_decode_static_workspace(q.data_ptr(), kv_cache.data_ptr(), block_table.data_ptr(),
+                                          seqlens.data_ptr(), float(softmax_scale), out.data_ptr(),
+                                          lse.data_ptr() if lse is not None else None, ctypes.byref(desc))
+    if st != AMLA_OK:
+        raise AmlaError(st)
+    return out, lse
+
+
+def amla_static_workspace_limit() -> int:
+    return int(lib.amla_static_workspace_limit())
 
 
 def amla_exponent_add(x, delta: int, y=None):

@@ -79,6 +79,29 @@ int device_cu_count() {
   return g_cu_count[dev];
 }
 
+// Workspace of amla_decode_static_workspace: one array per device, part of the loaded code object, held until
+// the process ends.  In host code the array's name is only a stand-in for the symbol; its device address is
+// asked for once per device, with that device current, and used from then on.
+constexpr size_t kStaticWorkspaceBytes = (size_t)128 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+void* static_workspace() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 // The causal mask and the per-sequence query counts live in the balanced kernels only, so they select them.
 bool uses_balanced(const amla_desc* d) {
   return (d->flags & (AMLA_FLAG_BALANCED | AMLA_FLAG_CAUSAL)) != 0 || d->q_lens != nullptr;
@@ -250,6 +273,23 @@ int amla_decode(const void* q, const void* kv_cache, const int32_t* block_table,
   }
   return enqueue_decode(q, kv_cache, block_table, seqlens, softmax_scale, out, lse, desc, desc->workspace, ns);
 }
+
+int amla_decode_static_workspace(const void* q, const void* kv_cache, const int32_t* block_table, const int32_t* seqlens,
+                                 float softmax_scale, void* out, float* lse, const amla_desc* desc) {
+  const int bad = check_decode_args(q, kv_cache, block_table, seqlens, softmax_scale, out, desc);
+  if (bad != AMLA_OK) return bad;
+  const int ns = choose_splits(desc);
+  const size_t need = amla_workspace_bytes(desc);
+  if (need > kStaticWorkspaceBytes) return AMLA_ERR_WORKSPACE;
+  void* base = nullptr;
+  if (need > 0) {
+    base = static_workspace();
+    if (base == nullptr) return AMLA_ERR_LAUNCH;
+  }
+  return enqueue_decode(q, kv_cache, block_table, seqlens, softmax_scale, out, lse, desc, base, ns);
+}
+
+size_t amla_static_workspace_limit(void) { return kStaticWorkspaceBytes; }
 
 int amla_exponent_add(const float* x, float* y, size_t n, int32_t delta, void* stream) {
   if (x == nullptr || y == nullptr) return AMLA_ERR_NULL_ARG;

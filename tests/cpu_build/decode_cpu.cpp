@@ -3,9 +3,9 @@
 // C-ABI entry points amla_workspace_bytes and amla_decode on host buffers of exactly the documented
 // sizes (AddressSanitizer sees every access past an end), and writes out and lse.
 //
-// input file: 12 int32 (batch, s_q, heads, num_blocks, max_blocks, variant, num_splits, flags, 0,
-//             has q_lens (0/1), 0, 0), float softmax_scale, then q bits, cache bits, block table, seqlens
-//             and, when announced, q_lens
+// input file: 12 int32 (batch, s_q, heads, num_blocks, max_blocks, variant, num_splits, flags,
+//             use amla_decode_static_workspace (0/1), has q_lens (0/1), 0, 0), float softmax_scale, then q bits,
+//             cache bits, block table, seqlens and, when announced, q_lens
 // output file: int32 status, int32 effective splits; then, when status is 0, out bits
 //             [batch * rows * 512] uint16 and lse [batch * rows] float
 #include "../../paper_2509_25224_amd/csrc/amla_decode.hip"
@@ -59,7 +59,12 @@ int main(int argc, char** argv) {
   d.workspace = ws_bytes ? ws : nullptr;
   d.workspace_bytes = ws_bytes;
   const int32_t splits = amla_effective_splits(&d);
-  const int32_t status = amla_decode(q, kv, table, lens, scale, out, lse, &d);
+  if (h[8]) {          // the entry point that brings its own workspace must not look at the caller's
+    d.workspace = nullptr;
+    d.workspace_bytes = 0;
+  }
+  const int32_t status = h[8] ? amla_decode_static_workspace(q, kv, table, lens, scale, out, lse, &d)
+                              : amla_decode(q, kv, table, lens, scale, out, lse, &d);
   f = std::fopen(argv[2], "wb");
   if (!f) return 2;
   std::fwrite(&status, 4, 1, f);

@@ -38,11 +38,11 @@ def exe(tmp_path_factory):
     return build(tmp_path_factory.mktemp("cpu_build"))
 
 
-def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0, q_lens=None):
+def run_cpu(exe, tmp_path, case, variant, flags=0, ns=0, expect_status=0, q_lens=None, static_ws=False):
     inp, outp = str(tmp_path / "in.bin"), str(tmp_path / "out.bin")
     with open(inp, "wb") as f:
         f.write(struct.pack("<12i", case.batch, case.s_q, case.heads, case.num_blocks, case.max_blocks_per_seq,
-                            variant, ns, flags, 0, int(q_lens is not None), 0, 0))
+                            variant, ns, flags, int(static_ws), int(q_lens is not None), 0, 0))
         f.write(struct.pack("<f", case.softmax_scale))
         for a in (case.q_bits, case.kv_bits, case.block_table, case.seqlens):
             f.write(np.ascontiguousarray(a).tobytes())
@@ -210,6 +210,21 @@ def test_entry_point_rejects_what_it_documents(exe, tmp_path):
     run_cpu(exe, tmp_path, case, ADD, flags=32, expect_status=-2)
     run_cpu(exe, tmp_path, case, ADD, flags=64, expect_status=-2)
     run_cpu(exe, tmp_path, case, LDEXP, flags=BALANCED, expect_status=-2)     # equal-share kernels only
+
+
+def test_static_workspace_entry_point(exe, tmp_path):
+    """amla_decode_static_workspace against amla_decode, bit for bit: same kernels, the partial results in
+    the library's own array instead of the caller's (here an ordinary host array; on the device its address
+    comes from hipGetSymbolAddress).  Equal-share splits, the balanced walk, and a shape that needs none."""
+    case = _ragged(56)
+    for variant, flags, ns in ((ADD, 0, 3), (MUL, BALANCED, 8), (COMP, 0, 1), (ADD, TRANSPOSED, 2)):
+        want, want_lse, _ = run_cpu(exe, tmp_path, case, variant, flags=flags, ns=ns)
+        got, got_lse, _ = run_cpu(exe, tmp_path, case, variant, flags=flags, ns=ns, static_ws=True)
+        assert np.array_equal(got, want) and np.array_equal(got_lse, want_lse, equal_nan=True)
+    # what does not fit the array is refused: 20 sequences x 16 splits x 256 rows of 513 floats = 160 MiB > 128 MiB
+    big = wl.make_case("big", 57, batch=20, s_q=2, heads=128, seqlens=[64] * 20)
+    run_cpu(exe, tmp_path, big, ADD, ns=16, static_ws=True, expect_status=-3)
+    run_cpu(exe, tmp_path, big, ADD, ns=12, static_ws=True)                      # 120 MiB: accepted
 
 
 def test_random_shapes_lengths_and_decompositions(exe, tmp_path):
