@@ -33,7 +33,11 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one launch of the headline kernel on the headline workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs scaled by a copy kernel of known size (profiles/amla_decode_rg_kernel_mtp_b128.md); null for
 # any other kernel or workload
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # FETCH_SIZE 314182 KiB x 2.000 + WRITE_SIZE 34688 KiB x 1.000 (factors: profiles/copy_probe_512mib.md)
+    ("amla_decode_rg_kernel", "add", "mtp_b128", 1): {"read": 643.4e6, "written": 35.5e6},
+    ("amla_decode_rg_kernel", "mul", "mtp_b128", 1): {"read": 643.4e6, "written": 35.5e6},
+}
 
 
 def parse():
@@ -237,7 +241,8 @@ def main():
     kern_ms = sum(per) / len(per)          # one decode launch per step (+ the combine kernel when split)
     achieved = flops / (kern_ms * 1e-3) / 1e12
     kname = kernel_name(chosen, args.balanced)
-    traffic = MEASURED_TRAFFIC.get((kname, chosen, case.name, splits))
+    measured = MEASURED_TRAFFIC.get((kname, chosen, case.name, splits))
+    traffic = measured["read"] + measured["written"] if measured else None
 
     result = {
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -252,7 +257,8 @@ def main():
                    "kv_splits": splits, "decomposition": "balanced" if args.balanced else "equal_share", "seed": case.seed},
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_unit": "B per launch",
+                     "traffic_read_written": measured, "traffic_over_algorithmic": traffic / abytes if traffic else None,
                      "kernel": kname, "kernel_ms": kern_ms, "kernel_ms_median": median(per), "kernel_ms_min": min(per),
                      "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": abytes,
                      "algorithmic_GBps": abytes / (kern_ms * 1e-3) / 1e9, "hbm_peak_GBps": HBM_PEAK_GBS},
