@@ -68,46 +68,40 @@ constexpr int kRgLdsBytes = 2 * kRgTileBytes;         // double buffer, 155648 o
 #define AMLA_HIDDEN_LDS_LOAD_AT(base, off, lds) AMLA_HIDDEN_LDS_LOAD((base) + (off), (lds))
 #endif
 
-// Per-lane constants of the tile loads.
+// Per-lane constants of the tile loads.  Everything wave-uniform in a load's global address goes into its scalar
+// base, so that issuing a load takes no vector instruction: with one wave per SIMD every instruction costs
+// issue time that an MFMA's 32 cycles have to cover.
 struct TileLoadLane {
-  int lane;      // 0 .. 63
-  int off_b;     // region B: byte offset of this lane's chunk within the block for row group 0
+  unsigned c16[4];   // region A: byte offset within the row of the chunk that lives at position lane, for row permutation 0 .. 3
+  unsigned off_b;    // region B: byte offset of this lane's chunk within an 8-row group
 };
 __device__ __forceinline__ TileLoadLane tile_load_lane(const int wave, const int lane) {
-  // rows 8 m + (lane >> 3) of row group m = wave + 4 k: (4 m) & 7 = 4 (wave & 1) whatever k
+  TileLoadLane t;
+  // region A, load k: row i = wave + 4 k, whose permutation is (i >> 2) & 3 = k & 3; position l holds chunk
+  // (l & ~3) | ((l - k) & 3)
+#pragma unroll
+  for (int k = 0; k < 4; ++k) t.c16[k] = 16u * (unsigned)((lane & ~3) | ((lane - k) & 3));
+  // region B, rows 8 m + (lane >> 3) of row group m = wave + 4 k: (4 m) & 7 = 4 (wave & 1) whatever k
   const int c8 = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
-  return {lane, (lane >> 3) * kRowBytes + 64 * 16 + c8 * 16};
+  t.off_b = (unsigned)((lane >> 3) * kRowBytes + 64 * 16 + c8 * 16);
+  return t;
 }
-// Region A, load k (0 .. 15) of this wave: row i = wave + 4 k, whose permutation is i >> 2 = k.
-__device__ __forceinline__ void issue_tile_load_a(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
-                                                  const TileLoadLane& t, const int k) {
-  const int i = wave + 4 * k;
-  // recomputed at every load: hoisted out of the block loop these offsets would be spilled, and a reload from
-  // scratch in front of a load waits (in-order vmcnt) for every tile load in flight
-  int l = t.lane;
-  AMLA_OPAQUE(l);
-  const int c = (l & ~3) | ((l - k) & 3);                        // the chunk that lives at position lane of row i
-  AMLA_HIDDEN_LDS_LOAD_AT(block_base, (unsigned)(i * kRowBytes + c * 16), buf + i * kRgRowA);
-}
-// Region B, load k (0 or 1) of this wave: rows 8 m .. 8 m + 7 of row group m = wave + 4 k.
-__device__ __forceinline__ void issue_tile_load_b(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
-                                                  const TileLoadLane& t, const int k) {
-  const int m = wave + 4 * k;
-  int off = t.off_b;
-  AMLA_OPAQUE(off);
-  AMLA_HIDDEN_LDS_LOAD_AT(block_base, (unsigned)(off + m * 8 * kRowBytes), buf + kRgRegionA + m * 1024);
-}
-// load n (0 .. 17) of this wave's share of a tile
+// load n (0 .. 17) of this wave's share of a tile: 16 rows of region A (i = wave + 4 n), then two 8-row groups of
+// region B (m = wave + 4 (n - 16))
+template <int N>
 __device__ __forceinline__ void issue_tile_load(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
-                                                const TileLoadLane& t, const int n) {
-  if (n < kRgLoadsA)
-    issue_tile_load_a(block_base, buf, wave, t, n);
-  else
-    issue_tile_load_b(block_base, buf, wave, t, n - kRgLoadsA);
+                                                const TileLoadLane& t) {
+  if constexpr (N < kRgLoadsA) {
+    const int i = wave + 4 * N;
+    AMLA_HIDDEN_LDS_LOAD_AT(block_base + i * kRowBytes, t.c16[N & 3], buf + i * kRgRowA);
+  } else {
+    const int m = wave + 4 * (N - kRgLoadsA);
+    AMLA_HIDDEN_LDS_LOAD_AT(block_base + m * 8 * kRowBytes, t.off_b, buf + kRgRegionA + m * 1024);
+  }
 }
 constexpr int kRgLoadsPerWave = kRgLoadsA + kRgLoadsB;   // 18
 
-constexpr int kKAhead = 3;   // [C1]: K operand pairs (two 32-key tiles of one 16-deep step) read this many steps ahead
+constexpr int kKAhead = 3;   // [C1]: K operands read this many MFMAs ahead
 constexpr int kVAhead = 4;   // [C2]: V operands read this many MFMAs ahead
 
 // acc + the two BF16 values packed in w, in FP32: one dot-product instruction with a pair of ones
@@ -115,6 +109,14 @@ constexpr int kVAhead = 4;   // [C2]: V operands read this many MFMAs ahead
 __device__ __forceinline__ float bf16_pair_sum(const unsigned w, const float acc) {
   const unsigned ones = 0x3f803f80u;
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, ones), acc, false);
+}
+#endif
+
+// max of x over the two lanes l and l ^ 32: one cross-half register swap, no LDS
+#ifndef AMLA_TARGET_HOOKS
+__device__ __forceinline__ float max_over_halves(const float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 #endif
 
@@ -182,6 +184,9 @@ __device__ __forceinline__ void acc_exponent_add_rows(const int n23) {
   asm volatile(AMLA_ACC_EACH_TILE(AMLA_ACC_ADD_ONE) : "=&v"(t), "=&v"(u) : "v"(n23), "n"(I) : AMLA_ACC_ALL);
 }
 __device__ __forceinline__ void acc_idle(void) { asm volatile("s_nop 7"); }
+// x stays where it is in the instruction stream, and nothing of the compiler's lives in an AccVGPR across this point
+// (between two statements that name the accumulator it would otherwise be free to put short-lived operands there)
+#define AMLA_PIN(x) asm volatile("" : "+v"(x) : : AMLA_ACC_ALL)
 // the kernel owns every AccVGPR from here on
 __device__ __forceinline__ void acc_claim(void) { asm volatile("" : : : AMLA_ACC_ALL); }
 #endif
@@ -247,8 +252,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   const TileLoadLane tl = tile_load_lane(wave, lane);
   if (j0 < j1) {
     const uint8_t* first = kvb + (size_t)phys_of(j0) * blk_bytes;
-#pragma unroll
-    for (int k = 0; k < kRgLoadsPerWave; ++k) issue_tile_load(first, smem, wave, tl, k);
+    static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(first, smem, wave, tl); });
   }
 
   // per-lane LDS offsets of the operand reads (see the tile layout above)
@@ -290,126 +294,209 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
       __syncthreads();
     }
 
-    // ---- [C1] S^T[64 keys x 32 rows] ----
-    f32x16 s[2];
-    s[0] = f32x16{0};
-    s[1] = f32x16{0};
-    {
-      bf16x8 ka[kKAhead][2];
-      auto k_addr = [&](int ks, int kt) {
-        if (ks < 32) return buf + ((ks & 1) ? k_odd : k_even) + kt * 32 * kRgRowA + (ks >> 1) * 64;
-        return buf + k_tail + 32 * ((ks - 32) ^ k_tail_x) + kt * 32 * kRgRowB;
-      };
-#pragma unroll
-      for (int d = 0; d < kKAhead; ++d) {
-        ka[d][0] = *(LDS_PTR(bf16x8))k_addr(d, 0);
-        ka[d][1] = *(LDS_PTR(bf16x8))k_addr(d, 1);
-      }
-#pragma unroll
-      for (int ks = 0; ks < kDqk / 16; ++ks) {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead][0], qf[ks], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead][1], qf[ks], s[1], 0, 0, 0);
-        if (ks + kKAhead < kDqk / 16) {
-          ka[ks % kKAhead][0] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 0);
-          ka[ks % kKAhead][1] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 1);
-        }
-        // the 18 loads of the next tile: one behind every second step
-        if (more && (ks & 1)) issue_tile_load(next_block, nxt, wave, tl, ks >> 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
+    // The block is worked as two sub-blocks of 32 keys, each one iteration of the online softmax, so that the
+    // vector work of one sub-block runs while the matrix pipe is busy with the other's product (a wave issues
+    // in order, but an MFMA keeps its pipe for 32 cycles and independent VALU instructions issue behind it):
+    //   phase A  S0^T = K[0:32] Q^T                      | the next tile's loads
+    //   phase B  S1^T = K[32:64] Q^T                     | softmax of sub-block 0
+    //            rescale for sub-block 0
+    //   phase C  O += P0 V[0:32]                         | softmax of sub-block 1
+    //            rescale for sub-block 1
+    //   phase D  O += P1 V[32:64]
+    // The softmax is cut into chunks of at most about seven VALU issue slots, one chunk behind each MFMA.
+    f32x16 s0 = f32x16{0}, s0b = f32x16{0}, s1 = f32x16{0};
+    bf16x8 ka[kKAhead];
+    auto k_addr = [&](int ks, int kt) {
+      if (ks < 32) return buf + ((ks & 1) ? k_odd : k_even) + kt * 32 * kRgRowA + (ks >> 1) * 64;
+      return buf + k_tail + 32 * ((ks - 32) ^ k_tail_x) + kt * 32 * kRgRowB;
+    };
+    constexpr int kSteps = kDqk / 16;   // 36 MFMAs per sub-block of the first product
 
-    // the first V operands of [C2] are fetched under the softmax
-    s16x4 vr[kVAhead][2];
-#pragma unroll
-    for (int d = 0; d < kVAhead; ++d) {
-      vr[d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_lo + d * 64));
-      vr[d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_hi + d * 64));
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- [V1] online softmax ----
-    if (MASKED ? rem < kBlock + mask_span : rem < kBlock) {
-      // with the causal mask a row's own limit lies causal_shift keys before the sequence's end
-      const int rem_row = MASKED ? rem - causal_shift : rem;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = 32 * kt + 4 * h + 8 * (r >> 2) + (r & 3);
-          if (key >= rem_row) s[kt][r] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * p.scale_log2e);
-    // Under a mask a row may have seen no key yet: it starts its recurrence at the first block that holds
-    // one, and until then keeps a finite reference so that its weights are 2^(-inf) = 0 and not NaN.
-    const bool first = MASKED ? ((j == j0) || m_run == -INFINITY) : (j == j0);
-    const float m_use = MASKED ? (m_new == -INFINITY ? 0.f : m_new) : m_new;
-
-    float ref_new;
-    float alpha = 1.f;   // factor on the old row sums (MUL, ADD_COMP) and, for MUL, on the old accumulator
-    int n23 = 0;         // ADD: (n_i - n_{i-1}) << 23, <= 0; ADD_COMP: plus the mantissa term
-    if (VARIANT == AMLA_RESCALE_ADD_COMP) {
-      // Algorithm 2's compensation (S32, S16, c_i, eps, N) in base 2: S32 = 2^(m - mu) in [2^-1/2, 2^1/2], S16 its
-      // BF16 rounding, weights 2^(t - m) S16 = 2^(t - (m - log2 S16)); the shift of the exponent field and the
-      // mantissa nudge 1.5 eps 2^23 travel in one integer
-      const float mu = __builtin_rintf(m_use);
-      const float s32 = fast_exp2(m_use - mu);
-      const float s16 = __uint_as_float(pack_bf16(s32, 0.f) << 16);
-      const float c_new = s16 / s32;
-      ref_new = m_use - fast_log2(s16);
-      if (!first) {
-        const float eps = 1.5f * (c_new / c_run - 1.f);
-        n23 = max((int)(mu_run - mu), -30) * (1 << 23) + (int)__builtin_rintf(eps * 8388608.f);
-        alpha = fast_exp2(ref - ref_new);
-      }
-      mu_run = mu;
-      c_run = c_new;
-    } else if (VARIANT == AMLA_RESCALE_MUL) {
-      ref_new = m_use;
-      if (!first) alpha = fast_exp2(ref - ref_new);
-    } else {
-      ref_new = __builtin_rintf(m_use);
-      if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
-    }
-    m_run = m_new;
-    ref = ref_new;
-
-    float psum = 0.f, bsum = 0.f;
+    // softmax state of the sub-block in flight
+    float mxp = 0.f;       // partial row max
+    float alpha = 1.f;     // factor on the old row sums (MUL, ADD_COMP) and, for MUL, on the old accumulator
+    int n23 = 0;           // ADD: (n_i - n_{i-1}) << 23, <= 0; ADD_COMP: plus the mantissa term
+    float psum = 0.f, bsum = 0.f, p_even = 0.f;
     unsigned pk[16];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const float p0 = fast_exp2(__builtin_fmaf(s[kt][r], p.scale_log2e, -ref_new));
-        const float p1 = fast_exp2(__builtin_fmaf(s[kt][r + 1], p.scale_log2e, -ref_new));
-        psum += p0 + p1;
-        const unsigned w = pack_bf16(p0, p1);
-        pk[kt * 8 + (r >> 1)] = w;
-        bsum = bf16_pair_sum(w, bsum);
-      }
-    // the row sums are kept per half of the wave (each half sums its own 32 keys of every block; both halves
-    // apply the same factors) and added once at the end of the piece
-    if (VARIANT == AMLA_RESCALE_ADD) {
-      l_f32 = exponent_add(l_f32, n23) + psum;
-      l_b16 = exponent_add(l_b16, n23) + bsum;
-    } else {
-      l_f32 = l_f32 * alpha + psum;
-      l_b16 = l_b16 * alpha + bsum;
-    }
+    const int rem_row = MASKED ? rem - causal_shift : rem;
+    const bool masked_block = MASKED ? rem < kBlock + mask_span : rem < kBlock;
 
-    // ---- [V2] rescale the accumulator registers of the rows whose reference moved ----
-    {
+    // chunk C of the softmax of sub-block SB (scores T).  The empty assembly statements pin a chunk's inputs and
+    // results to its place in the instruction stream (pure arithmetic would otherwise sink to its first use,
+    // behind the MFMAs it is meant to run under).
+    float m_new = 0.f, m_use = 0.f, p_odd = 0.f;
+    auto softmax_chunk = [&](auto sbc, auto cc, f32x16& T) {
+      constexpr int SB = sbc.value, C = cc.value;
+      if constexpr (C == 0) {
+        if (masked_block) {
+          // with the causal mask a row's own limit lies causal_shift keys before the sequence's end
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = 32 * SB + 4 * h + 8 * (r >> 2) + (r & 3);
+            if (key >= rem_row) T[r] = -INFINITY;
+          }
+        }
+        AMLA_OPAQUE(T);
+        mxp = fmaxf(fmaxf(T[0], T[1]), T[2]);
+        mxp = fmaxf(fmaxf(mxp, T[3]), T[4]);
+        mxp = fmaxf(fmaxf(mxp, T[5]), T[6]);
+        mxp = fmaxf(fmaxf(mxp, T[7]), T[8]);
+        AMLA_OPAQUE(mxp);
+      } else if constexpr (C == 1) {
+        mxp = fmaxf(fmaxf(mxp, T[9]), T[10]);
+        mxp = fmaxf(fmaxf(mxp, T[11]), T[12]);
+        mxp = fmaxf(fmaxf(mxp, T[13]), T[14]);
+        mxp = fmaxf(mxp, T[15]);
+        AMLA_OPAQUE(mxp);
+      } else if constexpr (C == 2) {
+        mxp = max_over_halves(mxp);
+        AMLA_OPAQUE(mxp);
+      } else if constexpr (C == 3) {
+        m_new = fmaxf(m_run, mxp * p.scale_log2e);
+        // Under a mask a row may have seen no key yet: it starts its recurrence at the first sub-block that holds
+        // one, and until then keeps a finite reference so that its weights are 2^(-inf) = 0 and not NaN.
+        m_use = MASKED ? (m_new == -INFINITY ? 0.f : m_new) : m_new;
+        AMLA_OPAQUE(m_new);
+        if (MASKED) AMLA_OPAQUE(m_use);
+      } else if constexpr (C == 4) {
+        if (!MASKED) m_use = m_new;
+        const bool first = MASKED ? ((j == j0 && SB == 0) || m_run == -INFINITY) : (j == j0 && SB == 0);
+        float ref_new;
+        alpha = 1.f;
+        n23 = 0;
+        if constexpr (SB == 0 && VARIANT != AMLA_RESCALE_ADD_COMP) {
+          // The reference is brought up to the running maximum once per 64-key block, behind the second
+          // sub-block (the block size of Algorithm 1 / Algorithm 2 stays the cache block).  The first sub-block
+          // keeps the previous block's reference when no row's maximum has left it by more than 2^8: its
+          // weights are then at most 2^8 instead of 1 -- the same relative precision in BF16 and FP32 -- and the
+          // accumulator is rescaled once per block instead of twice.  Otherwise, and in a piece's first block,
+          // the sub-block moves the reference itself.
+          const bool far = first || m_new - ref > 8.f;
+          if (j != j0 && __builtin_amdgcn_ballot_w64(far) == 0) {
+            m_run = m_new;
+            psum = 0.f;
+            bsum = 0.f;
+            AMLA_OPAQUE(m_run);
+            return;
+          }
+        }
+        if (VARIANT == AMLA_RESCALE_ADD_COMP) {
+          // Algorithm 2's compensation (S32, S16, c_i, eps, N) in base 2: S32 = 2^(m - mu) in [2^-1/2, 2^1/2], S16 its
+          // BF16 rounding, weights 2^(t - m) S16 = 2^(t - (m - log2 S16)); the shift of the exponent field and the
+          // mantissa nudge 1.5 eps 2^23 travel in one integer
+          const float mu = __builtin_rintf(m_use);
+          const float s32 = fast_exp2(m_use - mu);
+          const float s16 = __uint_as_float(pack_bf16(s32, 0.f) << 16);
+          const float c_new = s16 / s32;
+          ref_new = m_use - fast_log2(s16);
+          if (!first) {
+            const float eps = 1.5f * (c_new / c_run - 1.f);
+            n23 = max((int)(mu_run - mu), -30) * (1 << 23) + (int)__builtin_rintf(eps * 8388608.f);
+            alpha = fast_exp2(ref - ref_new);
+          }
+          mu_run = mu;
+          c_run = c_new;
+        } else if (VARIANT == AMLA_RESCALE_MUL) {
+          ref_new = m_use;
+          if (!first) alpha = fast_exp2(ref - ref_new);
+        } else {
+          ref_new = __builtin_rintf(m_use);
+          if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
+        }
+        m_run = m_new;
+        ref = ref_new;
+        psum = 0.f;
+        bsum = 0.f;
+        AMLA_OPAQUE(ref);
+        if (VARIANT == AMLA_RESCALE_MUL)
+          AMLA_OPAQUE(alpha);
+        else
+          AMLA_OPAQUE(n23);
+      } else if constexpr (C < 5 + 24) {
+        // the 16 weights, a pair per three chunks: two exponentials, then the sums and the BF16 pair
+        constexpr int q = (C - 5) / 3, part = (C - 5) % 3;
+        if constexpr (part < 2) {
+          float t = T[2 * q + part];
+          AMLA_OPAQUE(t);
+          const float pv = fast_exp2(__builtin_fmaf(t, p.scale_log2e, -ref));
+          if constexpr (part == 0) {
+            p_even = pv;
+            AMLA_OPAQUE(p_even);
+          } else {
+            p_odd = pv;
+            AMLA_OPAQUE(p_odd);
+          }
+        } else {
+          psum += p_even + p_odd;
+          unsigned w = pack_bf16(p_even, p_odd);
+          bsum = bf16_pair_sum(w, bsum);
+          AMLA_OPAQUE(psum);
+          AMLA_OPAQUE(w);
+          AMLA_OPAQUE(bsum);
+          pk[SB * 8 + q] = w;
+        }
+      } else if constexpr (C == 29) {
+        // the row sums are kept per half of the wave (each half sums its own keys of every sub-block; both halves
+        // apply the same factors) and added once at the end of the piece
+        l_f32 = (VARIANT == AMLA_RESCALE_ADD ? exponent_add(l_f32, n23) : l_f32 * alpha) + psum;
+        AMLA_OPAQUE(l_f32);
+      } else if constexpr (C == 30) {
+        l_b16 = (VARIANT == AMLA_RESCALE_ADD ? exponent_add(l_b16, n23) : l_b16 * alpha) + bsum;
+        AMLA_OPAQUE(l_b16);
+      }
+    };
+    constexpr int kSoftmaxChunks = 31;
+    // the same work in 47 smaller chunks (a pair of weights in five: the two arguments, either exponential, the
+    // sums, the BF16 pair), for the steps of the second product, which have less issue time to spare
+    float t_even = 0.f, t_odd = 0.f;
+    auto softmax_fine = [&](auto sbc, auto cc, f32x16& T) {
+      constexpr int SB = sbc.value, C = cc.value;
+      if constexpr (C < 5) {
+        softmax_chunk(sbc, cc, T);
+      } else if constexpr (C < 45) {
+        constexpr int q = (C - 5) / 5, part = (C - 5) % 5;
+        if constexpr (part == 0) {
+          float a = T[2 * q], b = T[2 * q + 1];
+          AMLA_OPAQUE(a);
+          AMLA_OPAQUE(b);
+          t_even = __builtin_fmaf(a, p.scale_log2e, -ref);
+          t_odd = __builtin_fmaf(b, p.scale_log2e, -ref);
+          AMLA_OPAQUE(t_even);
+          AMLA_OPAQUE(t_odd);
+        } else if constexpr (part == 1) {
+          p_even = fast_exp2(t_even);
+          AMLA_OPAQUE(p_even);
+        } else if constexpr (part == 2) {
+          p_odd = fast_exp2(t_odd);
+          AMLA_OPAQUE(p_odd);
+        } else if constexpr (part == 3) {
+          psum += p_even + p_odd;
+          AMLA_OPAQUE(psum);
+        } else {
+          unsigned w = pack_bf16(p_even, p_odd);
+          bsum = bf16_pair_sum(w, bsum);
+          AMLA_OPAQUE(w);
+          AMLA_OPAQUE(bsum);
+          pk[SB * 8 + q] = w;
+        }
+      } else {
+        softmax_chunk(sbc, std::integral_constant<int, C - 45 + 29>{}, T);
+      }
+    };
+    constexpr int kFineChunks = 47;
+
+    // [V2] rescale the accumulator registers of the rows whose reference moved in the sub-block just finished.
+    // `drain`: the second product's last MFMAs may still be in flight.
+    auto rescale = [&](const bool not_first, const bool drain) {
       const bool moved = VARIANT == AMLA_RESCALE_MUL ? alpha != 1.f : n23 != 0;
       unsigned rows_moved = (unsigned)__builtin_amdgcn_ballot_w64(moved);   // bit r: row r of the wave (both halves agree)
-      if ((p.flags & AMLA_FLAG_NO_SKIP) && j != j0) rows_moved = 0xffffffffu;
+      if ((p.flags & AMLA_FLAG_NO_SKIP) && not_first) rows_moved = 0xffffffffu;
       if (rows_moved != 0) {
+        if (drain) {
+          acc_idle();
+          acc_idle();
+          acc_idle();
+        }
         const int bits = VARIANT == AMLA_RESCALE_MUL ? __float_as_int(alpha) : n23;
         static_for<4>([&](auto gc) {
           constexpr int g = gc.value;
@@ -431,21 +518,90 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
         });
         acc_idle();
       }
-    }
+    };
 
-    // ---- [C2] O[32 rows x 512] += P V ----
-    static_for<4 * (kDv / 32)>([&](auto nc) {
+    // ---- phase A: [C1] for keys 0 .. 31; the next block streams in under it ----
+#pragma unroll
+    for (int d = 0; d < kKAhead; ++d) ka[d] = *(LDS_PTR(bf16x8))k_addr(d, 0);
+    auto phase_a = [&](auto more_c) {
+      static_for<kSteps>([&](auto ksc) {
+        constexpr int ks = ksc.value;
+        // two accumulation chains (even and odd steps): a dependent MFMA issues some cycles late
+        if constexpr ((ks & 1) == 0) {
+          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead], qf[ks], s0, 0, 0, 0);
+          AMLA_PIN(s0);
+        } else {
+          s0b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead], qf[ks], s0b, 0, 0, 0);
+          AMLA_PIN(s0b);
+        }
+        constexpr int nk = ks + kKAhead;
+        ka[ks % kKAhead] = *(LDS_PTR(bf16x8))(nk < kSteps ? k_addr(nk, 0) : k_addr(nk - kSteps, 1));
+        // the 18 loads of the next tile: one behind every second step
+        if constexpr (more_c.value && (ks & 1)) issue_tile_load<(ks >> 1)>(next_block, nxt, wave, tl);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+    if (more)
+      phase_a(std::true_type{});
+    else
+      phase_a(std::false_type{});
+
+    // ---- phase B: [C1] for keys 32 .. 63 | [V1] of sub-block 0 ----
+    static_for<kSteps>([&](auto ksc) {
+      constexpr int ks = ksc.value;
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(kSteps + ks) % kKAhead], qf[ks], s1, 0, 0, 0);
+      AMLA_PIN(s1);
+      if constexpr (ks + kKAhead < kSteps) ka[(kSteps + ks) % kKAhead] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 1);
+      if constexpr (ks < 4) {
+        // the two chains of the first sub-block are joined here, four scores a step
+#pragma unroll
+        for (int r = 4 * ks; r < 4 * ks + 4; ++r) s0[r] += s0b[r];
+        if constexpr (ks == 3) AMLA_OPAQUE(s0);
+      } else if constexpr (ks - 4 < kSoftmaxChunks) {
+        softmax_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, ks - 4>{}, s0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+
+    // the first V operands of [C2]
+    s16x4 vr[kVAhead][2];
+#pragma unroll
+    for (int d = 0; d < kVAhead; ++d) {
+      vr[d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_lo + d * 64));
+      vr[d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_hi + d * 64));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    rescale(j != j0, false);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- [C2] O[32 rows x 512] += P V, 16 keys x 32 columns per MFMA ----
+    auto pv_step = [&](auto nc) {
       constexpr int n = nc.value, st = n / (kDv / 32), dt = n % (kDv / 32);
       const i32x4 pb = {(int)pk[4 * st], (int)pk[4 * st + 1], (int)pk[4 * st + 2], (int)pk[4 * st + 3]};
       const i32x2 lo2 = __builtin_bit_cast(i32x2, vr[n % kVAhead][0]), hi2 = __builtin_bit_cast(i32x2, vr[n % kVAhead][1]);
       const i32x4 vb = {lo2[0], lo2[1], hi2[0], hi2[1]};
       acc_mfma<dt>(__builtin_bit_cast(bf16x8, pb), __builtin_bit_cast(bf16x8, vb));
       constexpr int nx = n + kVAhead;
-      if (nx < 4 * (kDv / 32)) {
+      if constexpr (nx < 4 * (kDv / 32)) {
         constexpr int step = (nx / (kDv / 32)) * 16 * kRgRowA + (nx % (kDv / 32)) * 64;
         vr[n % kVAhead][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_lo + step));
         vr[n % kVAhead][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(buf + v_hi + step));
       }
+    };
+    // ---- phase C: keys 0 .. 31 | [V1] of sub-block 1 ----
+    // (one fine chunk a step: maximum, reference, and the weights of keys 32 .. 53)
+    static_for<2 * (kDv / 32)>([&](auto nc) {
+      pv_step(nc);
+      softmax_fine(std::integral_constant<int, 1>{}, nc, s1);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    rescale(true, true);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- phase D: keys 32 .. 63 | the remaining weights (keys 54 .. 63, needed from step 16 on) and the row sums ----
+    static_for<2 * (kDv / 32)>([&](auto nc) {
+      constexpr int n = nc.value;
+      pv_step(std::integral_constant<int, 2 * (kDv / 32) + n>{});
+      if constexpr (32 + n < kFineChunks) softmax_fine(std::integral_constant<int, 1>{}, std::integral_constant<int, 32 + n>{}, s1);
       __builtin_amdgcn_sched_barrier(0);
     });
   }

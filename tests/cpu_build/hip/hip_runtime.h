@@ -335,6 +335,7 @@ inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); 
 #define AMLA_WAIT_TILE_LOADS() shim::wait_tile_loads()
 #endif
 #define AMLA_OPAQUE(x) ((void)(x))
+#define AMLA_PIN(x) ((void)(x))
 #define AMLA_ONE_WAVE_PER_SIMD
 #define AMLA_TWO_WAVES_PER_SIMD
 #define AMLA_UNIFORM_LOAD_I32(p, i) ((p)[i])
@@ -380,6 +381,8 @@ inline void wait_tile_loads_but(int n) { shim::wait_tile_loads_but(n); }
 inline float bf16_pair_sum(unsigned w, float acc) {
   return acc + (__builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u));
 }
+// v_permlane32_swap + max: the larger of x in lanes l and l ^ 32
+inline float max_over_halves(float x) { return std::fmax(x, shim::shfl_xor(x, 32)); }
 inline void acc_idle() {}
 inline void acc_claim() {}
 
