@@ -216,22 +216,6 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   const int row = tile * kRowsPerWg + wave * 32 + l32;   // this lane's query row within the sequence
   const size_t grow = (size_t)b * p.rows + (row < p.rows ? row : 0);
 
-  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
-  // sequence's row range read row 0 (valid memory); their results are never stored.
-  bf16x8 qf[kDqk / 16];
-  {
-    const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
-#pragma unroll
-    for (int ks = 0; ks < kDqk / 16; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
-    // waited for here: the tile loads are hidden from the compiler's wait counting, and a wait for these
-    // loads left inside the loop would be a wait for the tile
-#pragma unroll
-    for (int ks = 0; ks < kDqk / 16; ++ks) AMLA_ARRIVED(qf[ks]);
-  }
-
-  // accumulator register 16 dt + i: value column 32 dt + l32, query row 32 wave + 8 (i / 4) + 4 h + i % 4
-  static_for<256>([&](auto r) { acc_clear<r.value>(); });
-
   float m_run = -INFINITY;   // running row max of t = s * scale * log2 e
   float ref = 0.f;           // reference subtracted in the exponent: m_run (MUL), rint(m_run) (ADD),
                              // m_run - log2 S16 (ADD_COMP)
@@ -239,6 +223,14 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   float c_run = 1.f;         // ADD_COMP: c_i = S16 / S32
   float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse), over this half-wave's keys
   float l_b16 = 0.f;         // sum of the BF16-rounded weights (normalises the output), over this half-wave's keys
+
+  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
+  // sequence's row range read row 0 (valid memory); their results are never stored.  Issued first: nothing
+  // else in the prologue depends on them, and the block-table lookup below is a memory round trip of its own.
+  bf16x8 qf[kDqk / 16];
+  const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
+#pragma unroll
+  for (int ks = 0; ks < kDqk / 16; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
 
   const int32_t* tab = p.table + (size_t)b * p.max_blocks;
   const uint8_t* kvb = reinterpret_cast<const uint8_t*>(p.kv);
@@ -254,6 +246,15 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     const uint8_t* first = kvb + (size_t)phys_of(j0) * blk_bytes;
     static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(first, smem, wave, tl); });
   }
+
+  // (The first tile and the query rows are on their way; the accumulator is cleared under their latency.)
+  // accumulator register 16 dt + i: value column 32 dt + l32, query row 32 wave + 8 (i / 4) + 4 h + i % 4
+  static_for<256>([&](auto r) { acc_clear<r.value>(); });
+
+  // The query rows are waited for here: the tile loads are hidden from the compiler's wait counting, and a wait
+  // for these loads left inside the loop would be a wait for the tile.
+#pragma unroll
+  for (int ks = 0; ks < kDqk / 16; ++ks) AMLA_ARRIVED(qf[ks]);
 
   // per-lane LDS offsets of the operand reads (see the tile layout above)
   // [C1] A operand, steps 0 .. 31 (region A): row l32 (+ 32 for the second key tile), chunk 2 ks + h; even and
