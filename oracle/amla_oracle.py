@@ -22,10 +22,12 @@ What it holds
 * `amla_fp32_emulation` Algorithm 2's loop in FP32 with BF16 P and the INT32 exponent add,
                        without the BF16 scale compensation (the S32 / S16 / c_i steps).
 * `flash_fp32_emulation` Algorithm 1 in FP32 with BF16 P (the paper's "Base", Section 5.1).
-* `amla_alg2_emulation` Algorithm 2 with its BF16 scale compensation, step by step in the paper's
-                       notation, with either printed definition of c_i.
-* `amla_comp_fp32_emulation` the same compensation restated in base 2 with one reference per row
-                       and integer-built N (the form of the kernels' ADD_COMP variant).
+* `amla_comp_fp32_emulation` Algorithm 2 with its BF16 scale compensation (Appendix A) in base 2 with one
+                       reference per row; defaults = the form of the kernels' ADD_COMP variant, options
+                       for either definition of c_i, the truncating cast with its guard, the plain add
+                       and the FP32 normaliser.
+* `amla_alg2_emulation` the same with the paper's own parameter choices (512-key blocks, truncating
+                       cast with 1e-6, plain add, FP32 row sum).
 * `frobenius_error`    the error metric of Section 5.1.
 
 Pins (tests/test_oracle_*.py): the worked example of Section 3.2 (0.5 <-> 126 * 2^23),
@@ -268,58 +270,27 @@ def amla_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, lazy_threshold=None
     return out, lse
 
 
-def amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="appendix", guard=1e-6):
-    """Algorithm 2 step by step in FP32, in the paper's notation, with its BF16 scale compensation
-    (the steps from S32 to N): S32 = exp(ln2 (n_i + m_i / ln2)), S16 = BF16(S32), c_i, eps = 1.5 (c_i / c_{i-1} - 1),
-    P <- BF16(P * S16), N = Cast_to_int32((max(n_i - n_{i-1}, -30) + eps + 1e-6) * 2^23), O <- AS_FP32(
-    AS_INT32(O) + N), O += P V, and O / (l_N * S16) at the end.
+def amla_comp_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, with_eps=True, c_reading="appendix", cast="rint",
+                            guard=0.0, saturate=True, normalise="b16"):
+    """Algorithm 2 with its BF16 scale compensation (Appendix A) in FP32, stated in base 2 with one reference per
+    row: mu = rint(m) (the algorithm's -n_i), S32 = 2^(m - mu), S16 = BF16(S32), weights P = 2^(t - ref) with
+    ref = m - log2 S16 (so P = 2^(t - m) S16 and the largest weight of a row is S16, BF16-exact), and on every
+    block but the first the integer N = 2^23 ((mu_prev - mu) clamped at `clamp`) + 2^23 * 1.5 (c / c_prev - 1) added
+    to the accumulator's bit patterns.  Two row sums relative to ref, rescaled by the exact factor
+    2^(ref_prev - ref): the FP32 sum of the unrounded weights (gives lse; it equals the algorithm's l_i S16) and
+    the sum of the BF16-rounded weights.
 
-    `c_reading` selects between the two definitions of c_i the paper gives: "algorithm" is the assignment to c_i as
-    printed (c_i = S32 / S16), "appendix" is Appendix A (c_i = r_i / r'_i = S16 / S32, since
-    S32 = 1 / r_i and S16 = 1 / r'_i).  Block size 512 is the paper's (Section 4.2)."""
-    f32 = np.float32
-    G, L = Q.shape[0], K.shape[0]
-    O = np.zeros((G, V.shape[1]), dtype=f32)
-    l = np.zeros(G, dtype=f32)
-    m = np.full(G, -np.inf, dtype=f32)
-    n_prev = None
-    c_prev = np.ones(G, dtype=f32)
-    S16 = np.ones(G, dtype=f32)
-    ln2 = f32(LN2)
-    for i, lo in enumerate(range(0, L, block)):
-        Kb, Vb = K[lo:lo + block], V[lo:lo + block]
-        S = ((Q @ Kb.T).astype(f32) * f32(scale)).astype(f32)
-        m_new = np.maximum(m, S.max(axis=1))
-        M_up = np.exp((m - m_new).astype(f32)).astype(f32)
-        n = np.rint(-m_new / ln2).astype(f32)
-        P = np.exp((S - m_new[:, None]).astype(f32)).astype(f32)
-        l = (l * M_up + P.sum(axis=1, dtype=f32)).astype(f32)
-        S32 = np.exp((ln2 * (n + m_new / ln2)).astype(f32)).astype(f32)
-        S16 = _round_bf16(S32)
-        c = (S32 / S16 if c_reading == "algorithm" else S16 / S32).astype(f32)
-        eps = (f32(1.5) * (c / c_prev - f32(1))).astype(f32)
-        Pb = _round_bf16((P * S16[:, None]).astype(f32))
-        if i > 0:
-            N = (np.maximum(n - n_prev, f32(-30)) + eps + f32(guard)).astype(f32)
-            Nint = np.trunc(N.astype(np.float64) * 2.0 ** 23).astype(np.int64)
-            I = as_int32(O).astype(np.int64) + Nint[:, None]
-            O = as_fp32((((I + (1 << 31)) % (1 << 32)) - (1 << 31)).astype(np.int32)).copy()
-        O = (O + (Pb @ Vb).astype(f32)).astype(f32)
-        m, n_prev, c_prev = m_new, n, c
-    return (O / (l * S16)[:, None]).astype(f32)
-
-
-def amla_comp_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, with_eps=True):
-    """Algorithm 2 with its compensation (the steps from S32 to N, Appendix A's c_i) restated in base 2 with one
-    reference per row, the form a register-resident kernel takes: mu = rint(m) = -n_i,
-    S32 = 2^(m - mu), S16 = BF16(S32), c = S16 / S32, weights P = 2^(t - ref) with
-    ref = m - log2 S16 (so P = 2^(t - m) S16 and the largest weight of a row is S16, BF16-exact),
-    N = ((mu_prev - mu) clamped at -30) * 2^23 + rint(2^23 * 1.5 (c / c_prev - 1)) built in integer
-    arithmetic (no 1e-6 guard: that guard protects a truncating float-to-int cast), guarded add of
-    N on the accumulator.  Two row sums relative to ref, rescaled by the exact factor 2^(ref_prev -
-    ref): the FP32 sum of the unrounded weights gives lse, the sum of the BF16-rounded weights
-    normalises the output.  `with_eps=False` drops the mantissa term (what the compensation buys
-    is then visible)."""
+    The defaults are the form the kernels take.  The options select what the paper's text fixes differently or
+    leaves open:
+      c_reading  "appendix": c = S16 / S32 (Appendix A: c_i = r_i / r'_i); "algorithm": the reciprocal, as the
+                 assignment in Algorithm 2 reads
+      cast       "rint": the shift is an integer by construction and the mantissa term is rounded; "trunc": shift,
+                 mantissa term and `guard` are added in FP32 and the product with 2^23 is truncated (Algorithm
+                 2's Cast_to_int32 with its 1e-6)
+      saturate   True: guarded add (saturating, never past the signed zero); False: the plain wrapping INT32 add
+      normalise  "b16": output divided by the sum of the rounded weights; "f32": by the FP32 sum (the
+                 algorithm's O / (l_N S16))
+      with_eps   False drops the mantissa term (what the compensation buys is then visible)"""
     f32 = np.float32
     G, L = Q.shape[0], K.shape[0]
     O = np.zeros((G, V.shape[1]), dtype=f32)
@@ -335,18 +306,23 @@ def amla_comp_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, with_eps=True)
         mu_new = np.rint(m)
         S32 = np.exp2((m - mu_new).astype(f32)).astype(f32)
         S16 = _round_bf16(S32)
-        c = (S16 / S32).astype(f32)
+        c = (S16 / S32 if c_reading == "appendix" else S32 / S16).astype(f32)
         ref_new = (m - np.log2(S16).astype(f32)).astype(f32)
         P = np.exp2((t - ref_new[:, None]).astype(f32)).astype(f32)
         Pb = _round_bf16(P)
         if mu is not None:
-            N = np.maximum(mu - mu_new, clamp).astype(np.int64) << 23
-            if with_eps:
-                eps = (f32(1.5) * ((c / c_prev).astype(f32) - f32(1))).astype(f32)
-                N = N + np.rint((eps * f32(2.0 ** 23)).astype(f32)).astype(np.int64)
+            shift = np.maximum(mu - mu_new, f32(clamp)).astype(f32)
+            eps = (f32(1.5) * ((c / c_prev).astype(f32) - f32(1))).astype(f32) if with_eps else np.zeros(G, f32)
+            if cast == "rint":
+                N = (shift.astype(np.int64) << 23) + np.rint((eps * f32(2.0 ** 23)).astype(f32)).astype(np.int64)
+            else:
+                N = np.trunc((shift + eps + f32(guard)).astype(f32).astype(np.float64) * 2.0 ** 23).astype(np.int64)
             I = as_int32(O).astype(np.int64)
-            R = np.clip(I + N[:, None], -(1 << 31), (1 << 31) - 1)       # saturating INT32 add
-            R = np.maximum(R, np.where(I < 0, -(1 << 31), 0))            # never below the signed zero
+            if saturate:
+                R = np.clip(I + N[:, None], -(1 << 31), (1 << 31) - 1)       # saturating INT32 add
+                R = np.maximum(R, np.where(I < 0, -(1 << 31), 0))            # never below the signed zero
+            else:
+                R = ((I + N[:, None] + (1 << 31)) % (1 << 32)) - (1 << 31)   # wrapping INT32 add
             O = as_fp32(R.astype(np.int32)).copy()
             a = np.exp2((ref - ref_new).astype(f32)).astype(f32)
             l32 = (l32 * a).astype(f32)
@@ -355,9 +331,17 @@ def amla_comp_fp32_emulation(Q, K, V, scale, block=64, clamp=-30, with_eps=True)
         l16 = (l16 + Pb.sum(axis=1, dtype=f32)).astype(f32)
         O = (O + (Pb @ Vb).astype(f32)).astype(f32)
         mu, c_prev, ref = mu_new, c, ref_new
-    out = O / l16[:, None]
+    out = O / (l16 if normalise == "b16" else l32)[:, None]
     lse = (ref.astype(np.float64) + np.log2(l32.astype(np.float64))) * LN2
     return out, lse
+
+
+def amla_alg2_emulation(Q, K, V, scale, block=512, c_reading="appendix", guard=1e-6):
+    """The compensated recurrence with the parameter choices of the paper's own kernel (Algorithm 2, Section 4.2):
+    512-key blocks, the truncating cast with its 1e-6, the plain integer add, the output divided by the FP32 row
+    sum.  `c_reading` as in amla_comp_fp32_emulation.  Returns the output only."""
+    return amla_comp_fp32_emulation(Q, K, V, scale, block=block, c_reading=c_reading, cast="trunc", guard=guard,
+                                    saturate=False, normalise="f32")[0]
 
 
 def flash_fp32_emulation(Q, K, V, scale, block=64):
