@@ -34,7 +34,10 @@
  *
  * Two kernel families run the path.  The default lays the accumulator out query row by register
  * (second product computed as O = P V): a register then belongs to two query rows, and the rescale
- * touches only the 16 registers of each row whose reference moved in the block.  The other
+ * touches only the 16 registers of each row whose reference moved in the block.  It works a block as two
+ * 32-key halves so that the softmax of one half runs under the MFMAs of the other; the reference follows
+ * the running maximum once per 64-key block (MUL, ADD; the first half keeps the previous block's
+ * reference while no row has left it by more than 2^8) or per half (ADD_COMP).  The other
  * (AMLA_FLAG_TRANSPOSED_ACC) computes both products transposed, so the rescale factor is a per-lane
  * scalar and every rescale passes over all 256 accumulator registers of the wave; it is kept as the
  * baseline in which the cost of the paper's [V2] stage shows, and carries the lazy and ldexp forms.
