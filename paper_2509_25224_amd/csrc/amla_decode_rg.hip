@@ -101,7 +101,7 @@ __device__ __forceinline__ void issue_tile_load(const uint8_t* block_base, LDS_P
 }
 constexpr int kRgLoadsPerWave = kRgLoadsA + kRgLoadsB;   // 18
 
-constexpr int kKAhead = 3;   // [C1]: K operands read this many MFMAs ahead
+constexpr int kKAhead = 4;   // [C1]: K operands read this many MFMAs ahead
 constexpr int kVAhead = 4;   // [C2]: V operands read this many MFMAs ahead
 
 // acc + the two BF16 values packed in w, in FP32: one dot-product instruction with a pair of ones
@@ -305,7 +305,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     //            rescale for sub-block 1
     //   phase D  O += P1 V[32:64]
     // The softmax is cut into chunks of at most about seven VALU issue slots, one chunk behind each MFMA.
-    f32x16 s0 = f32x16{0}, s0b = f32x16{0}, s1 = f32x16{0};
+    f32x16 s0 = f32x16{0}, s1 = f32x16{0};
     bf16x8 ka[kKAhead];
     auto k_addr = [&](int ks, int kt) {
       if (ks < 32) return buf + ((ks & 1) ? k_odd : k_even) + kt * 32 * kRgRowA + (ks >> 1) * 64;
@@ -465,15 +465,19 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
           AMLA_OPAQUE(t_even);
           AMLA_OPAQUE(t_odd);
         } else if constexpr (part == 1) {
+          AMLA_OPAQUE(t_even);
           p_even = fast_exp2(t_even);
           AMLA_OPAQUE(p_even);
         } else if constexpr (part == 2) {
+          AMLA_OPAQUE(t_odd);
           p_odd = fast_exp2(t_odd);
           AMLA_OPAQUE(p_odd);
         } else if constexpr (part == 3) {
+          AMLA_OPAQUE(p_even);
           psum += p_even + p_odd;
           AMLA_OPAQUE(psum);
         } else {
+          AMLA_OPAQUE(p_odd);
           unsigned w = pack_bf16(p_even, p_odd);
           bsum = bf16_pair_sum(w, bsum);
           AMLA_OPAQUE(w);
@@ -527,14 +531,8 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     auto phase_a = [&](auto more_c) {
       static_for<kSteps>([&](auto ksc) {
         constexpr int ks = ksc.value;
-        // two accumulation chains (even and odd steps): a dependent MFMA issues some cycles late
-        if constexpr ((ks & 1) == 0) {
-          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead], qf[ks], s0, 0, 0, 0);
-          AMLA_PIN(s0);
-        } else {
-          s0b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead], qf[ks], s0b, 0, 0, 0);
-          AMLA_PIN(s0b);
-        }
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks % kKAhead], qf[ks], s0, 0, 0, 0);
+        AMLA_PIN(s0);
         constexpr int nk = ks + kKAhead;
         ka[ks % kKAhead] = *(LDS_PTR(bf16x8))(nk < kSteps ? k_addr(nk, 0) : k_addr(nk - kSteps, 1));
         // the 18 loads of the next tile: one behind every second step
@@ -553,14 +551,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
       s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(kSteps + ks) % kKAhead], qf[ks], s1, 0, 0, 0);
       AMLA_PIN(s1);
       if constexpr (ks + kKAhead < kSteps) ka[(kSteps + ks) % kKAhead] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 1);
-      if constexpr (ks < 4) {
-        // the two chains of the first sub-block are joined here, four scores a step
-#pragma unroll
-        for (int r = 4 * ks; r < 4 * ks + 4; ++r) s0[r] += s0b[r];
-        if constexpr (ks == 3) AMLA_OPAQUE(s0);
-      } else if constexpr (ks - 4 < kSoftmaxChunks) {
-        softmax_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, ks - 4>{}, s0);
-      }
+      if constexpr (ks < kSoftmaxChunks) softmax_chunk(std::integral_constant<int, 0>{}, ksc, s0);
       __builtin_amdgcn_sched_barrier(0);
     });
 
