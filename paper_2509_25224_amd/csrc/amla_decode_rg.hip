@@ -156,9 +156,12 @@ __device__ __forceinline__ void acc_mfma(const bf16x8 a, const bf16x8 b) {
                : "v"(a), "v"(b), "n"(DT)
                : AMLA_ACC_ALL);
 }
-template <int R>
-__device__ __forceinline__ void acc_clear() {
-  asm volatile("v_accvgpr_write_b32 a[%0], 0" : : "n"(R) : AMLA_ACC_ALL);
+// tile DT <- 0: one MFMA with a zero addend and zero operands instead of sixteen register writes
+template <int DT>
+__device__ __forceinline__ void acc_clear_tile() {
+  const bf16x8 z = __builtin_bit_cast(bf16x8, i32x4{0, 0, 0, 0});
+  // (two idle states first: the zero operand may have been written by the VALU instruction just before)
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 a[%1*16:%1*16+15], %0, %0, 0" : : "v"(z), "n"(DT) : AMLA_ACC_ALL);
 }
 template <int R>
 __device__ __forceinline__ float acc_read() {
@@ -210,7 +213,8 @@ template <int VARIANT, bool MASKED>
 __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint8_t) smem, const int lane,
                                              const int wave, const int b, const int kv_len, const int j0,
                                              const int j1, const int tile, const bool to_final,
-                                             const size_t part_row0, const int causal_shift, const int mask_span) {
+                                             const size_t part_row0, const int causal_shift, const int mask_span,
+                                             const bool first_piece) {
   const int l32 = lane & 31;
   const int h = lane >> 5;
   const int row = tile * kRowsPerWg + wave * 32 + l32;   // this lane's query row within the sequence
@@ -224,32 +228,37 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   float l_f32 = 0.f;         // sum of 2^(t - ref) in FP32 (feeds lse), over this half-wave's keys
   float l_b16 = 0.f;         // sum of the BF16-rounded weights (normalises the output), over this half-wave's keys
 
-  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
-  // sequence's row range read row 0 (valid memory); their results are never stored.  Issued first: nothing
-  // else in the prologue depends on them, and the block-table lookup below is a memory round trip of its own.
-  bf16x8 qf[kDqk / 16];
-  const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
-#pragma unroll
-  for (int ks = 0; ks < kDqk / 16; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
-
   const int32_t* tab = p.table + (size_t)b * p.max_blocks;
   const uint8_t* kvb = reinterpret_cast<const uint8_t*>(p.kv);
   const size_t blk_bytes = (size_t)kBlock * kRowBytes;
   auto phys_of = [&](int j) {
     return min(max(__builtin_amdgcn_readfirstlane(AMLA_UNIFORM_LOAD_I32(tab, j)), 0), p.num_blocks - 1);
   };
+  // The block-table entry of the first block is asked for first (a memory round trip of its own), then the
+  // query rows; the first tile's loads follow as soon as the entry is there.
+  const int first_entry = j0 < j1 ? AMLA_UNIFORM_LOAD_I32(tab, j0) : 0;
+  __builtin_amdgcn_sched_barrier(0);
+
+  // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
+  // sequence's row range read row 0 (valid memory); their results are never stored.
+  bf16x8 qf[kDqk / 16];
+  const i32x4* qrow = reinterpret_cast<const i32x4*>(p.q + grow * kDqk) + h;
+#pragma unroll
+  for (int ks = 0; ks < kDqk / 16; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qrow[2 * ks]);
+  __builtin_amdgcn_sched_barrier(0);
+  const int first_phys = min(max(__builtin_amdgcn_readfirstlane(first_entry), 0), p.num_blocks - 1);
 
   // the previous piece's last tile may still be read by a slower wave
-  __syncthreads();
+  if (!first_piece) __syncthreads();
   const TileLoadLane tl = tile_load_lane(wave, lane);
   if (j0 < j1) {
-    const uint8_t* first = kvb + (size_t)phys_of(j0) * blk_bytes;
+    const uint8_t* first = kvb + (size_t)first_phys * blk_bytes;
     static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(first, smem, wave, tl); });
   }
 
   // (The first tile and the query rows are on their way; the accumulator is cleared under their latency.)
   // accumulator register 16 dt + i: value column 32 dt + l32, query row 32 wave + 8 (i / 4) + 4 h + i % 4
-  static_for<256>([&](auto r) { acc_clear<r.value>(); });
+  static_for<kDv / 32>([&](auto dt) { acc_clear_tile<dt.value>(); });
 
   // The query rows are waited for here: the tile loads are hidden from the compiler's wait counting, and a wait
   // for these loads left inside the loop would be a wait for the tile.
@@ -660,7 +669,7 @@ void amla_decode_rg_kernel(const DecodeParams p) {
   const int j0 = (int)(((long long)split * nb) / p.n_splits);
   const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
   decode_piece<VARIANT, false>(p, smem, lane, wave, b, kv_len, j0, j1, tile, p.n_splits == 1,
-                               (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0);
+                               (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0, true);
 }
 
 // Balanced decomposition (ragged batches, causal mask among the s_q tokens, per-sequence query counts):
@@ -716,6 +725,7 @@ void amla_decode_rg_balanced_kernel(const DecodeParams p) {
 
   const int row = tile * kRowsPerWg + wave * 32 + (lane & 31);   // this lane's query row within the sequence
   PlanWalk walk = {b0, jstart, g1 - g0};
+  bool first_piece = true;
   while (walk.left > 0 && walk.b < p.batch) {
     const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[walk.b]), p.max_blocks, kBlock);
     PlanPiece piece;
@@ -731,7 +741,8 @@ void amla_decode_rg_balanced_kernel(const DecodeParams p) {
     const int t_row = row / p.heads;
     const int causal_shift = t_row >= q_len ? kNoKeys : (p.causal_span != 0 ? q_len - 1 - t_row : 0);
     decode_piece<VARIANT, true>(p, smem, lane, wave, piece.b, kv_len, piece.j0, piece.j1, tile, piece.full != 0,
-                                ((size_t)stream + piece.b) * p.rows, causal_shift, mask_span);
+                                ((size_t)stream + piece.b) * p.rows, causal_shift, mask_span, first_piece);
+    first_piece = false;
   }
 }
 

@@ -357,8 +357,10 @@ inline void acc_mfma(AB a, AB b) {
   c = shim::mfma_32x32x16_bf16(a, b, c, 0, 0, 0);
   for (int r = 0; r < 16; ++r) shim::acc_file[16 * DT + r] = c[r];
 }
-template <int R>
-inline void acc_clear() { shim::acc_file[R] = 0.f; }
+template <int DT>
+inline void acc_clear_tile() {
+  for (int r = 0; r < 16; ++r) shim::acc_file[16 * DT + r] = 0.f;
+}
 template <int R>
 inline float acc_read() { return shim::acc_file[R]; }
 template <int I>
