@@ -147,13 +147,29 @@ int choose_splits(const amla_desc* d) {
     if (w > 256) w = 256;
     return (int)w;
   }
+  // Equal shares: the split factor that a small cost model likes best, in units of one 64-key block of one
+  // workgroup.  A workgroup costs its share of the longest possible sequence plus a fixed part (prologue,
+  // epilogue; more when it writes FP32 partial rows); the workgroups run in rounds of one per compute unit; the
+  // combine kernel costs a little per split.  At least four blocks per share, at most 64 shares.  (Measured at
+  // batch 96, two tokens, 4096 keys: 281 us unsplit, 320 us in two shares, 343 us in four -- 192 workgroups
+  // on 256 compute units are better left alone than cut into one and a half rounds.)
   const long long base = (long long)d->batch * tiles;       // workgroups without splitting
   if (base >= cus) return 1;
-  long long ns = (cus + base - 1) / base;
-  const long long cap = d->max_blocks_per_seq / 4 > 0 ? d->max_blocks_per_seq / 4 : 1;   // >= 4 blocks per split
-  if (ns > cap) ns = cap;
-  if (ns > 64) ns = 64;
-  return (int)(ns < 1 ? 1 : ns);
+  const long long blocks = d->max_blocks_per_seq > 0 ? d->max_blocks_per_seq : 1;
+  long long cap = blocks / 4 > 0 ? blocks / 4 : 1;
+  if (cap > 64) cap = 64;
+  long long best = 1, best_cost = 0;
+  for (long long ns = 1; ns <= cap; ++ns) {
+    const long long rounds = (base * ns + cus - 1) / cus;
+    const long long share = (blocks + ns - 1) / ns;
+    // tenths of a block: fixed part 4.0 (6.0 with partial rows), combine 1.0 + 0.6 per share
+    const long long cost = rounds * (10 * share + (ns > 1 ? 60 : 40)) + (ns > 1 ? 10 + 6 * ns : 0);
+    if (ns == 1 || cost < best_cost) {
+      best = ns;
+      best_cost = cost;
+    }
+  }
+  return (int)best;
 }
 
 // Everything a call enqueues, shared by amla_decode and its variants: the decode kernel of the selected
