@@ -39,8 +39,6 @@ typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
 #define AMLA_OPAQUE(x) asm volatile("" : "+v"(x))
 // one wave per SIMD: the whole 512-register file belongs to it
 #define AMLA_ONE_WAVE_PER_SIMD __attribute__((amdgpu_waves_per_eu(1, 1)))
-// two waves per SIMD, 256 registers each
-#define AMLA_TWO_WAVES_PER_SIMD __attribute__((amdgpu_waves_per_eu(2, 2)))
 // One 16-byte-per-lane direct-to-LDS load (lane l lands at lds + 16 l, lds wave-uniform) issued from inline
 // assembly, so that the compiler's wait-count pass does not know LDS is being written: it otherwise puts a
 // full vmcnt(0) in front of the first transposing LDS read that follows, and the second product could never

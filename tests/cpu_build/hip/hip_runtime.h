@@ -238,13 +238,8 @@ void launch(unsigned grid_x, unsigned grid_y, unsigned threads, F kernel) {
 // ---- the slice of the HIP runtime API the library's host code uses ---------------------------------
 typedef int hipError_t;
 typedef void* hipStream_t;
-typedef void* hipModule_t;
-typedef void* hipFunction_t;
 enum { hipSuccess = 0, hipErrorNotSupported = 801 };
 enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
-#define HIP_LAUNCH_PARAM_BUFFER_POINTER ((void*)1)
-#define HIP_LAUNCH_PARAM_BUFFER_SIZE ((void*)2)
-#define HIP_LAUNCH_PARAM_END ((void*)3)
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
@@ -256,44 +251,6 @@ inline hipError_t hipDeviceGetAttribute(int*, int, int) { return hipErrorNotSupp
 #define HIP_SYMBOL(x) (&(x))
 inline hipError_t hipGetSymbolAddress(void** ptr, const void* symbol) {
   *ptr = const_cast<void*>(symbol);
-  return hipSuccess;
-}
-// Code objects cannot run on the CPU.  By default loading one fails (the hand-scheduled kernels are then
-// unavailable in this build).  With the environment variable AMLA_SHIM_RECORD naming a file, loading
-// succeeds and every launch of a code-object kernel is appended to that file instead of run: the kernel's
-// name, grid, block and argument block, so that a test can check what the host code would hand to the
-// kernel (and run the kernel on the assembly emulator with exactly those arguments).
-namespace shim {
-inline std::vector<std::string>& module_names() {
-  static std::vector<std::string> names;
-  return names;
-}
-}  // namespace shim
-inline hipError_t hipModuleLoadData(hipModule_t* m, const void*) {
-  if (std::getenv("AMLA_SHIM_RECORD") == nullptr) return hipErrorNotSupported;
-  *m = reinterpret_cast<hipModule_t>(1);
-  return hipSuccess;
-}
-inline hipError_t hipModuleGetFunction(hipFunction_t* f, hipModule_t, const char* name) {
-  shim::module_names().push_back(name);
-  *f = reinterpret_cast<hipFunction_t>(shim::module_names().size());     // 1-based index into the names
-  return hipSuccess;
-}
-inline hipError_t hipModuleLaunchKernel(hipFunction_t f, unsigned gx, unsigned gy, unsigned gz, unsigned bx, unsigned by,
-                                        unsigned bz, unsigned, hipStream_t, void**, void** extra) {
-  const char* path = std::getenv("AMLA_SHIM_RECORD");
-  if (path == nullptr || extra == nullptr || extra[0] != HIP_LAUNCH_PARAM_BUFFER_POINTER ||
-      extra[2] != HIP_LAUNCH_PARAM_BUFFER_SIZE)
-    return hipErrorNotSupported;
-  const size_t bytes = *static_cast<const size_t*>(extra[3]);
-  FILE* out = std::fopen(path, "ab");
-  if (out == nullptr) return hipErrorNotSupported;
-  const std::string& name = shim::module_names()[reinterpret_cast<size_t>(f) - 1];
-  const uint32_t head[8] = {(uint32_t)name.size(), gx, gy, gz, bx, by, bz, (uint32_t)bytes};
-  std::fwrite(head, 4, 8, out);
-  std::fwrite(name.data(), 1, name.size(), out);
-  std::fwrite(extra[1], 1, bytes, out);
-  std::fclose(out);
   return hipSuccess;
 }
 #define hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, ...)                              \
@@ -337,7 +294,6 @@ inline float __uint_as_float(unsigned u) { return __builtin_bit_cast(float, u); 
 #define AMLA_OPAQUE(x) ((void)(x))
 #define AMLA_PIN(x) ((void)(x))
 #define AMLA_ONE_WAVE_PER_SIMD
-#define AMLA_TWO_WAVES_PER_SIMD
 #define AMLA_UNIFORM_LOAD_I32(p, i) ((p)[i])
 #define AMLA_ARRIVED(x) ((void)(x))
 #define AMLA_HIDDEN_LDS_LOAD(gptr, lds) shim::global_load_lds((gptr), (lds), 16, 0, 0)
