@@ -303,6 +303,41 @@ def test_device_exponent_add(env):
         assert np.array_equal(got.view(np.int32), orc.exponent_add_guarded(x, d).view(np.int32)), d
 
 
+def test_random_shapes_lengths_and_decompositions(env):
+    """A seeded sweep over what the fixed cases do not enumerate: 40 draws of batch, query tokens, heads, ragged
+    lengths (empty sequences included), logit width, rescale variant, split count, balanced decomposition and
+    causal mask, each against the oracle.  Rows with wide logits are peaked; they take the bound derived for
+    peaked rows (half a BF16 step of the output + 6e-3: an FP32 emulation of Algorithm 1 itself reaches 1.5e-2
+    on such rows), the others the plain one."""
+    torch, orc, amla, wl = env
+    rng = np.random.default_rng(20250925)
+    for it in range(40):
+        batch, s_q = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+        heads = int(rng.choice([16, 40, 64, 80, 128]))
+        lens = [int(x) for x in rng.integers(0, 3000, batch)]
+        if max(lens) == 0:
+            lens[0] = 77
+        sigma = float(rng.choice([1.0, 2.0, 4.0, 6.0]))
+        variant, ns = int(rng.integers(0, 3)), int(rng.integers(0, 6))
+        balanced = bool(rng.integers(0, 2))
+        causal = balanced and bool(rng.integers(0, 2))
+        flags = (amla.AMLA_FLAG_BALANCED if balanced else 0) | (amla.AMLA_FLAG_CAUSAL if causal else 0)
+        case = wl.make_case(f"sweep{it}", 5000 + it, batch=batch, s_q=s_q, heads=heads, seqlens=lens, q_sigma=sigma,
+                            spare_frac=0.25)
+        what = f"sweep {it}: batch {batch} s_q {s_q} heads {heads} lens {lens} sigma {sigma} variant {variant} flags {flags} splits {ns}"
+        print(what, flush=True)
+        out, lse = run_gpu(torch, amla, case, to_dev(torch, case), variant=variant, flags=flags, num_splits=ns)
+        want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens, case.softmax_scale,
+                                    causal=causal)
+        bound = out_tolerance(want)
+        if sigma > 2.0:
+            bound = np.maximum(bound, np.abs(want) * 2.0 ** -8 + 6e-3)
+        fin = np.isfinite(want_lse)
+        assert np.array_equal(lse[~fin], want_lse[~fin]), what
+        assert np.all(np.abs(out - want) <= bound), (what, float(np.abs(out - want).max()))
+        assert not fin.any() or np.abs(lse[fin] - want_lse[fin]).max() <= LSE_TOL, what
+
+
 # ----------------------------------------------------------------------------------------
 # The measured configurations at full size, every row against the oracle
 # ----------------------------------------------------------------------------------------
