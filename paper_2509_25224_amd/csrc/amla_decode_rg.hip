@@ -59,13 +59,21 @@ constexpr int kRgLdsBytes = 2 * kRgTileBytes;         // double buffer, 155648 o
 // One 16-byte-per-lane direct-to-LDS load from scalar base + per-lane 32-bit offset (lane l lands at lds + 16 l,
 // lds wave-uniform), issued from inline assembly like AMLA_HIDDEN_LDS_LOAD and for the same reason.
 #ifndef AMLA_TARGET_HOOKS
-#define AMLA_HIDDEN_LDS_LOAD_AT(base, off, lds)                                                              \
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2"                              \
-               :                                                                                             \
-               : "v"(off), "s"(__builtin_amdgcn_readfirstlane((unsigned)(__UINTPTR_TYPE__)(lds))), "s"(base) \
-               : "memory", "m0")
+// Three instructions: the LDS address is lds (wave-uniform, in an SGPR) plus a compile-time constant, added
+// straight into M0; the global address is base (SGPR pair) + off (per lane) + a compile-time constant, added by the
+// vector instruction that also fills the wait state between the M0 write and the load.
+#define AMLA_HIDDEN_LDS_LOAD_AT(base, off, off_const, lds, lds_const)                                         \
+  do {                                                                                                       \
+    unsigned amla_voff_;                                                                                     \
+    asm volatile("s_add_u32 m0, %2, %4\n\tv_add_u32 %0, %5, %1\n\tglobal_load_lds_dwordx4 %0, %3"           \
+                 : "=&v"(amla_voff_)                                                                         \
+                 : "v"(off), "s"(__builtin_amdgcn_readfirstlane((unsigned)(__UINTPTR_TYPE__)(lds))),         \
+                   "s"(base), "n"(lds_const), "n"(off_const)                                                 \
+                 : "memory", "m0", "scc");                                                                   \
+  } while (0)
 #else
-#define AMLA_HIDDEN_LDS_LOAD_AT(base, off, lds) AMLA_HIDDEN_LDS_LOAD((base) + (off), (lds))
+#define AMLA_HIDDEN_LDS_LOAD_AT(base, off, off_const, lds, lds_const) \
+  AMLA_HIDDEN_LDS_LOAD((base) + (off) + (off_const), (lds) + (lds_const))
 #endif
 
 // Per-lane constants of the tile loads.  Everything wave-uniform in a load's global address goes into its scalar
@@ -92,11 +100,11 @@ template <int N>
 __device__ __forceinline__ void issue_tile_load(const uint8_t* block_base, LDS_PTR(uint8_t) buf, const int wave,
                                                 const TileLoadLane& t) {
   if constexpr (N < kRgLoadsA) {
-    const int i = wave + 4 * N;
-    AMLA_HIDDEN_LDS_LOAD_AT(block_base + i * kRowBytes, t.c16[N & 3], buf + i * kRgRowA);
+    AMLA_HIDDEN_LDS_LOAD_AT(block_base + wave * kRowBytes, t.c16[N & 3], 4 * N * kRowBytes, buf + wave * kRgRowA,
+                            4 * N * kRgRowA);
   } else {
-    const int m = wave + 4 * (N - kRgLoadsA);
-    AMLA_HIDDEN_LDS_LOAD_AT(block_base + m * 8 * kRowBytes, t.off_b, buf + kRgRegionA + m * 1024);
+    AMLA_HIDDEN_LDS_LOAD_AT(block_base + wave * 8 * kRowBytes, t.off_b, 4 * (N - kRgLoadsA) * 8 * kRowBytes,
+                            buf + wave * 1024, kRgRegionA + 4 * (N - kRgLoadsA) * 1024);
   }
 }
 constexpr int kRgLoadsPerWave = kRgLoadsA + kRgLoadsB;   // 18

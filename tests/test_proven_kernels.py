@@ -115,7 +115,7 @@ def _check_loads_are_not_serialised(bodies, pattern, expect):
         if not re.search(pattern, name):
             continue
         loop = _steady_loop(body)
-        issue = [i for i, ln in enumerate(loop) if ln.startswith("s_mov_b32 m0")]
+        issue = [i for i, ln in enumerate(loop) if ln.startswith("s_mov_b32 m0") or ln.startswith("s_add_u32 m0")]
         assert issue, name                                   # the loads are issued inside the loop
         after = loop[issue[0]:]                              # from the first issue point to the closing branch
         assert not [ln for ln in after if ln.startswith("scratch_load")], (name, "reload behind the tile loads")
