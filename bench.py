@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE runs scaled by a copy kernel of known size (profiles/amla_decode_rg_kernel_mtp_b128.md); null for
 # any other kernel or workload
 MEASURED_TRAFFIC = {
-    # FETCH_SIZE 314065 KiB x 2.000 + WRITE_SIZE 34432 KiB x 1.000 (factors: profiles/copy_probe_512mib.md)
-    ("amla_decode_rg_kernel", "add", "mtp_b128", 1): {"read": 643.2e6, "written": 35.3e6},
-    ("amla_decode_rg_kernel", "mul", "mtp_b128", 1): {"read": 643.1e6, "written": 35.3e6},
+    # FETCH_SIZE 313918 KiB x 2.000 + WRITE_SIZE 33408 KiB x 1.000 (factors: profiles/copy_probe_512mib.md)
+    ("amla_decode_rg_kernel", "add", "mtp_b128", 1): {"read": 642.9e6, "written": 34.2e6},
+    ("amla_decode_rg_kernel", "mul", "mtp_b128", 1): {"read": 642.8e6, "written": 34.2e6},
 }
 
 
