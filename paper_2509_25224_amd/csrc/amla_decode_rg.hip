@@ -178,21 +178,59 @@ __device__ __forceinline__ float acc_read() {
   return x;
 }
 // The rescale of register I of all 16 tiles (the two query rows that own it), one statement: FP32 multiply, or
-// Lemma 3.1 with its guard as in exponent_add() (saturating INT32 add, then max with the sign bit).
-#define AMLA_ACC_EACH_TILE(M) M(0) M(16) M(32) M(48) M(64) M(80) M(96) M(112) M(128) M(144) M(160) M(176) M(192) M(208) M(224) M(240)
-#define AMLA_ACC_SCALE_ONE(off) "v_accvgpr_read_b32 %0, a[%2+" #off "]\n\tv_mul_f32 %0, %0, %1\n\tv_accvgpr_write_b32 a[%2+" #off "], %0\n\t"
-#define AMLA_ACC_ADD_ONE(off)                                                                              \
-  "v_accvgpr_read_b32 %0, a[%3+" #off "]\n\tv_and_b32 %1, 0x80000000, %0\n\tv_add_i32 %0, %0, %2 clamp\n\t" \
-  "v_max_i32 %0, %0, %1\n\tv_accvgpr_write_b32 a[%3+" #off "], %0\n\t"
+// Lemma 3.1 with a guard.  Two forms of the guard:
+//   * any n23 (ADD_COMP: the shift may carry a mantissa term of either sign): as in exponent_add(), saturating
+//     INT32 add, then max with the sign bit;
+//   * n23 <= 0 (ADD: the reference only rises): saturating INT32 add, then the UNSIGNED minimum with x itself.
+//     Inside the lemma's range the sum is below x as an unsigned number for either sign and is kept.  A negative
+//     x whose exponent would drop below zero saturates to 0x80000000 = -0.0, which is below x too; a positive
+//     one wraps to a negative integer, above x as an unsigned number, and x stays as it is -- an element below
+//     2^(|delta| - 127) <= 2^-97 (+0.0 among them) is left unscaled instead of flushed, the same to any tolerance,
+//     and the guard is one instruction instead of two.
+// Four tiles travel together through the statement, each in registers of its own, so that an instruction's
+// operands were written four instructions earlier: one dependent chain per tile would run at the VALU's
+// result latency instead of its issue rate.
+#define AMLA_ACC_EACH_FOUR(M) M(0, 16, 32, 48) M(64, 80, 96, 112) M(128, 144, 160, 176) M(192, 208, 224, 240)
+#define AMLA_ACC_RD(r, off) "v_accvgpr_read_b32 " r ", a[%[i]+" #off "]\n\t"
+#define AMLA_ACC_WR(r, off) "v_accvgpr_write_b32 a[%[i]+" #off "], " r "\n\t"
+#define AMLA_ACC_RD4(o0, o1, o2, o3) AMLA_ACC_RD("%[x0]", o0) AMLA_ACC_RD("%[x1]", o1) AMLA_ACC_RD("%[x2]", o2) AMLA_ACC_RD("%[x3]", o3)
+#define AMLA_ACC_SCALE_FOUR(o0, o1, o2, o3)                                                                  \
+  AMLA_ACC_RD4(o0, o1, o2, o3)                                                                               \
+  "v_mul_f32 %[x0], %[x0], %[f]\n\tv_mul_f32 %[x1], %[x1], %[f]\n\tv_mul_f32 %[x2], %[x2], %[f]\n\tv_mul_f32 %[x3], %[x3], %[f]\n\t" \
+  AMLA_ACC_WR("%[x0]", o0) AMLA_ACC_WR("%[x1]", o1) AMLA_ACC_WR("%[x2]", o2) AMLA_ACC_WR("%[x3]", o3)
+#define AMLA_ACC_ADD_FOUR(o0, o1, o2, o3)                                                                    \
+  AMLA_ACC_RD4(o0, o1, o2, o3)                                                                               \
+  "v_and_b32 %[y0], 0x80000000, %[x0]\n\tv_and_b32 %[y1], 0x80000000, %[x1]\n\t"                             \
+  "v_and_b32 %[y2], 0x80000000, %[x2]\n\tv_and_b32 %[y3], 0x80000000, %[x3]\n\t"                             \
+  "v_add_i32 %[x0], %[x0], %[f] clamp\n\tv_add_i32 %[x1], %[x1], %[f] clamp\n\t"                             \
+  "v_add_i32 %[x2], %[x2], %[f] clamp\n\tv_add_i32 %[x3], %[x3], %[f] clamp\n\t"                             \
+  "v_max_i32 %[x0], %[x0], %[y0]\n\tv_max_i32 %[x1], %[x1], %[y1]\n\t"                                       \
+  "v_max_i32 %[x2], %[x2], %[y2]\n\tv_max_i32 %[x3], %[x3], %[y3]\n\t"                                       \
+  AMLA_ACC_WR("%[x0]", o0) AMLA_ACC_WR("%[x1]", o1) AMLA_ACC_WR("%[x2]", o2) AMLA_ACC_WR("%[x3]", o3)
+#define AMLA_ACC_LOWER_FOUR(o0, o1, o2, o3)                                                                  \
+  AMLA_ACC_RD4(o0, o1, o2, o3)                                                                               \
+  "v_add_i32 %[y0], %[x0], %[f] clamp\n\tv_add_i32 %[y1], %[x1], %[f] clamp\n\t"                             \
+  "v_add_i32 %[y2], %[x2], %[f] clamp\n\tv_add_i32 %[y3], %[x3], %[f] clamp\n\t"                             \
+  "v_min_u32 %[y0], %[y0], %[x0]\n\tv_min_u32 %[y1], %[y1], %[x1]\n\t"                                       \
+  "v_min_u32 %[y2], %[y2], %[x2]\n\tv_min_u32 %[y3], %[y3], %[x3]\n\t"                                       \
+  AMLA_ACC_WR("%[y0]", o0) AMLA_ACC_WR("%[y1]", o1) AMLA_ACC_WR("%[y2]", o2) AMLA_ACC_WR("%[y3]", o3)
+#define AMLA_ACC_X4 [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2), [x3] "=&v"(x3)
+#define AMLA_ACC_Y4 [y0] "=&v"(y0), [y1] "=&v"(y1), [y2] "=&v"(y2), [y3] "=&v"(y3)
 template <int I>
 __device__ __forceinline__ void acc_scale_rows(const float factor) {
-  int t;
-  asm volatile(AMLA_ACC_EACH_TILE(AMLA_ACC_SCALE_ONE) : "=&v"(t) : "v"(factor), "n"(I) : AMLA_ACC_ALL);
+  int x0, x1, x2, x3;
+  asm volatile(AMLA_ACC_EACH_FOUR(AMLA_ACC_SCALE_FOUR) : AMLA_ACC_X4 : [f] "v"(factor), [i] "n"(I) : AMLA_ACC_ALL);
 }
 template <int I>
 __device__ __forceinline__ void acc_exponent_add_rows(const int n23) {
-  int t, u;
-  asm volatile(AMLA_ACC_EACH_TILE(AMLA_ACC_ADD_ONE) : "=&v"(t), "=&v"(u) : "v"(n23), "n"(I) : AMLA_ACC_ALL);
+  int x0, x1, x2, x3, y0, y1, y2, y3;
+  asm volatile(AMLA_ACC_EACH_FOUR(AMLA_ACC_ADD_FOUR) : AMLA_ACC_X4, AMLA_ACC_Y4 : [f] "v"(n23), [i] "n"(I) : AMLA_ACC_ALL);
+}
+// the same for n23 <= 0
+template <int I>
+__device__ __forceinline__ void acc_exponent_lower_rows(const int n23) {
+  int x0, x1, x2, x3, y0, y1, y2, y3;
+  asm volatile(AMLA_ACC_EACH_FOUR(AMLA_ACC_LOWER_FOUR) : AMLA_ACC_X4, AMLA_ACC_Y4 : [f] "v"(n23), [i] "n"(I) : AMLA_ACC_ALL);
 }
 __device__ __forceinline__ void acc_idle(void) { asm volatile("s_nop 7"); }
 // x stays where it is in the instruction stream, and nothing of the compiler's lives in an AccVGPR across this point
@@ -532,6 +570,8 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
                 const int mine = h ? hi : lo;
                 if (VARIANT == AMLA_RESCALE_MUL)
                   acc_scale_rows<4 * g + e>(__int_as_float(mine));
+                else if (VARIANT == AMLA_RESCALE_ADD)
+                  acc_exponent_lower_rows<4 * g + e>(mine);
                 else
                   acc_exponent_add_rows<4 * g + e>(mine);
               }

@@ -334,6 +334,17 @@ inline void acc_exponent_add_rows(int n23) {
     shim::acc_file[16 * dt + I] = __builtin_bit_cast(float, std::max((int)r, guard));
   }
 }
+template <int I>
+inline void acc_exponent_lower_rows(int n23) {
+  // n23 <= 0: saturating INT32 add, then the unsigned minimum with the operand (the instruction pair of the GPU build)
+  for (int dt = 0; dt < 16; ++dt) {
+    const int i = __builtin_bit_cast(int, shim::acc_file[16 * dt + I]);
+    long long r = (long long)i + n23;
+    r = r > 2147483647ll ? 2147483647ll : (r < -2147483648ll ? -2147483648ll : r);
+    const unsigned u = std::min((unsigned)(int)r, (unsigned)i);
+    shim::acc_file[16 * dt + I] = __builtin_bit_cast(float, u);
+  }
+}
 inline void wait_tile_loads_but(int n) { shim::wait_tile_loads_but(n); }
 // v_dot2_f32_bf16 with a pair of ones: the two BF16 values of w added to acc in FP32
 inline float bf16_pair_sum(unsigned w, float acc) {
