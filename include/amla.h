@@ -18,8 +18,9 @@
  *   AMLA_RESCALE_ADD  O <- AS_FP32(AS_INT32(O) + (n_new - n_old) * 2^23)
  *                     with the running reference quantised to an integer power of two
  *                     (Eq. (4), Lemma 3.1, Algorithm 2's n_i, N and AtomicAdd<INT32>), the INT32 add
- *                     guarded so that an exponent that would drop to or below zero yields
- *                     a signed zero instead of a wrapped bit pattern.
+ *                     guarded so that an exponent that would drop to or below zero never yields
+ *                     a wrapped bit pattern: such an element (magnitude below 2^-97) becomes a
+ *                     signed zero or keeps its value, whichever the kernel's form of the guard gives.
  *   AMLA_RESCALE_ADD_COMP  the ADD variant with the BF16 scale compensation of Algorithm 2
  *                     (S32, S16, c_i, eps) and Appendix A: the weights are 2^(t - m) * S16 with S16 the
  *                     BF16 rounding of S32 = 2^(m - rint(m)), so the largest weight of a row is
