@@ -381,8 +381,10 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     // results to its place in the instruction stream (pure arithmetic would otherwise sink to its first use,
     // behind the MFMAs it is meant to run under).
     float m_new = 0.f, m_use = 0.f, p_odd = 0.f;
-    auto softmax_chunk = [&](auto sbc, auto cc, f32x16& T) {
+    auto softmax_chunk = [&](auto sbc, auto cc, f32x16& T, auto&& mid) {
       constexpr int SB = sbc.value, C = cc.value;
+      constexpr bool pins_first = C == 0 || (C >= 5 && C < 5 + 24 && (C - 5) % 3 < 2);
+      if constexpr (!pins_first) mid();
       if constexpr (C == 0) {
         if (masked_block) {
           // with the causal mask a row's own limit lies causal_shift keys before the sequence's end
@@ -393,6 +395,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
           }
         }
         AMLA_OPAQUE(T);
+        mid();
         mxp = fmaxf(fmaxf(T[0], T[1]), T[2]);
         mxp = fmaxf(fmaxf(mxp, T[3]), T[4]);
         mxp = fmaxf(fmaxf(mxp, T[5]), T[6]);
@@ -474,6 +477,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
         if constexpr (part < 2) {
           float t = T[2 * q + part];
           AMLA_OPAQUE(t);
+          mid();
           const float pv = fast_exp2(__builtin_fmaf(t, p.scale_log2e, -ref));
           if constexpr (part == 0) {
             p_even = pv;
@@ -505,34 +509,39 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     // the same work in 47 smaller chunks (a pair of weights in five: the two arguments, either exponential, the
     // sums, the BF16 pair), for the steps of the second product, which have less issue time to spare
     float t_even = 0.f, t_odd = 0.f;
-    auto softmax_fine = [&](auto sbc, auto cc, f32x16& T) {
+    auto softmax_fine = [&](auto sbc, auto cc, f32x16& T, auto&& mid) {
       constexpr int SB = sbc.value, C = cc.value;
       if constexpr (C < 5) {
-        softmax_chunk(sbc, cc, T);
+        softmax_chunk(sbc, cc, T, mid);
       } else if constexpr (C < 45) {
         constexpr int q = (C - 5) / 5, part = (C - 5) % 5;
         if constexpr (part == 0) {
           float a = T[2 * q], b = T[2 * q + 1];
           AMLA_OPAQUE(a);
           AMLA_OPAQUE(b);
+          mid();
           t_even = __builtin_fmaf(a, p.scale_log2e, -ref);
           t_odd = __builtin_fmaf(b, p.scale_log2e, -ref);
           AMLA_OPAQUE(t_even);
           AMLA_OPAQUE(t_odd);
         } else if constexpr (part == 1) {
           AMLA_OPAQUE(t_even);
+          mid();
           p_even = fast_exp2(t_even);
           AMLA_OPAQUE(p_even);
         } else if constexpr (part == 2) {
           AMLA_OPAQUE(t_odd);
+          mid();
           p_odd = fast_exp2(t_odd);
           AMLA_OPAQUE(p_odd);
         } else if constexpr (part == 3) {
           AMLA_OPAQUE(p_even);
+          mid();
           psum += p_even + p_odd;
           AMLA_OPAQUE(psum);
         } else {
           AMLA_OPAQUE(p_odd);
+          mid();
           unsigned w = pack_bf16(p_even, p_odd);
           bsum = bf16_pair_sum(w, bsum);
           AMLA_OPAQUE(w);
@@ -540,7 +549,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
           pk[SB * 8 + q] = w;
         }
       } else {
-        softmax_chunk(sbc, std::integral_constant<int, C - 45 + 29>{}, T);
+        softmax_chunk(sbc, std::integral_constant<int, C - 45 + 29>{}, T, mid);
       }
     };
     constexpr int kFineChunks = 47;
@@ -607,8 +616,15 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
       constexpr int ks = ksc.value;
       s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(kSteps + ks) % kKAhead], qf[ks], s1, 0, 0, 0);
       AMLA_PIN(s1);
-      if constexpr (ks + kKAhead < kSteps) ka[(kSteps + ks) % kKAhead] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 1);
-      if constexpr (ks < kSoftmaxChunks) softmax_chunk(std::integral_constant<int, 0>{}, ksc, s0);
+      // (the operand read sits between a chunk's input pins and its arithmetic: an instruction that reads what an
+      // assembly statement has just defined is given a wait state by the compiler)
+      auto read_next = [&]() {
+        if constexpr (ks + kKAhead < kSteps) ka[(kSteps + ks) % kKAhead] = *(LDS_PTR(bf16x8))k_addr(ks + kKAhead, 1);
+      };
+      if constexpr (ks < kSoftmaxChunks)
+        softmax_chunk(std::integral_constant<int, 0>{}, ksc, s0, read_next);
+      else
+        read_next();
       __builtin_amdgcn_sched_barrier(0);
     });
 
@@ -624,12 +640,15 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- [C2] O[32 rows x 512] += P V, 16 keys x 32 columns per MFMA ----
-    auto pv_step = [&](auto nc) {
+    auto pv_mfma = [&](auto nc) {
       constexpr int n = nc.value, st = n / (kDv / 32), dt = n % (kDv / 32);
       const i32x4 pb = {(int)pk[4 * st], (int)pk[4 * st + 1], (int)pk[4 * st + 2], (int)pk[4 * st + 3]};
       const i32x2 lo2 = __builtin_bit_cast(i32x2, vr[n % kVAhead][0]), hi2 = __builtin_bit_cast(i32x2, vr[n % kVAhead][1]);
       const i32x4 vb = {lo2[0], lo2[1], hi2[0], hi2[1]};
       acc_mfma<dt>(__builtin_bit_cast(bf16x8, pb), __builtin_bit_cast(bf16x8, vb));
+    };
+    auto pv_reads = [&](auto nc) {
+      constexpr int n = nc.value;
       constexpr int nx = n + kVAhead;
       if constexpr (nx < 4 * (kDv / 32)) {
         constexpr int step = (nx / (kDv / 32)) * 16 * kRgRowA + (nx % (kDv / 32)) * 64;
@@ -640,8 +659,8 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     // ---- phase C: keys 0 .. 31 | [V1] of sub-block 1 ----
     // (one fine chunk a step: maximum, reference, and the weights of keys 32 .. 53)
     static_for<2 * (kDv / 32)>([&](auto nc) {
-      pv_step(nc);
-      softmax_fine(std::integral_constant<int, 1>{}, nc, s1);
+      pv_mfma(nc);
+      softmax_fine(std::integral_constant<int, 1>{}, nc, s1, [&]() { pv_reads(nc); });
       __builtin_amdgcn_sched_barrier(0);
     });
     rescale(true, true);
@@ -649,8 +668,12 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     // ---- phase D: keys 32 .. 63 | the remaining weights (keys 54 .. 63, needed from step 16 on) and the row sums ----
     static_for<2 * (kDv / 32)>([&](auto nc) {
       constexpr int n = nc.value;
-      pv_step(std::integral_constant<int, 2 * (kDv / 32) + n>{});
-      if constexpr (32 + n < kFineChunks) softmax_fine(std::integral_constant<int, 1>{}, std::integral_constant<int, 32 + n>{}, s1);
+      constexpr auto step = std::integral_constant<int, 2 * (kDv / 32) + n>{};
+      pv_mfma(step);
+      if constexpr (32 + n < kFineChunks)
+        softmax_fine(std::integral_constant<int, 1>{}, std::integral_constant<int, 32 + n>{}, s1, [&]() { pv_reads(step); });
+      else
+        pv_reads(step);
       __builtin_amdgcn_sched_barrier(0);
     });
   }
