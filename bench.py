@@ -35,8 +35,8 @@ HBM_PEAK_GBS = 8000.0
 # any other kernel or workload
 MEASURED_TRAFFIC = {
     # FETCH_SIZE 313918 KiB x 2.000 + WRITE_SIZE 33408 KiB x 1.000 (factors: profiles/copy_probe_512mib.md)
-    ("amla_decode_rg_kernel", "add", "mtp_b128", 1): {"read": 642.9e6, "written": 34.2e6},
-    ("amla_decode_rg_kernel", "mul", "mtp_b128", 1): {"read": 642.8e6, "written": 34.2e6},
+    ("amla_decode_rg_kernel", "add", "mtp_b128", 1): {"read": 643.7e6, "written": 35.0e6},
+    ("amla_decode_rg_kernel", "mul", "mtp_b128", 1): {"read": 643.6e6, "written": 35.0e6},
 }
 
 
