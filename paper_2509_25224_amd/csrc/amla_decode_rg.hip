@@ -260,7 +260,8 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
                                              const int wave, const int b, const int kv_len, const int j0,
                                              const int j1, const int tile, const bool to_final,
                                              const size_t part_row0, const int causal_shift, const int mask_span,
-                                             const bool first_piece) {
+                                             const bool first_piece, const bool have_entry = false,
+                                             const int entry = 0) {
   const int l32 = lane & 31;
   const int h = lane >> 5;
   const int row = tile * kRowsPerWg + wave * 32 + l32;   // this lane's query row within the sequence
@@ -281,8 +282,9 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
     return min(max(__builtin_amdgcn_readfirstlane(AMLA_UNIFORM_LOAD_I32(tab, j)), 0), p.num_blocks - 1);
   };
   // The block-table entry of the first block is asked for first (a memory round trip of its own), then the
-  // query rows; the first tile's loads follow as soon as the entry is there.
-  const int first_entry = j0 < j1 ? AMLA_UNIFORM_LOAD_I32(tab, j0) : 0;
+  // query rows; the first tile's loads follow as soon as the entry is there.  (have_entry: the caller already
+  // holds table entry j0.)
+  const int first_entry = have_entry ? entry : j0 < j1 ? AMLA_UNIFORM_LOAD_I32(tab, j0) : 0;
   __builtin_amdgcn_sched_barrier(0);
 
   // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
@@ -735,12 +737,16 @@ void amla_decode_rg_kernel(const DecodeParams p) {
   const int b = stream / p.n_splits;
   const int split = stream - b * p.n_splits;
 
+  // A sequence's first share starts at block 0 whatever its length: its table entry is asked for together
+  // with the length instead of after it (one memory round trip less before the first tile can be requested).
+  const bool have_entry = split == 0;
+  const int entry = have_entry ? AMLA_UNIFORM_LOAD_I32(p.table + (size_t)b * p.max_blocks, 0) : 0;
   const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[b]), p.max_blocks, kBlock);
   const int nb = plan_blocks_of(kv_len, kBlock);
   const int j0 = (int)(((long long)split * nb) / p.n_splits);
   const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
   decode_piece<VARIANT, false>(p, smem, lane, wave, b, kv_len, j0, j1, tile, p.n_splits == 1,
-                               (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0, true);
+                               (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0, true, have_entry, entry);
 }
 
 // Balanced decomposition (ragged batches, causal mask among the s_q tokens, per-sequence query counts):
