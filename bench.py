@@ -48,6 +48,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="index into the measured configurations (0-4)")
     ap.add_argument("--variant", default="add",
                     help="the kernel that is timed: mul, add, add_comp (row-rescale kernels, the default family), "
+                         "mul_512, add_512 (the same with one iteration of the recurrence per 512 keys), "
                          "mul_t, add_t, add_comp_t, mul_lazy, add_lazy, add_ldexp, add_ldexp_lazy "
                          "(transposed-accumulator kernels)")
     ap.add_argument("--balanced", action="store_true",
@@ -67,8 +68,9 @@ def parse():
 
 
 def variants(amla):
-    T, L = amla.AMLA_FLAG_TRANSPOSED_ACC, amla.AMLA_FLAG_LAZY_RESCALE
+    T, L, I = amla.AMLA_FLAG_TRANSPOSED_ACC, amla.AMLA_FLAG_LAZY_RESCALE, amla.AMLA_FLAG_ITERATION_512
     return {"mul": (amla.AMLA_RESCALE_MUL, 0), "add": (amla.AMLA_RESCALE_ADD, 0), "add_comp": (amla.AMLA_RESCALE_ADD_COMP, 0),
+            "mul_512": (amla.AMLA_RESCALE_MUL, I), "add_512": (amla.AMLA_RESCALE_ADD, I),
             "mul_t": (amla.AMLA_RESCALE_MUL, T), "add_t": (amla.AMLA_RESCALE_ADD, T),
             "add_comp_t": (amla.AMLA_RESCALE_ADD_COMP, T),
             "mul_lazy": (amla.AMLA_RESCALE_MUL, L), "add_lazy": (amla.AMLA_RESCALE_ADD, L),
@@ -76,7 +78,7 @@ def variants(amla):
 
 
 def kernel_name(name, balanced):
-    row = name in ("mul", "add", "add_comp")
+    row = name in ("mul", "add", "add_comp", "mul_512", "add_512")
     return ("amla_decode_rg" if row else "amla_decode") + ("_balanced_kernel" if balanced else "_kernel")
 
 
@@ -310,7 +312,7 @@ def main():
             med = {k: median(v) for k, v in ab.items() if v}
             # the paper's comparison, strict ADD against strict MUL on the same kernel: alternate launches
             pairs = {}
-            for a, b in (("add", "mul"), ("add_t", "mul_t")):
+            for a, b in (("add", "mul"), ("add_512", "mul_512"), ("add_t", "mul_t")):
                 ta, tb = [], []
                 for _ in range(4):
                     ta.extend(prob.time(a, 10, 2, args.balanced, args.splits)[1])
@@ -319,7 +321,9 @@ def main():
                 pairs[f"{a}_ms_median_of_{len(ta)}"] = median(ta)
                 pairs[f"{b}_ms_median_of_{len(tb)}"] = median(tb)
             result["rescale"] = {"ms_median": med, "tflops": {k: flops / (v * 1e-3) / 1e12 for k, v in med.items()}, **pairs,
-                                 "note": "same binary; mul / add / add_comp = row-rescale kernels (rescale per moved row); _t = "
+                                 "note": "same binary; mul / add / add_comp = row-rescale kernels (rescale per moved row, reference moves "
+                                         "once per 64-key cache block); _512 = the same with the reference moving once per 512 keys, "
+                                         "the KV block of Section 4.2; _t = "
                                          "transposed-accumulator kernels (rescale of all 256 registers whenever a row of the "
                                          "wave moved); lazy = reference moves only past 2^8; add_ldexp = the exponent add done "
                                          "by v_ldexp_f32; strict = reference moves with every new row max"}
@@ -349,7 +353,7 @@ def main():
                 ab_ = acc.algorithmic_bytes(c.heads, c.s_q, c.batch, c.total_kv)
                 entry = {"workload": f"batch {c.batch}, s_q {c.s_q}, {c.heads} heads, sum kv_len {c.total_kv}"
                                      + (", two pool copies read alternately" if idx == 1 else "")}
-                legs = [("add", False), ("mul", False)] + ([("add", True), ("mul", True)] if idx == 3 else [])
+                legs = [("add", False), ("mul", False), ("add_512", False)] + ([("add", True), ("mul", True)] if idx == 3 else [])
                 times = {}
                 # the first launches on a fresh problem run slow whatever the variant (clocks and address
                 # translation settle): one untimed pass over every leg, then interleaved passes in alternating order

@@ -96,6 +96,14 @@ enum {
                                    out = 0, lse = -inf.  Without the flag every token attends to all
                                    kv_len keys.  Runs in the balanced kernels (implies
                                    AMLA_FLAG_BALANCED). */
+  AMLA_FLAG_ITERATION_512 = 32, /* one iteration of the recurrence = eight 64-key cache blocks, the 512-key
+                                   KV block of Section 4.2: the reference (and with it the accumulator
+                                   rescale) moves once per 512 keys of a workgroup's range instead of once
+                                   per cache block.  The eight blocks are worked one after the other under
+                                   the reference the iteration started with (their weights may exceed 1;
+                                   a row whose maximum leaves that reference by more than 2^8 moves it at
+                                   once).  Same result up to rounding.  Default (row-rescale) kernels with
+                                   AMLA_RESCALE_MUL or AMLA_RESCALE_ADD only. */
   AMLA_FLAG_TRANSPOSED_ACC = 128 /* run the kernels that compute both products transposed (S^T = K Q^T,
                                    O^T = V^T P^T): the accumulator's rescale factor is then a per-lane
                                    scalar and a rescale passes over all 256 accumulator registers of the

@@ -24,6 +24,7 @@ AMLA_FLAG_NO_SKIP = 1
 AMLA_FLAG_LAZY_RESCALE = 2
 AMLA_FLAG_BALANCED = 8
 AMLA_FLAG_CAUSAL = 16
+AMLA_FLAG_ITERATION_512 = 32
 AMLA_FLAG_TRANSPOSED_ACC = 128
 
 EXPORTS = ("amla_decode", "amla_decode_static_workspace", "amla_static_workspace_limit", "amla_workspace_bytes", "amla_effective_splits", "amla_exponent_add",

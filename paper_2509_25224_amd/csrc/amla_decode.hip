@@ -121,7 +121,11 @@ bool desc_supported(const amla_desc* d) {
     return false;
   if (d->num_splits < 0 || d->num_splits > 256 || d->reserved != 0) return false;
   if ((d->flags & ~(AMLA_FLAG_NO_SKIP | AMLA_FLAG_LAZY_RESCALE | AMLA_FLAG_BALANCED | AMLA_FLAG_CAUSAL |
-                    AMLA_FLAG_TRANSPOSED_ACC)) != 0)
+                    AMLA_FLAG_ITERATION_512 | AMLA_FLAG_TRANSPOSED_ACC)) != 0)
+    return false;
+  // the 512-key iteration exists in the row-rescale kernels, for the variants whose reference may lag
+  if ((d->flags & AMLA_FLAG_ITERATION_512) &&
+      (uses_transposed(d) || (d->variant != AMLA_RESCALE_MUL && d->variant != AMLA_RESCALE_ADD)))
     return false;
   // ldexp rescale with the balanced decomposition does not exist (the compiler's AGPR-copy rewrite pass
   // crashes on that instantiation of the transposed-accumulator kernels)
@@ -211,7 +215,7 @@ int enqueue_decode(const void* q, const void* kv_cache, const int32_t* block_tab
   AmlaDecodeKernel kern = nullptr;
   int lds_bytes = kLdsBytes;
   if (!uses_transposed(desc)) {
-    kern = amla_row_rescale_kernel(desc->variant, balanced);
+    kern = amla_row_rescale_kernel(desc->variant, balanced, (desc->flags & AMLA_FLAG_ITERATION_512) != 0);
     lds_bytes = amla_row_rescale_lds_bytes();
   } else if (!balanced) {
     kern = desc->variant == AMLA_RESCALE_ADD_COMP ? amla_decode_kernel<AMLA_RESCALE_ADD_COMP, false>

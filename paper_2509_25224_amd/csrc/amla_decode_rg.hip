@@ -255,7 +255,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 // row part_row0 of the workspace.  causal_shift (per lane: keys between this lane's row limit and the
 // sequence's end; kNoKeys for the row of a padding token) and mask_span (wave-uniform: the piece's largest
 // shift) are 0 without a mask.
-template <int VARIANT, bool MASKED>
+template <int VARIANT, bool MASKED, bool ITER512>
 __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint8_t) smem, const int lane,
                                              const int wave, const int b, const int kv_len, const int j0,
                                              const int j1, const int tile, const bool to_final,
@@ -423,6 +423,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
         if (!MASKED) m_use = m_new;
         const bool first = MASKED ? ((j == j0 && SB == 0) || m_run == -INFINITY) : (j == j0 && SB == 0);
         float ref_new;
+        bool keep = false;   // wave-uniform; only ever true with ITER512
         alpha = 1.f;
         n23 = 0;
         if constexpr (SB == 0 && VARIANT != AMLA_RESCALE_ADD_COMP) {
@@ -441,6 +442,14 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
             return;
           }
         }
+        if constexpr (SB == 1 && ITER512) {
+          // AMLA_FLAG_ITERATION_512: the iteration of the recurrence is eight cache blocks (the KV block of
+          // Section 4.2), so the second sub-block of every block but the iteration's last keeps the reference in the
+          // same way -- here without a branch (the new reference is the old one, so the shift is 0 and the factor
+          // 2^0): measured cheaper in this phase.
+          const bool far = first || m_new - ref > 8.f;
+          keep = ((j - j0) & 7) != 7 && __builtin_amdgcn_ballot_w64(far) == 0;
+        }
         if (VARIANT == AMLA_RESCALE_ADD_COMP) {
           // Algorithm 2's compensation (S32, S16, c_i, eps, N) in base 2: S32 = 2^(m - mu) in [2^-1/2, 2^1/2], S16 its
           // BF16 rounding, weights 2^(t - m) S16 = 2^(t - (m - log2 S16)); the shift of the exponent field and the
@@ -458,10 +467,10 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
           mu_run = mu;
           c_run = c_new;
         } else if (VARIANT == AMLA_RESCALE_MUL) {
-          ref_new = m_use;
+          ref_new = ITER512 && keep ? ref : m_use;
           if (!first) alpha = fast_exp2(ref - ref_new);
         } else {
-          ref_new = __builtin_rintf(m_use);
+          ref_new = ITER512 && keep ? ref : __builtin_rintf(m_use);
           if (!first) n23 = max((int)(ref - ref_new), -30) * (1 << 23);
         }
         m_run = m_new;
@@ -717,7 +726,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
 }
 
 // Equal-share decomposition: workgroup = (sequence, split, 128-row tile).
-template <int VARIANT>
+template <int VARIANT, bool ITER512>
 __global__ __launch_bounds__(kThreads) AMLA_ONE_WAVE_PER_SIMD
 void amla_decode_rg_kernel(const DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
@@ -745,7 +754,7 @@ void amla_decode_rg_kernel(const DecodeParams p) {
   const int nb = plan_blocks_of(kv_len, kBlock);
   const int j0 = (int)(((long long)split * nb) / p.n_splits);
   const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
-  decode_piece<VARIANT, false>(p, smem, lane, wave, b, kv_len, j0, j1, tile, p.n_splits == 1,
+  decode_piece<VARIANT, false, ITER512>(p, smem, lane, wave, b, kv_len, j0, j1, tile, p.n_splits == 1,
                                (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0, true, have_entry, entry);
 }
 
@@ -755,7 +764,7 @@ void amla_decode_rg_kernel(const DecodeParams p) {
 // sequence) pair is a piece with its own softmax state.  A piece that covers its whole sequence writes the
 // final result, any other writes a partial row set into slot worker + sequence of the workspace, which
 // amla_combine_balanced_kernel merges.
-template <int VARIANT>
+template <int VARIANT, bool ITER512>
 __global__ __launch_bounds__(kThreads) AMLA_ONE_WAVE_PER_SIMD
 void amla_decode_rg_balanced_kernel(const DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
@@ -817,7 +826,7 @@ void amla_decode_rg_balanced_kernel(const DecodeParams p) {
     const int mask_span = q_len < p.s_q ? kNoKeys : p.causal_span;
     const int t_row = row / p.heads;
     const int causal_shift = t_row >= q_len ? kNoKeys : (p.causal_span != 0 ? q_len - 1 - t_row : 0);
-    decode_piece<VARIANT, true>(p, smem, lane, wave, piece.b, kv_len, piece.j0, piece.j1, tile, piece.full != 0,
+    decode_piece<VARIANT, true, ITER512>(p, smem, lane, wave, piece.b, kv_len, piece.j0, piece.j1, tile, piece.full != 0,
                                 ((size_t)stream + piece.b) * p.rows, causal_shift, mask_span, first_piece);
     first_piece = false;
   }
@@ -826,14 +835,22 @@ void amla_decode_rg_balanced_kernel(const DecodeParams p) {
 }  // namespace
 
 // The kernels of this file for a rescale variant (AMLA_RESCALE_MUL, _ADD or _ADD_COMP), for amla_decode to
-// launch with 256 threads and amla_row_rescale_lds_bytes() of dynamic LDS.
+// launch with 256 threads and amla_row_rescale_lds_bytes() of dynamic LDS; iteration_512 = the build whose
+// recurrence steps once per eight cache blocks (AMLA_FLAG_ITERATION_512).
 int amla_row_rescale_lds_bytes() { return kRgLdsBytes; }
-AmlaDecodeKernel amla_row_rescale_kernel(int variant, bool balanced) {
+AmlaDecodeKernel amla_row_rescale_kernel(int variant, bool balanced, bool iteration_512) {
+  if (iteration_512) {   // MUL and ADD only (amla_decode refuses the flag for the compensated variant)
+    if (balanced)
+      return variant == AMLA_RESCALE_ADD ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD, true>
+                                         : amla_decode_rg_balanced_kernel<AMLA_RESCALE_MUL, true>;
+    return variant == AMLA_RESCALE_ADD ? amla_decode_rg_kernel<AMLA_RESCALE_ADD, true>
+                                       : amla_decode_rg_kernel<AMLA_RESCALE_MUL, true>;
+  }
   if (balanced)
-    return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD_COMP>
-           : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD>
-                                            : amla_decode_rg_balanced_kernel<AMLA_RESCALE_MUL>;
-  return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_kernel<AMLA_RESCALE_ADD_COMP>
-         : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_kernel<AMLA_RESCALE_ADD>
-                                          : amla_decode_rg_kernel<AMLA_RESCALE_MUL>;
+    return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD_COMP, false>
+           : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_balanced_kernel<AMLA_RESCALE_ADD, false>
+                                            : amla_decode_rg_balanced_kernel<AMLA_RESCALE_MUL, false>;
+  return variant == AMLA_RESCALE_ADD_COMP ? amla_decode_rg_kernel<AMLA_RESCALE_ADD_COMP, false>
+         : variant == AMLA_RESCALE_ADD    ? amla_decode_rg_kernel<AMLA_RESCALE_ADD, false>
+                                          : amla_decode_rg_kernel<AMLA_RESCALE_MUL, false>;
 }

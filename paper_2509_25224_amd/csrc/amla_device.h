@@ -152,7 +152,7 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
 
 // Kernels defined in other translation units of the library, looked up by amla_decode.
 typedef void (*AmlaDecodeKernel)(const DecodeParams);
-AmlaDecodeKernel amla_row_rescale_kernel(int variant, bool balanced);   // amla_decode_rg.hip
+AmlaDecodeKernel amla_row_rescale_kernel(int variant, bool balanced, bool iteration_512);   // amla_decode_rg.hip
 int amla_row_rescale_lds_bytes();
 
 #endif  // AMLA_DEVICE_H_

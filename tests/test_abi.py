@@ -84,10 +84,20 @@ def test_argument_validation_error_codes(amla):
 
 
 def test_retired_flag_bits_are_rejected(amla):
-    for bit in (4, 32, 64, 256):
+    for bit in (4, 64, 256):
         d = amla.make_desc(2, 1, 16, 8, 4, flags=bit)
         assert _call(amla, d) == amla.AMLA_ERR_UNSUPPORTED
         assert amla.amla_effective_splits(d) == 0
+
+
+def test_iteration_512_exists_for_mul_and_add_of_the_default_family_only(amla):
+    it = amla.AMLA_FLAG_ITERATION_512
+    for variant in (amla.AMLA_RESCALE_ADD_COMP, amla.AMLA_RESCALE_ADD_LDEXP):
+        assert _call(amla, amla.make_desc(2, 1, 16, 8, 4, variant=variant, flags=it)) == amla.AMLA_ERR_UNSUPPORTED
+    for variant in (amla.AMLA_RESCALE_MUL, amla.AMLA_RESCALE_ADD):
+        t = amla.make_desc(2, 1, 16, 8, 4, variant=variant, flags=it | amla.AMLA_FLAG_TRANSPOSED_ACC)
+        assert _call(amla, t) == amla.AMLA_ERR_UNSUPPORTED
+        assert amla.amla_effective_splits(amla.make_desc(2, 1, 16, 8, 4, variant=variant, flags=it)) >= 1
 
 
 def test_balanced_decomposition_is_sized(amla):

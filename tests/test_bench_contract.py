@@ -81,7 +81,7 @@ def test_default_line_has_the_contract_keys(fake_gpu, monkeypatch):
     par = r["parity"]
     assert par["rows_checked"] > 0 and par["kernel"] == roof["kernel"] and par["variant"] == "add"
     assert isinstance(par["max_out_err"], float) and isinstance(par["max_lse_err"], float) and par["passed"] is False
-    assert {"mul", "add", "add_comp", "mul_t", "add_t", "mul_lazy", "add_lazy", "add_ldexp"} <= set(r["rescale"]["tflops"])
+    assert {"mul", "add", "add_comp", "mul_512", "add_512", "mul_t", "add_t", "mul_lazy", "add_lazy", "add_ldexp"} <= set(r["rescale"]["tflops"])
     assert r["rescale"]["add_over_mul_speedup"] > 0 and r["rescale"]["add_t_over_mul_t_speedup"] > 0
 
 

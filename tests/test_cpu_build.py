@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SHIM = os.path.join(ROOT, "tests", "cpu_build")
 CLANG = os.path.join(os.environ.get("ROCM_LLVM_BIN", "/opt/rocm/lib/llvm/bin"), "clang++")
 MUL, ADD, COMP, LDEXP = 0, 1, 2, 3
-NO_SKIP, LAZY, BALANCED, CAUSAL, TRANSPOSED = 1, 2, 8, 16, 128
+NO_SKIP, LAZY, BALANCED, CAUSAL, ITER512, TRANSPOSED = 1, 2, 8, 16, 32, 128
 FLAGS = ["-std=c++20", "-O0", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
          "-Wno-unknown-attributes", "-Wno-ignored-attributes", "-Wno-psabi"]
 
@@ -86,7 +86,8 @@ KINDS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pyt
          pytest.param((MUL, TRANSPOSED), id="mul_t"), pytest.param((ADD, TRANSPOSED), id="add_t"),
          pytest.param((COMP, TRANSPOSED), id="add_comp_t"),
          pytest.param((MUL, LAZY), id="mul_lazy"), pytest.param((ADD, LAZY), id="add_lazy"),
-         pytest.param((LDEXP, 0), id="add_ldexp"), pytest.param((LDEXP, LAZY), id="add_ldexp_lazy")]
+         pytest.param((LDEXP, 0), id="add_ldexp"), pytest.param((LDEXP, LAZY), id="add_ldexp_lazy"),
+         pytest.param((MUL, ITER512), id="mul_512"), pytest.param((ADD, ITER512), id="add_512")]
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -104,7 +105,7 @@ def _ragged(seed, heads=80):
 
 
 @pytest.mark.parametrize("kind,ns", [((MUL, 0), 1), ((ADD, 0), 3), ((COMP, 0), 2), ((MUL, TRANSPOSED), 1), ((ADD, TRANSPOSED), 3),
-                                     ((ADD, LAZY), 0), ((LDEXP, 0), 2)])
+                                     ((ADD, LAZY), 0), ((LDEXP, 0), 2), ((ADD, ITER512), 3), ((MUL, ITER512), 1)])
 def test_ragged_equal_share_splits(exe, tmp_path, kind, ns):
     case = _ragged(51)
     out, lse, splits = run_cpu(exe, tmp_path, case, kind[0], flags=kind[1], ns=ns)
@@ -115,7 +116,8 @@ def test_ragged_equal_share_splits(exe, tmp_path, kind, ns):
 
 @pytest.mark.parametrize("kind,workers", [((MUL, 0), 3), ((ADD, 0), 8), ((ADD, 0), 41), ((COMP, 0), 1), ((MUL, 0), 5), ((ADD, 0), 0),
                                           ((MUL, TRANSPOSED), 3), ((ADD, TRANSPOSED), 8), ((ADD, LAZY), 41),
-                                          ((COMP, TRANSPOSED), 1), ((MUL, LAZY), 5)])
+                                          ((COMP, TRANSPOSED), 1), ((MUL, LAZY), 5), ((ADD, ITER512), 3),
+                                          ((MUL, ITER512), 8)])
 def test_ragged_balanced_decomposition(exe, tmp_path, kind, workers):
     """Worker counts below, at and above the number of sequences and (41) above the number of blocks:
     pieces that start mid-sequence, workers that cross several sequences, full pieces written in
@@ -132,7 +134,8 @@ def test_ragged_balanced_decomposition(exe, tmp_path, kind, workers):
 @pytest.mark.parametrize("kind", [pytest.param((ADD, LAZY), id="add_lazy"), pytest.param((MUL, LAZY), id="mul_lazy"),
                                   pytest.param((COMP, 0), id="add_comp"), pytest.param((COMP, TRANSPOSED), id="add_comp_t"),
                                   pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"),
-                                  pytest.param((LDEXP, 0), id="add_ldexp")])
+                                  pytest.param((LDEXP, 0), id="add_ldexp"),
+                                  pytest.param((MUL, ITER512), id="mul_512"), pytest.param((ADD, ITER512), id="add_512")])
 def test_wide_logits_move_the_reference(exe, tmp_path, kind):
     """Logit spread of tens of base-2 units over 11 blocks: the lazy kernels take the deferred update
     several times, the compensated one rescales with mantissa terms of both signs."""
@@ -207,7 +210,8 @@ def test_entry_point_rejects_what_it_documents(exe, tmp_path):
     run_cpu(exe, tmp_path, case, COMP, flags=LAZY, expect_status=-2)
     run_cpu(exe, tmp_path, case, 7, expect_status=-2)
     run_cpu(exe, tmp_path, case, ADD, flags=4, expect_status=-2)              # flag bits that are not (or no longer) defined
-    run_cpu(exe, tmp_path, case, ADD, flags=32, expect_status=-2)
+    run_cpu(exe, tmp_path, case, COMP, flags=ITER512, expect_status=-2)       # MUL and ADD of the default family only
+    run_cpu(exe, tmp_path, case, ADD, flags=ITER512 | TRANSPOSED, expect_status=-2)
     run_cpu(exe, tmp_path, case, ADD, flags=64, expect_status=-2)
     run_cpu(exe, tmp_path, case, LDEXP, flags=BALANCED, expect_status=-2)     # equal-share kernels only
 
@@ -232,7 +236,7 @@ def test_random_shapes_lengths_and_decompositions(exe, tmp_path):
     last blocks), rescale variant, flags, split factor or worker count."""
     rng = np.random.default_rng(56)
     kinds = [(MUL, 0), (ADD, 0), (COMP, 0), (ADD, NO_SKIP), (MUL, TRANSPOSED), (ADD, TRANSPOSED), (MUL, LAZY), (ADD, LAZY),
-             (COMP, TRANSPOSED), (ADD, NO_SKIP | TRANSPOSED)]
+             (COMP, TRANSPOSED), (ADD, NO_SKIP | TRANSPOSED)]      # (the 512-key iteration has a sweep of its own below)
     for trial in range(14):
         batch = int(rng.integers(1, 6))
         s_q = int(rng.integers(1, 4))
@@ -372,3 +376,19 @@ def test_row_rescale_kernel(exe, tmp_path, variant):
     dirty.kv_bits[phys, 700 % 64:, :] = 0x7FC0          # NaN in every slot past the end of the last block
     c = run_cpu(exe, tmp_path, dirty, variant)
     assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
+
+
+@pytest.mark.parametrize("variant", [MUL, ADD])
+def test_iteration_of_512_keys(exe, tmp_path, variant):
+    """AMLA_FLAG_ITERATION_512: the reference moves once per eight cache blocks.  Sequences of 24, 9, 8 and 7 blocks
+    (an iteration boundary inside, at and past the end), with a ragged last block, whole and in shares that start
+    inside an iteration; steep logits (sigma 6: rows leave the kept reference by more than 2^8 and must move it
+    at once); the balanced walk and the causal mask."""
+    case = wl.make_case("it512", 81, batch=4, s_q=2, heads=40, seqlens=[1500, 570, 512, 448], spare_frac=0.25)
+    for flags, ns in ((0, 1), (0, 3), (BALANCED, 5), (CAUSAL, 0)):
+        out, lse, _ = run_cpu(exe, tmp_path, case, variant, flags=ITER512 | flags, ns=ns)
+        check(out, lse, case, causal=bool(flags & CAUSAL))
+    steep = wl.make_case("it512_steep", 84, batch=2, s_q=1, heads=16, seqlens=[1100, 640], q_sigma=6.0)
+    for ns in (1, 2):
+        out, lse, _ = run_cpu(exe, tmp_path, steep, variant, flags=ITER512, ns=ns)
+        check(out, lse, steep, peaked=True)

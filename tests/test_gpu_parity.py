@@ -111,10 +111,12 @@ def check(out, lse, want, want_lse, what):
 
 # (rescale variant, flags).  Without a flag the row-rescale kernels run (what a caller gets by default);
 # AMLA_FLAG_TRANSPOSED_ACC selects the kernels that rescale the whole accumulator.
-MUL, ADD, COMP, NO_SKIP, LAZY, TRANSPOSED = 0, 1, 2, 1, 2, 128
+# AMLA_FLAG_ITERATION_512 makes eight cache blocks one iteration of the recurrence (the 512-key block of Section 4.2).
+MUL, ADD, COMP, NO_SKIP, LAZY, ITER512, TRANSPOSED = 0, 1, 2, 1, 2, 32, 128
 VARIANTS = [pytest.param((MUL, 0), id="mul"), pytest.param((ADD, 0), id="add"), pytest.param((COMP, 0), id="add_comp"),
-            pytest.param((MUL, TRANSPOSED), id="mul_t"), pytest.param((ADD, TRANSPOSED), id="add_t")]
-ALL = [(MUL, 0), (ADD, 0), (COMP, 0), (MUL, TRANSPOSED), (ADD, TRANSPOSED)]
+            pytest.param((MUL, TRANSPOSED), id="mul_t"), pytest.param((ADD, TRANSPOSED), id="add_t"),
+            pytest.param((MUL, ITER512), id="mul_512"), pytest.param((ADD, ITER512), id="add_512")]
+ALL = [(MUL, 0), (ADD, 0), (COMP, 0), (MUL, TRANSPOSED), (ADD, TRANSPOSED), (MUL, ITER512), (ADD, ITER512)]
 
 
 def kw_of(v):
@@ -305,12 +307,13 @@ def test_device_exponent_add(env):
 
 def test_random_shapes_lengths_and_decompositions(env):
     """A seeded sweep over what the fixed cases do not enumerate: 40 draws of batch, query tokens, heads, ragged
-    lengths (empty sequences included), logit width, rescale variant, split count, balanced decomposition and
-    causal mask, each against the oracle.  Rows with wide logits are peaked; they take the bound derived for
+    lengths (empty sequences included), logit width, rescale variant, split count, balanced decomposition,
+    causal mask and (MUL / ADD) the 512-key iteration, each against the oracle.  Rows with wide logits are peaked; they take the bound derived for
     peaked rows (half a BF16 step of the output + 6e-3: an FP32 emulation of Algorithm 1 itself reaches 1.5e-2
     on such rows), the others the plain one."""
     torch, orc, amla, wl = env
     rng = np.random.default_rng(20250925)
+    rng_512 = np.random.default_rng(512)          # its own stream: the draws above it stay what they were
     for it in range(40):
         batch, s_q = int(rng.integers(1, 6)), int(rng.integers(1, 5))
         heads = int(rng.choice([16, 40, 64, 80, 128]))
@@ -322,6 +325,8 @@ def test_random_shapes_lengths_and_decompositions(env):
         balanced = bool(rng.integers(0, 2))
         causal = balanced and bool(rng.integers(0, 2))
         flags = (amla.AMLA_FLAG_BALANCED if balanced else 0) | (amla.AMLA_FLAG_CAUSAL if causal else 0)
+        if variant < 2 and rng_512.integers(0, 2):
+            flags |= amla.AMLA_FLAG_ITERATION_512
         case = wl.make_case(f"sweep{it}", 5000 + it, batch=batch, s_q=s_q, heads=heads, seqlens=lens, q_sigma=sigma,
                             spare_frac=0.25)
         what = f"sweep {it}: batch {batch} s_q {s_q} heads {heads} lens {lens} sigma {sigma} variant {variant} flags {flags} splits {ns}"
