@@ -37,6 +37,7 @@ MEASURED_TRAFFIC = {
     # FETCH_SIZE 313918 KiB x 2.000 + WRITE_SIZE 33408 KiB x 1.000 (factors: profiles/copy_probe_512mib.md)
     ("amla_decode_rg_kernel", "add", "mtp_b128", 1): {"read": 643.7e6, "written": 35.0e6},
     ("amla_decode_rg_kernel", "mul", "mtp_b128", 1): {"read": 643.6e6, "written": 35.0e6},
+    ("amla_decode_rg_kernel", "add_512", "mtp_b128", 1): {"read": 643.9e6, "written": 35.0e6},
 }
 
 
