@@ -287,6 +287,41 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   const int first_entry = have_entry ? entry : j0 < j1 ? AMLA_UNIFORM_LOAD_I32(tab, j0) : 0;
   __builtin_amdgcn_sched_barrier(0);
 
+  // A wave none of whose 32 rows exists (fewer than 128 heads x tokens in the last row tile: 16 heads of a
+  // tensor-parallel shard leave three of the four waves without a row) takes no part in the arithmetic.  It
+  // still owes the workgroup its quarter of every tile's loads, the clearing of slots past the sequence's end
+  // and every barrier the working waves pass, in the same order; its matrix and vector pipes stay idle, which
+  // on a chip that runs this loop at its power limit is clock for the waves that work.
+  if (tile * kRowsPerWg + wave * 32 >= p.rows) {   // wave-uniform
+    const int first_phys = min(max(__builtin_amdgcn_readfirstlane(first_entry), 0), p.num_blocks - 1);
+    if (!first_piece) __syncthreads();
+    const TileLoadLane tl = tile_load_lane(wave, lane);
+    if (j0 < j1) {
+      const uint8_t* first = kvb + (size_t)first_phys * blk_bytes;
+      static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(first, smem, wave, tl); });
+    }
+    for (int j = j0; j < j1; ++j) {
+      LDS_PTR(uint8_t) buf = smem + ((j - j0) & 1) * kRgTileBytes;
+      LDS_PTR(uint8_t) nxt = smem + ((j + 1 - j0) & 1) * kRgTileBytes;
+      AMLA_WAIT_TILE_LOADS();
+      __syncthreads();
+      const int rem = kv_len - j * kBlock;
+      if (rem < kBlock) {
+        for (int c = (int)threadIdx.x; c < (kBlock - rem) * (kRowBytes / 16); c += kThreads) {
+          const int r = rem + c / (kRowBytes / 16), cc = c % (kRowBytes / 16);
+          LDS_PTR(uint8_t) at = cc < 64 ? buf + r * kRgRowA + cc * 16 : buf + kRgRegionA + r * kRgRowB + (cc - 64) * 16;
+          *(LDS_PTR(i32x4))at = i32x4{0, 0, 0, 0};
+        }
+        __syncthreads();
+      }
+      if (j + 1 < j1) {
+        const uint8_t* next_block = kvb + (size_t)phys_of(j + 1) * blk_bytes;
+        static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(next_block, nxt, wave, tl); });
+      }
+    }
+    return;
+  }
+
   // Q fragment: B operand of S^T = K Q^T.  Lane holds q[row][16 ks + 8 h .. + 7].  Rows past the end of the
   // sequence's row range read row 0 (valid memory); their results are never stored.
   bf16x8 qf[kDqk / 16];
