@@ -13,7 +13,8 @@ Algorithm 2 (AMLA_RESCALE_ADD) on the row-rescale kernels.  One JSON line is pri
   cpu_baseline  the oracle timed on the host cores on a bounded sample
   rescale       every rescale variant of both kernel families timed side by side, and the ADD / MUL
                 ratio as interleaved medians
-  per_config    the other measured configurations (HBM-bound s_q = 1, ragged, long context)
+  per_config    the other measured configurations (HBM-bound s_q = 1, ragged, long context) and a
+                low-head-count batch (16 heads: achieved HBM GB/s)
 """
 from __future__ import annotations
 
@@ -344,9 +345,9 @@ def main():
         per_config = {}
         del prob
         torch.cuda.empty_cache()
-        for idx in (1, 3, 4):
+        for idx in (1, 3, 4, "low_heads"):
             try:
-                c = wl.make_config(idx)
+                c = wl.make_low_head_case() if idx == "low_heads" else wl.make_config(idx)
                 pr = Problem(torch, amla, c)
                 if idx == 1:
                     pr.second_pool()      # 302 MB pool: alternate two copies so that it comes from HBM each launch
@@ -376,7 +377,8 @@ def main():
                         "frac_of_binding_roof": max(mfma_t, hbm_t) / (ms * 1e-3),
                         "frac_of_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
                 entry["add_over_mul_speedup"] = median(times[("mul", False)]) / median(times[("add", False)])
-                per_config[f"configs[{idx}] {c.name}"] = entry
+                per_config[f"configs[{idx}] {c.name}" if idx != "low_heads" else
+                           f"{c.name} (one GPU's 16 heads of an eight-way tensor-parallel group)"] = entry
                 del pr
                 torch.cuda.empty_cache()
             except Exception as e:  # noqa: BLE001

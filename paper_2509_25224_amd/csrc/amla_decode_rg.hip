@@ -288,18 +288,26 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   __builtin_amdgcn_sched_barrier(0);
 
   // A wave none of whose 32 rows exists (fewer than 128 heads x tokens in the last row tile: 16 heads of a
-  // tensor-parallel shard leave three of the four waves without a row) takes no part in the arithmetic.  It
-  // still owes the workgroup its quarter of every tile's loads, the clearing of slots past the sequence's end
-  // and every barrier the working waves pass, in the same order; its matrix and vector pipes stay idle, which
-  // on a chip that runs this loop at its power limit is clock for the waves that work.
-  if (tile * kRowsPerWg + wave * 32 >= p.rows) {   // wave-uniform
+  // tensor-parallel shard leave three of the four waves without a row) takes no part in the arithmetic.  Such
+  // waves fetch the tiles instead, all 72 loads of each dealt among them, so the waves that work issue none;
+  // they also clear the slots past the sequence's end and pass every barrier the working waves pass, in the
+  // same order.  Their matrix and vector pipes stay idle, which on a chip that runs this loop at its power
+  // limit is clock for the waves that work.
+  const int working_waves = min(kThreads / 64, (p.rows - tile * kRowsPerWg + 31) / 32);   // workgroup-uniform, >= 1
+  const bool fetch_own_share = working_waves == kThreads / 64;
+  if (wave >= working_waves) {   // wave-uniform
     const int first_phys = min(max(__builtin_amdgcn_readfirstlane(first_entry), 0), p.num_blocks - 1);
     if (!first_piece) __syncthreads();
-    const TileLoadLane tl = tile_load_lane(wave, lane);
-    if (j0 < j1) {
-      const uint8_t* first = kvb + (size_t)first_phys * blk_bytes;
-      static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(first, smem, wave, tl); });
-    }
+    const TileLoadLane tl_even = tile_load_lane(0, lane), tl_odd = tile_load_lane(1, lane);
+    const int fetchers = kThreads / 64 - working_waves, me = wave - working_waves;
+    auto fetch_tile = [&](const uint8_t* block, LDS_PTR(uint8_t) to) {
+      // load n of wave w's share is slot 4 n + w; a fetching wave takes the slots congruent to its number
+      static_for<kRgLoadsPerWave>([&](auto k) {
+        for (int w = 0; w < kThreads / 64; ++w)
+          if ((4 * k.value + w) % fetchers == me) issue_tile_load<k.value>(block, to, w, (w & 1) ? tl_odd : tl_even);
+      });
+    };
+    if (j0 < j1) fetch_tile(kvb + (size_t)first_phys * blk_bytes, smem);
     for (int j = j0; j < j1; ++j) {
       LDS_PTR(uint8_t) buf = smem + ((j - j0) & 1) * kRgTileBytes;
       LDS_PTR(uint8_t) nxt = smem + ((j + 1 - j0) & 1) * kRgTileBytes;
@@ -314,10 +322,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
         }
         __syncthreads();
       }
-      if (j + 1 < j1) {
-        const uint8_t* next_block = kvb + (size_t)phys_of(j + 1) * blk_bytes;
-        static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(next_block, nxt, wave, tl); });
-      }
+      if (j + 1 < j1) fetch_tile(kvb + (size_t)phys_of(j + 1) * blk_bytes, nxt);
     }
     return;
   }
@@ -334,7 +339,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
   // the previous piece's last tile may still be read by a slower wave
   if (!first_piece) __syncthreads();
   const TileLoadLane tl = tile_load_lane(wave, lane);
-  if (j0 < j1) {
+  if (j0 < j1 && fetch_own_share) {
     const uint8_t* first = kvb + (size_t)first_phys * blk_bytes;
     static_for<kRgLoadsPerWave>([&](auto k) { issue_tile_load<k.value>(first, smem, wave, tl); });
   }
@@ -652,7 +657,7 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
         __builtin_amdgcn_sched_barrier(0);
       });
     };
-    if (more)
+    if (more && fetch_own_share)
       phase_a(std::true_type{});
     else
       phase_a(std::false_type{});

@@ -167,6 +167,13 @@ def make_config(index: int) -> DecodeCase:
     raise IndexError(index)
 
 
+def make_low_head_case(heads: int = 16, batch: int = 256, kv_len: int = 4096, seed: int = 7) -> DecodeCase:
+    """A low-head-count decode batch: what one GPU of a tensor-parallel group sees of the 128-head model (16
+    heads at eight-way sharding), s_q = 1, every sequence kv_len long, random block table.  With 16 rows per
+    cached row the shape has 30 FLOP per byte and is bound by HBM."""
+    return make_case(f"low_heads_h{heads}_b{batch}", seed, batch, 1, heads, [kv_len] * batch)
+
+
 def make_table5_case(s_q: int, s_k: int, seed: int = 5) -> DecodeCase:
     """A shape of the paper's performance table (Section 5.2, Table 5): batch 96, 128 query heads on
     one shared KV head, BF16, every sequence s_k long, s_q in {1, 2}, cache laid out contiguously

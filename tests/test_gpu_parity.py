@@ -379,3 +379,24 @@ def test_full_size_configs_all_rows(env, index):
         assert worst[v][1] <= LSE_TOL
         assert big > 0 or worst[v][0] <= OUT_TOL
     print(f"  elements with |exact| >= 4 (bf16 half-ulp 1.56e-2 > 1e-2): {big}", flush=True)
+
+
+def test_low_head_count_batch(env):
+    """The low-head-count batch that bench.py times (16 heads: three of a workgroup's four waves have no query
+    row and fetch the tiles for the one that works), in its launch configuration, every row of 24 sequences
+    spread over the batch against the oracle; also 40 and 80 rows per sequence (two and three working waves)."""
+    torch, orc, amla, wl = env
+    for case, picks in ((wl.make_low_head_case(), list(range(0, 256, 11))),
+                        (wl.make_low_head_case(heads=40, batch=48, kv_len=3000, seed=8), list(range(0, 48, 5))),
+                        (wl.make_low_head_case(heads=80, batch=48, kv_len=2500, seed=9), list(range(0, 48, 5)))):
+        print(f"{case.name}: B={case.batch} H={case.heads} sum kv_len={case.total_kv}", flush=True)
+        dev = to_dev(torch, case)
+        results = {v: run_gpu(torch, amla, case, dev, **kw_of(v)) for v in ((MUL, 0), (ADD, 0), (ADD, ITER512))}
+        for b in picks:
+            want, want_lse = orc.decode(case.q_bits, case.kv_bits, case.block_table, case.seqlens,
+                                        case.softmax_scale, seq_ids=[b])
+            for v, (out, lse) in results.items():
+                assert np.all(np.abs(out[b] - want[b]) <= out_tolerance(want[b])), (case.name, b, v)
+                assert np.abs(lse[b] - want_lse[b]).max() <= LSE_TOL, (case.name, b, v)
+        del dev
+        torch.cuda.empty_cache()
