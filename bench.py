@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--table5", default=None, metavar="SQ,SK",
                     help="use a shape of the paper's performance table instead of --config: batch 96, 128 heads, "
                          "s_q SQ, every sequence SK keys, contiguous cache; 'all' times the table's 12 shapes")
+    ap.add_argument("--low-heads", type=int, default=0, metavar="H",
+                    help="use the low-head-count batch instead of --config: 256 sequences, s_q 1, H heads (16 = one GPU "
+                         "of an eight-way tensor-parallel group), 4096 keys each")
     ap.add_argument("--splits", type=int, default=0, help="split-KV factor, 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (and with it the parity block)")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the measured-MFMA-peak probe")
@@ -232,6 +235,9 @@ def main():
         sq, sk = (int(x) for x in args.table5.split(","))
         case = wl.make_table5_case(sq, sk)
         workload_tag = f"paper Table 5 shape {case.name}"
+    elif args.low_heads:
+        case = wl.make_low_head_case(heads=args.low_heads)
+        workload_tag = f"low-head-count batch {case.name}"
     else:
         case = wl.make_config(args.config)
         workload_tag = f"configs[{args.config}] {case.name}"
@@ -341,7 +347,7 @@ def main():
         except Exception as e:  # noqa: BLE001
             notes.append(f"oracle leg failed: {e!r}")
 
-    if not args.no_per_config and not args.table5 and args.config == 2:
+    if not args.no_per_config and not args.table5 and not args.low_heads and args.config == 2:
         per_config = {}
         del prob
         torch.cuda.empty_cache()
