@@ -13,6 +13,9 @@ What it holds
                        two-pass safe softmax, plus lse = max + ln(sum).  The paper's
                        "Golden" (Section 5.1) in fp64 instead of fp32.  Options outside the paper:
                        a causal mask among the s_q tokens and per-sequence query counts.
+                       (`amla_oracle_decode.c` beside this file is the same definition as plain C loops
+                       with host pointers, in the argument order of the library's entry point; it is
+                       pinned on its own and against this function by tests/test_oracle_c.py.)
 * `flash_attention`    Algorithm 1 (FlashAttention / "Base") written step by step in fp64.
 * `amla_recurrence`    Eq. (4): the AMLA transform with n_i = round(-m_i / ln 2) and
                        r_i = exp(-n_i ln 2 - m_i), in fp64.
