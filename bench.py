@@ -361,7 +361,7 @@ def main():
                 ab_ = acc.algorithmic_bytes(c.heads, c.s_q, c.batch, c.total_kv)
                 entry = {"workload": f"batch {c.batch}, s_q {c.s_q}, {c.heads} heads, sum kv_len {c.total_kv}"
                                      + (", two pool copies read alternately" if idx == 1 else "")}
-                legs = [("add", False), ("mul", False), ("add_512", False)] + ([("add", True), ("mul", True)] if idx == 3 else [])
+                legs = [("add", False), ("mul", False), ("add_512", False)] + ([("add", True), ("mul", True), ("add_512", True)] if idx == 3 else [])
                 times = {}
                 # the first launches on a fresh problem run slow whatever the variant (clocks and address
                 # translation settle): one untimed pass over every leg, then interleaved passes in alternating order
