@@ -203,7 +203,10 @@ size_t amla_static_workspace_limit(void);
 /*
  * amla_workspace_bytes -- bytes of desc->workspace that amla_decode needs for this desc
  * (0 when the effective split factor is 1).  Only shape fields, num_splits and flags are
- * read.  Returns 0 for a NULL or unsupported desc.
+ * read.  Returns 0 for a NULL or unsupported desc.  The figure is 512 FP32 values and a log-sum-exp
+ * per partial row whichever kernels run; the default kernels store their partial rows as FP16 (the
+ * rows are normalised, so of the value rows' magnitude, and the merge weights them in FP32) and
+ * leave the rest of the range untouched.
  */
 size_t amla_workspace_bytes(const amla_desc* desc);
 

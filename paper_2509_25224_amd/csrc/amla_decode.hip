@@ -235,11 +235,14 @@ int enqueue_decode(const void* q, const void* kv_cache, const int32_t* block_tab
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds_bytes, stream, p);
   if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   if (balanced) {
-    hipLaunchKernelGGL(amla_combine_balanced_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o,
+    // (the row-rescale kernels leave their partial rows in FP16, the transposed-accumulator kernels in FP32)
+    const auto combine = uses_transposed(desc) ? amla_combine_balanced_kernel<false> : amla_combine_balanced_kernel<true>;
+    hipLaunchKernelGGL(combine, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o,
                        p.part_lse, p.seqlens, p.out, p.lse, p.batch, p.rows, ns, p.max_blocks);
     if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   } else if (ns > 1) {
-    hipLaunchKernelGGL(amla_combine_kernel, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
+    const auto combine = uses_transposed(desc) ? amla_combine_kernel<false> : amla_combine_kernel<true>;
+    hipLaunchKernelGGL(combine, dim3((unsigned)n_rows), dim3(128), 0, stream, p.part_o, p.part_lse,
                        p.out, p.lse, (int)n_rows, ns);
     if (hipGetLastError() != hipSuccess) return AMLA_ERR_LAUNCH;
   }

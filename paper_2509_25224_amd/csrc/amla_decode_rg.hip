@@ -757,9 +757,15 @@ __device__ __forceinline__ void decode_piece(const DecodeParams& p, LDS_PTR(uint
 #pragma unroll
         for (int dt = 0; dt < kDv / 32; ++dt) orow[32 * dt] = (uint16_t)pack_bf16(o[dt], 0.f);
       } else {
-        float* orow = p.part_o + (part_row0 + row_i) * kDv + l32;
+        // a partial row goes out in FP16 (the values are normalised, so of the value rows' magnitude; the merge
+        // weights them in FP32), the lane's 16 columns side by side at position 16 l32: two 16-byte stores
+        // instead of sixteen, and half the bytes that the combine kernel reads back
+        unsigned hw[kDv / 64];
 #pragma unroll
-        for (int dt = 0; dt < kDv / 32; ++dt) orow[32 * dt] = o[dt];
+        for (int k = 0; k < kDv / 64; ++k) hw[k] = pack_f16(o[2 * k], o[2 * k + 1]);
+        i32x4* prow = reinterpret_cast<i32x4*>(reinterpret_cast<uint16_t*>(p.part_o) + (part_row0 + row_i) * kDv + 16 * l32);
+        prow[0] = i32x4{(int)hw[0], (int)hw[1], (int)hw[2], (int)hw[3]};
+        prow[1] = i32x4{(int)hw[4], (int)hw[5], (int)hw[6], (int)hw[7]};
       }
     }
   });

@@ -105,6 +105,15 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned, b);
 }
 
+// two FP32 values as a pair of FP16 (round to nearest even), lo in the low half
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ unsigned pack_f16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  f16x2 b = __builtin_convertvector(v, f16x2);
+  return __builtin_bit_cast(unsigned, b);
+}
+
 // Issue this wave's share (one of NWAVES) of the direct-to-LDS loads of one 64 x 576 bf16 block.
 // LDS destination of load i is the 1 KiB range [i * 1024, (i + 1) * 1024) of the tile buffer,
 // lane l landing at + 16 l; chunk c = 64 i + l of the padded tile is row c / 73, column chunk

@@ -17,7 +17,8 @@ SRC = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "amla_decode.hip")
 SRC_ROW = os.path.join(ROOT, "paper_2509_25224_amd", "csrc", "amla_decode_rg.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # strict MUL / ADD decode kernels, the split combine kernel, the exponent-add test kernel
-PINNED = ("amla_decode_kernelILi0ELb0E", "amla_decode_kernelILi1ELb0E", "amla_combine_kernelE", "amla_exponent_add_kernelE")
+PINNED = ("amla_decode_kernelILi0ELb0E", "amla_decode_kernelILi1ELb0E", "amla_combine_kernelILb0EE", "amla_combine_kernelILb1EE",
+          "amla_exponent_add_kernelE")
 
 
 def device_assembly(tmp, src=SRC, name="device.s"):
