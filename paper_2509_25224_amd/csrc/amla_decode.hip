@@ -209,7 +209,8 @@ int enqueue_decode(const void* q, const void* kv_cache, const int32_t* block_tab
 
   hipStream_t stream = static_cast<hipStream_t>(desc->stream);
   const long long streams_pad = ((long long)p.n_streams + 7) / 8 * 8;
-  const long long grid = streams_pad * p.n_tiles;
+  // (the equal-share row-rescale kernels deal sequences, not streams, over the 8 XCDs: the batch is padded)
+  const long long grid = (!uses_transposed(desc) && !balanced ? ((long long)desc->batch + 7) / 8 * 8 * ns : streams_pad) * p.n_tiles;
   if (grid > 0x7fffffffll) return AMLA_ERR_UNSUPPORTED;
   const bool lazy = (desc->flags & AMLA_FLAG_LAZY_RESCALE) != 0;
   AmlaDecodeKernel kern = nullptr;

@@ -781,25 +781,30 @@ void amla_decode_rg_kernel(const DecodeParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   acc_claim();
 
-  // Workgroup -> (kv stream, row tile).  Consecutive workgroup ids go round-robin over the 8 XCDs; the row
-  // tiles of one (sequence, split) get ids that differ by 8 so that they land on the same XCD next to each
-  // other and share the KV blocks in that XCD's L2.
+  // Workgroup -> (sequence, split, row tile).  Consecutive workgroup ids go round-robin over the 8 XCDs.  The row
+  // tiles of one (sequence, split) get ids that differ by 8, so that they land on the same XCD next to each other
+  // and share the KV blocks in that XCD's L2; so do the splits of one sequence, which all read the same query
+  // rows (sequence = 8 * (group / splits) + xcd, split = group % splits: with four shares the query rows were
+  // otherwise fetched from HBM four times, once per XCD).
   const int xcd = blockIdx.x & 7;
   const int slot = blockIdx.x >> 3;
-  const int stream = (slot / p.n_tiles) * 8 + xcd;
+  const int group = slot / p.n_tiles;
   const int tile = slot % p.n_tiles;
-  if (stream >= p.n_streams) return;
-  const int b = stream / p.n_splits;
-  const int split = stream - b * p.n_splits;
+  const int b = (group / p.n_splits) * 8 + xcd;
+  const int split = group % p.n_splits;
+  if (b >= p.batch) return;
 
-  // A sequence's first share starts at block 0 whatever its length: its table entry is asked for together
-  // with the length instead of after it (one memory round trip less before the first tile can be requested).
-  const bool have_entry = split == 0;
-  const int entry = have_entry ? AMLA_UNIFORM_LOAD_I32(p.table + (size_t)b * p.max_blocks, 0) : 0;
+  // The first 64 entries of the sequence's block-table row are asked for together with its length, one per lane:
+  // a share that starts within them (any share of a sequence of up to 4096 keys, the first shares of a longer
+  // one) then has its first entry without a second memory round trip before the first tile can be requested.
+  const int32_t* table_row = p.table + (size_t)b * p.max_blocks;
+  const int lane_entry = table_row[min(lane, p.max_blocks - 1)];
   const int kv_len = plan_len(__builtin_amdgcn_readfirstlane(p.seqlens[b]), p.max_blocks, kBlock);
   const int nb = plan_blocks_of(kv_len, kBlock);
   const int j0 = (int)(((long long)split * nb) / p.n_splits);
   const int j1 = (int)(((long long)(split + 1) * nb) / p.n_splits);
+  const bool have_entry = j0 < 64;
+  const int entry = __builtin_amdgcn_readlane(lane_entry, j0 & 63);
   decode_piece<VARIANT, false, ITER512>(p, smem, lane, wave, b, kv_len, j0, j1, tile, p.n_splits == 1,
                                (size_t)split * p.batch * p.rows + (size_t)b * p.rows, 0, 0, true, have_entry, entry);
 }
