@@ -60,3 +60,24 @@ def test_rejections():
     out = ctypes.c_int32(0)
     assert amla.lib.amla_preload_rotation(None, None, 2, ctypes.byref(out), ctypes.byref(out),
                                           ctypes.byref(out)) == amla.AMLA_ERR_NULL_ARG
+
+
+def test_the_block_loop_is_the_cycle_the_rule_picks_for_its_measured_stages():
+    """The decode kernels' block loop works a 64-key block as two 32-key sub-blocks in the order
+    C1(0), C1(1) | V1(0), C2(0) | V1(1), C2(1): seen from one sub-block, its vector stage runs beside the matrix
+    stage that follows its own C1, and its C2 comes after that -- the Cycle [C2, C1] with V1 under it, in which
+    the C1 -> V1 dependency is the one that crosses Cycles (Section 4.1).  With the stage lengths measured on
+    the MI355X (cycles per sub-block and wave: C1 36 MFMAs at 32.6 - 37.4, C2 32 MFMAs at 32.6, V1 about 600 of
+    vector issue) the rotation rule returns exactly that Cycle, the oracle's timeline admits it, and the vector
+    work fits under the matrix work (the theorem's matrix-bound case)."""
+    for c1 in (36 * 33, 36 * 37):                 # the first product's MFMAs issue between 32.6 and 37.4 cycles apart
+        cube, vec = [c1, 32 * 33], [600, 0]
+        assert sum(vec) <= sum(cube)
+        first, external, count = amla.amla_preload_rotation(cube, vec)
+        assert (first, external, count) == (2, 1, 2)
+        assert po.cube_order(2, first) == [2, 1]                 # the Cycle starts with C2 and ends with C1
+        assert first in po.admissible_rotations(cube, vec)
+    # were the vector stage longer than the matrix stage it hides under plus the slack of the Cycle, no rotation
+    # could hide it: the rule refuses the vector-bound case
+    with pytest.raises(amla.AmlaError):
+        amla.amla_preload_rotation([36 * 33, 32 * 33], [2300, 0])
