@@ -400,3 +400,24 @@ def test_low_head_count_batch(env):
                 assert np.abs(lse[b] - want_lse[b]).max() <= LSE_TOL, (case.name, b, v)
         del dev
         torch.cuda.empty_cache()
+
+
+def test_repeated_launches_give_identical_bits(env):
+    """The tile buffers are shared by waves that only meet at barriers (with fewer than 128 rows some waves fetch
+    and others compute): a tile read early or refilled late would show as launches that differ.  Ragged batches
+    with one, two, three and four working waves, splits and the balanced walk, twenty launches each."""
+    torch, orc, amla, wl = env
+    for heads, s_q, batch, ns, flags in ((16, 1, 96, 0, 0), (40, 1, 64, 0, 0), (80, 1, 48, 3, ITER512),
+                                         (24, 3, 40, 0, amla.AMLA_FLAG_BALANCED), (128, 2, 32, 0, 0)):
+        rng = np.random.default_rng(heads + s_q)
+        case = wl.make_case("again", 3000 + heads, batch, s_q, heads, [int(x) for x in rng.integers(1, 4000, batch)],
+                            spare_frac=0.1)
+        q, kv, tab, lens = to_dev(torch, case)
+        first = None
+        for launch in range(20):
+            out, lse = amla.amla_decode(q, kv, tab, lens, case.softmax_scale, variant=ADD, flags=flags, num_splits=ns)
+            torch.cuda.synchronize()
+            bits = (out.view(torch.int16).cpu().numpy(), lse.cpu().numpy())
+            if first is None:
+                first = bits
+            assert np.array_equal(bits[0], first[0]) and np.array_equal(bits[1], first[1]), (heads, s_q, launch)
